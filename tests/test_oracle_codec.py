@@ -1,0 +1,226 @@
+"""Pins for the oracle's encoder and decoder (no GPU)."""
+import itertools
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import approxifer_oracle as orc
+
+
+def _berrut_eval_scalar(z, nodes, signs, values):
+    """Direct evaluation of eq. (1)-(2) for one point with python floats, term by
+    term, written independently of the oracle's vectorised routine."""
+    num = 0.0
+    den = 0.0
+    for xi, si, fi in zip(nodes, signs, values):
+        t = si / (z - xi)
+        num += t * fi
+        den += t
+    return num / den
+
+
+# ----------------------------------------------------------------------------
+# encoder
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("K,W", [(4, 6), (12, 20)])
+def test_encode_constant_queries_reproduce(K, W):
+    # the basis functions sum to one, so identical queries give identical coded queries
+    alpha, beta = orc.chebyshev_nodes(K, W)
+    v = np.random.default_rng(0).uniform(0, 1, 33)
+    X = np.broadcast_to(v, (2, K, 33)).copy()
+    coded = orc.encode(X, alpha, beta)
+    assert coded.shape == (2, W, 33)
+    assert np.max(np.abs(coded - v)) < 1e-13
+
+
+def test_encode_commutes_with_affine_model():
+    # f(x) = Mx + b: f(u(beta_i)) = sum_j l_j(beta_i) f(X_j) because sum_j l_j = 1
+    rng = np.random.default_rng(1)
+    K, W, D, C = 5, 9, 40, 7
+    alpha, beta = orc.chebyshev_nodes(K, W)
+    X = rng.standard_normal((3, K, D))
+    M, b = rng.standard_normal((D, C)), rng.standard_normal(C)
+    lhs = orc.encode(X, alpha, beta) @ M + b
+    rhs = orc.encode(X @ M + b, alpha, beta)
+    assert np.allclose(lhs, rhs, atol=1e-11)
+
+
+def test_encode_is_linear_and_elementwise_in_D():
+    rng = np.random.default_rng(2)
+    K, W, D = 4, 6, 10
+    alpha, beta = orc.chebyshev_nodes(K, W)
+    X1, X2 = rng.standard_normal((2, 1, K, D))
+    assert np.allclose(orc.encode(2 * X1 - 3 * X2, alpha, beta),
+                       2 * orc.encode(X1, alpha, beta) - 3 * orc.encode(X2, alpha, beta), atol=1e-12)
+    # each feature is coded on its own: coding column d alone gives the same column
+    full = orc.encode(X1, alpha, beta)
+    for d in (0, 7):
+        assert np.allclose(orc.encode(X1[:, :, d:d + 1], alpha, beta)[..., 0], full[..., d], rtol=0, atol=1e-14)
+
+
+def test_encode_matches_scalar_definition():
+    rng = np.random.default_rng(3)
+    K, W, D = 6, 10, 3
+    alpha, beta = orc.chebyshev_nodes(K, W)
+    X = rng.standard_normal((2, K, D)).astype(np.float32)
+    coded = orc.encode(X, alpha, beta)
+    signs = [(-1) ** j for j in range(K)]
+    for g, i, d in itertools.product(range(2), range(W), range(D)):
+        want = _berrut_eval_scalar(float(beta[i]), [float(a) for a in alpha], signs, [float(v) for v in X[g, :, d]])
+        assert coded[g, i, d] == pytest.approx(want, rel=1e-12, abs=1e-13)
+
+
+def test_encode_through_query_when_nodes_coincide():
+    # K=2, W=5: beta_1 = alpha_0 and beta_3 = alpha_1, the coded query IS the query
+    alpha, beta = orc.chebyshev_nodes(2, 5)
+    beta = beta.copy()
+    beta[1], beta[3] = alpha[0], alpha[1]           # make the coincidence exact in floating point
+    X = np.random.default_rng(4).standard_normal((1, 2, 8))
+    coded = orc.encode(X, alpha, beta)
+    assert np.array_equal(coded[0, 1], X[0, 0]) and np.array_equal(coded[0, 3], X[0, 1])
+
+
+def test_k2_w3_coded_queries_closed_form():
+    # K=2, S=1 (the paper's example figure): coded queries are the line through X_0, X_1 at z = 1, 0, -1
+    alpha, beta = orc.chebyshev_nodes(2, 3)
+    X = np.array([[[2.0, -1.0], [4.0, 3.0]]])
+    coded = orc.encode(X, alpha, beta)[0]
+    r = math.sqrt(2.0)
+    mid = (X[0, 0] + X[0, 1]) / 2
+    half = (X[0, 0] - X[0, 1]) / 2
+    assert np.allclose(coded[0], mid + r * half, atol=1e-14)
+    assert np.allclose(coded[1], mid, atol=1e-14)
+    assert np.allclose(coded[2], mid - r * half, atol=1e-14)
+
+
+# ----------------------------------------------------------------------------
+# decoder
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("mode", [0, 1])
+def test_decode_without_stragglers_is_direct_berrut(mode):
+    rng = np.random.default_rng(5)
+    K, W, C = 4, 7, 5
+    alpha, beta = orc.chebyshev_nodes(K, W)
+    Y = rng.standard_normal((2, W, C)).astype(np.float32)
+    out, st = orc.decode(Y, np.ones((2, W), np.uint8), alpha, beta, 0, mode)
+    assert np.all(st == 0)
+    signs = [(-1) ** i for i in range(W)]
+    for g, j, c in itertools.product(range(2), range(K), range(C)):
+        want = _berrut_eval_scalar(float(alpha[j]), [float(b) for b in beta], signs, [float(v) for v in Y[g, :, c]])
+        assert out[g, j, c] == pytest.approx(want, rel=1e-12, abs=1e-13)
+
+
+def test_decode_sign_modes_definition_with_stragglers():
+    # W=6, workers 1 and 4 missing: F = {0,2,3,5}
+    K, W = 3, 6
+    alpha, beta = orc.chebyshev_nodes(K, W)
+    F = [0, 2, 3, 5]
+    Y = np.random.default_rng(6).standard_normal((1, W, 2))
+    Y[0, [1, 4], :] = np.nan                        # never read
+    mask = np.zeros((1, W), np.uint8)
+    mask[0, F] = 1
+    for mode, signs in ((0, [1, 1, -1, -1]), (1, [1, -1, 1, -1])):
+        out, st = orc.decode(Y, mask, alpha, beta, 2, mode)
+        assert st[0] == 0 and np.all(np.isfinite(out))
+        for j, c in itertools.product(range(K), range(2)):
+            want = _berrut_eval_scalar(float(alpha[j]), [float(beta[i]) for i in F], signs, [float(Y[0, i, c]) for i in F])
+            assert out[0, j, c] == pytest.approx(want, rel=1e-12)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_decode_constants_and_interpolation_at_worker_nodes(mode):
+    rng = np.random.default_rng(8)
+    K, W, S, C = 4, 8, 3, 6
+    _, beta = orc.chebyshev_nodes(K, W)
+    mask = np.zeros((1, W), np.uint8)
+    F = [0, 2, 3, 6, 7]
+    mask[0, F] = 1
+    # constants reproduce
+    alpha = rng.uniform(-0.9, 0.9, K)
+    Yc = np.broadcast_to(rng.standard_normal(C), (1, W, C)).copy()
+    out, _ = orc.decode(Yc, mask, alpha, beta, S, mode)
+    assert np.allclose(out, Yc[:, :K], atol=1e-12)
+    # r passes through the returned predictions: evaluate at the surviving worker nodes themselves
+    Y = rng.standard_normal((1, W, C))
+    out, _ = orc.decode(Y, mask, beta[F][:K], beta, S, mode)
+    assert np.array_equal(out[0], Y[0, F[:K]])
+
+
+def test_k2_w3_affine_model_recovery():
+    # K=2, W=3, f affine.  f(u(z)) is then a straight line in z, sampled at z = 1, 0, -1.
+    # Rank signs (mode 1) on two surviving nodes is linear interpolation: exact for every mask.
+    # Worker-index signs (mode 0) equal rank signs for F={0,1} and F={1,2}; for F={0,2} the two
+    # terms carry the same sign and r(z) = [(z+1)Y_0 + (z-1)Y_2]/(2z), which is not the line.
+    alpha, beta = orc.chebyshev_nodes(2, 3)
+    rng = np.random.default_rng(9)
+    X = rng.standard_normal((1, 2, 6))
+    M, b = rng.standard_normal((6, 3)), rng.standard_normal(3)
+    truth = X @ M + b
+    Y = orc.encode(X, alpha, beta) @ M + b
+    for F in ([0, 1], [1, 2], [0, 2]):
+        mask = np.zeros((1, 3), np.uint8)
+        mask[0, F] = 1
+        out1, _ = orc.decode(Y, mask, alpha, beta, 1, 1)
+        assert np.allclose(out1, truth, atol=1e-12)
+        out0, _ = orc.decode(Y, mask, alpha, beta, 1, 0)
+        if F == [0, 2]:
+            a = math.sqrt(2) / 2
+            for j, z in enumerate((a, -a)):
+                want = ((z + 1) * Y[0, 0] + (z - 1) * Y[0, 2]) / (2 * z)
+                assert np.allclose(out0[0, j], want, atol=1e-12)
+            assert not np.allclose(out0, truth, atol=1e-3)
+        else:
+            assert np.allclose(out0, truth, atol=1e-12)
+
+
+def test_k2_w3_mode_weights_exact():
+    # worked example: nodes (1, 0, -1), F = {0, 2}, z = sqrt(2)/2
+    alpha, beta = orc.chebyshev_nodes(2, 3)
+    w0 = orc.decode_weights(alpha, beta, [0, 2], 0)[0]
+    w1 = orc.decode_weights(alpha, beta, [0, 2], 1)[0]
+    a = math.sqrt(2) / 2
+    assert np.allclose(w0, [(a + 1) / (2 * a), (a - 1) / (2 * a)], atol=1e-15)    # (1.2071, -0.2071)
+    assert np.allclose(w1, [(a + 1) / 2, (1 - a) / 2], atol=1e-15)                # (0.8536, 0.1464)
+
+
+def test_decode_weights_exact_rational():
+    # rational nodes: compare with Fractions, both sign modes, with a gap in F
+    beta = [Fraction(1), Fraction(1, 2), Fraction(-1, 4), Fraction(-3, 4), Fraction(-1)]
+    alpha = [Fraction(2, 3), Fraction(-1, 3)]
+    F = [0, 1, 3, 4]
+    for mode in (0, 1):
+        got = orc.decode_weights([float(a) for a in alpha], [float(b) for b in beta], F, mode)
+        for j, z in enumerate(alpha):
+            t = []
+            for r, i in enumerate(F):
+                sign = (-1) ** (i if mode == 0 else r)
+                t.append(Fraction(sign) / (z - beta[i]))
+            tot = sum(t)
+            assert np.allclose(got[j], [float(v / tot) for v in t], rtol=1e-13, atol=1e-15)
+
+
+def test_decode_status_on_wrong_popcount():
+    K, W, S = 2, 4, 1
+    alpha, beta = orc.chebyshev_nodes(K, W)
+    Y = np.ones((3, W, 2))
+    mask = np.array([[1, 1, 1, 0], [1, 1, 0, 0], [1, 1, 1, 1]], np.uint8)
+    out, st = orc.decode(Y, mask, alpha, beta, S)
+    assert list(st) == [0, 1, 1]
+    assert np.all(out[1:] == 0) and np.allclose(out[0], 1.0)
+
+
+def test_decode_error_shrinks_with_more_workers():
+    # Section 3 (background): convergence O(h) in the node spacing; with a smooth f and no
+    # stragglers the decoding error must fall as W grows.
+    K = 4
+    X = np.random.default_rng(10).uniform(0, 1, (1, K, 16))
+    f = lambda x: np.tanh(x @ np.linspace(-1, 1, 16 * 3).reshape(16, 3))
+    errs = []
+    for W in (8, 32, 128):
+        alpha, beta = orc.chebyshev_nodes(K, W)
+        Y = f(orc.encode(X, alpha, beta))
+        out, _ = orc.decode(Y, np.ones((1, W), np.uint8), alpha, beta, 0)
+        errs.append(np.max(np.abs(out - f(X))))
+    assert errs[0] > errs[1] > errs[2]

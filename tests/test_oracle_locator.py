@@ -1,0 +1,198 @@
+"""Pins for the oracle's adversary locator (Algorithm 2) and Byzantine decoder (no GPU)."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import approxifer_oracle as orc
+from paper_2109_09868_amd import synthetic as syn
+
+
+def _rational_samples(rng, K, x):
+    """y_i = p(x_i)/q(x_i) with deg p, deg q <= K-1 and q without zero on [-1, 1], q(0) = 1
+    (the function class of Theorem 1, Appendix A)."""
+    p = rng.standard_normal(K)
+    q = np.concatenate([[1.0], 0.3 * rng.uniform(-1, 1, K - 1) / max(K - 1, 1)])
+    P = np.polynomial.polynomial.polyval(x, p)
+    Q = np.polynomial.polynomial.polyval(x, q)
+    assert np.all(Q > 0.5)
+    return P / Q
+
+
+def _brute_force_adversaries(x, y, K, A):
+    """The A-subset whose removal leaves points that lie exactly on some rational function of
+    degree (K-1, K-1): smallest singular value of [V | -y V] (homogeneous, Appendix A
+    eq. P(x_i) = y_i Q(x_i) with no error locator) is ~0 for that subset only."""
+    n = len(x)
+    best = None
+    for sub in itertools.combinations(range(n), A):
+        keep = np.setdiff1d(np.arange(n), sub)
+        V = np.vander(x[keep], K, increasing=True)
+        H = np.concatenate([V, -y[keep, None] * V], axis=1)
+        H = H / np.linalg.norm(H, axis=0)
+        smin = np.linalg.svd(H, compute_uv=False)[-1]
+        if best is None or smin < best[0]:
+            best = (smin, sub)
+    return best
+
+
+def test_system_shape_and_rows():
+    # Algorithm 2 steps 1-2: 2(K+A)-1 unknowns, one equation per available worker
+    K, A = 3, 2
+    x = np.array([0.9, 0.5, 0.1, -0.2, -0.6, -0.8, -1.0, 0.3, 0.7, -0.4])
+    y = np.arange(10.0) + 1
+    Amat, rhs = orc.locator_system(x, y, K, A)
+    M = K + A
+    assert Amat.shape == (10, 2 * M - 1) and rhs.shape == (10,)
+    i = 4
+    # P part: x^0..x^{M-1}; Q part: -y x^1 .. -y x^{M-1}; rhs: y (the Q_0 = 1 term moved right)
+    assert np.allclose(Amat[i, :M], [x[i] ** k for k in range(M)])
+    assert np.allclose(Amat[i, M:], [-y[i] * x[i] ** k for k in range(1, M)])
+    assert rhs[i] == y[i]
+    # a (P, Q) pair that satisfies P(x_i) = y_i Q(x_i) exactly solves the system exactly
+    rng = np.random.default_rng(0)
+    Qc = np.concatenate([[1.0], rng.standard_normal(M - 1) * 0.1])
+    Pc = rng.standard_normal(M)
+    y2 = np.polynomial.polynomial.polyval(x, Pc) / np.polynomial.polynomial.polyval(x, Qc)
+    A2, r2 = orc.locator_system(x, y2, K, A)
+    assert np.allclose(A2 @ np.concatenate([Pc, Qc[1:]]), r2, atol=1e-12)
+
+
+@pytest.mark.parametrize("K,A,S", [(2, 1, 0), (3, 1, 2), (3, 2, 0), (4, 2, 2)])
+def test_theorem1_q_vanishes_at_adversaries(K, A, S):
+    # Appendix A: Q = q * Lambda, Lambda(x) = prod_{adv}(1 - x/x_i) => Q(x_adv) = 0, and Q = q elsewhere
+    rng = np.random.default_rng(11 * K + A)
+    W = 2 * (K + A) + S
+    _, beta = orc.chebyshev_nodes(K, W)
+    for trial in range(20):
+        avail = np.sort(rng.permutation(W)[: W - S])
+        x = beta[avail]
+        y = _rational_samples(rng, K, x)
+        bad = np.sort(rng.permutation(avail.size)[:A])
+        y_bad = y.copy()
+        y_bad[bad] += rng.standard_normal(A) * 10 + 3
+        a = orc.locator_values(x, y_bad, K, A)
+        order = np.argsort(np.abs(a))
+        assert set(order[:A]) == set(bad)
+        assert np.abs(a[order[A - 1]]) < 1e-6 * np.abs(a[order[A]])          # clean separation
+        picks = orc.pick_smallest(a, avail, A)
+        assert set(picks) == set(avail[bad])
+
+
+@pytest.mark.parametrize("K,A,W", [(2, 1, 6), (3, 1, 8), (2, 2, 8), (3, 2, 12)])
+def test_locator_agrees_with_brute_force_subset_search(K, A, W):
+    rng = np.random.default_rng(5 + K + 10 * A)
+    _, beta = orc.chebyshev_nodes(K, W)
+    avail = np.sort(rng.permutation(W)[: 2 * (K + A)])
+    x = beta[avail]
+    for trial in range(5):
+        y = _rational_samples(rng, K, x)
+        bad = np.sort(rng.permutation(avail.size)[:A])
+        y[bad] += rng.choice([-1, 1], A) * rng.uniform(1, 5, A)
+        smin, sub = _brute_force_adversaries(x, y, K, A)
+        assert smin < 1e-10 and set(sub) == set(bad)
+        a = orc.locator_values(x, y, K, A)
+        assert set(np.argsort(np.abs(a))[:A]) == set(sub)
+
+
+def test_zero_node_cannot_be_located_with_q0_fixed():
+    # Algorithm 2 fixes Q(0) = 1 while the error locator Lambda(x) = prod (1 - x/x_i) of Appendix A
+    # needs x_i != 0.  With an odd number of workers the middle node is 0: a_i = Q(0) = 1 there, so
+    # an adversary sitting on it is never among the smallest |a_i|.  Algorithm 1 (Q_0 free) finds it.
+    K, A, W = 3, 1, 9
+    _, beta = orc.chebyshev_nodes(K, W)
+    assert abs(beta[4]) < 1e-15
+    rng = np.random.default_rng(2)
+    x = beta[:8]
+    y = _rational_samples(rng, K, x)
+    y[4] += 5.0
+    a2 = orc.locator_values(x, y, K, A)
+    assert a2[4] == pytest.approx(1.0, abs=1e-12)
+    a1 = orc.locator_values_homogeneous(x, y, K, A)
+    assert np.argmin(np.abs(a1)) == 4
+
+
+def test_algorithm1_null_vector_agrees():
+    # Algorithm 1 (Q_0 free, null vector) locates the same workers as Algorithm 2 (Q_0 = 1)
+    rng = np.random.default_rng(21)
+    K, A, W = 4, 2, 14
+    _, beta = orc.chebyshev_nodes(K, W)
+    for trial in range(20):
+        avail = np.sort(rng.permutation(W)[: 2 * (K + A)])
+        x = beta[avail]
+        y = _rational_samples(rng, K, x)
+        bad = rng.permutation(avail.size)[:A]
+        y[bad] += rng.standard_normal(A) * 4 + 2
+        a2 = orc.locator_values(x, y, K, A)
+        a1 = orc.locator_values_homogeneous(x, y, K, A)
+        assert set(np.argsort(np.abs(a1))[:A]) == set(np.argsort(np.abs(a2))[:A]) == set(bad)
+        # same polynomial up to the normalisation Q(0) = 1: a1 / a2 is one constant off the adversaries
+        good = np.setdiff1d(np.arange(avail.size), bad)
+        ratio = a1[good] / a2[good]
+        assert np.allclose(ratio, ratio[0], rtol=1e-5)
+
+
+def test_locator_invariant_to_scaling_predictions():
+    rng = np.random.default_rng(22)
+    K, A, W = 3, 2, 10
+    _, beta = orc.chebyshev_nodes(K, W)
+    x = beta
+    y = _rational_samples(rng, K, x)
+    y[[2, 7]] += [3.0, -2.0]
+    a = orc.locator_values(x, y, K, A)
+    a_scaled = orc.locator_values(x, 1000.0 * y, K, A)        # P scales, Q does not
+    assert np.allclose(a, a_scaled, rtol=1e-6, atol=1e-9)
+
+
+def test_pick_and_vote_conventions():
+    # parity unpinned by the paper: ties -> smaller worker index first; output ascending
+    avail = np.array([1, 3, 4, 8, 9])
+    a = np.array([0.5, -0.1, 0.1, 2.0, -0.1])
+    assert list(orc.pick_smallest(a, avail, 2)) == [3, 4]        # |a| ties at 0.1: workers 3, 4, 9 -> 3, 4
+    assert list(orc.pick_smallest(a, avail, 3)) == [3, 4, 9]
+    I = np.array([[7, 2], [2, 7], [5, 2], [7, 5], [1, 5]])        # counts: 2->3, 7->3, 5->3, 1->1
+    adv, counts = orc.vote(I, 10, 2)
+    assert list(adv) == [2, 5] and counts[2] == 3 and counts[7] == 3 and counts[1] == 1
+    adv, _ = orc.vote(np.array([[9, 0], [9, 0], [9, 4]]), 10, 2)
+    assert list(adv) == [0, 9]                                    # returned ascending
+    assert adv.dtype == np.int32
+
+
+def test_locate_and_decode_byzantine_on_linear_model_groups():
+    # the "byzantine" workload at CPU size: linear hosted model => coded predictions are exactly
+    # rational in beta, so the planted adversaries must be found in every group (Theorem 1),
+    # even after the predictions are rounded to float32.
+    w = syn.scaled(syn.WORKLOADS["byzantine"], G=48)
+    alpha, beta = orc.chebyshev_nodes(w.K, w.W)
+    X = syn.queries(w)
+    params = syn.model_params(w)
+    clean = syn.model_apply(w, params, orc.encode(X, alpha, beta))
+    mask = syn.masks(w)
+    adv_true = syn.adversaries(w, mask)
+    Y = syn.corrupt(w, clean, adv_true)
+    assert Y.dtype == np.float32
+    out, adv, st = orc.decode_byzantine(Y, mask, alpha, beta, w.S, w.A)
+    assert np.all(st == 0)
+    assert np.array_equal(adv, adv_true)
+    # decoding after exclusion equals plain decoding with the adversaries masked out as stragglers
+    mask2 = mask.copy()
+    for g in range(w.G):
+        mask2[g, adv_true[g]] = 0
+    out2, st2 = orc.decode(Y, mask2, alpha, beta, w.S + w.A)
+    assert np.all(st2 == 0) and np.array_equal(out, out2)
+    # and it is far closer to the true predictions than decoding with the adversaries left in
+    truth = syn.model_apply(w, params, X)
+    out_dirty, _ = orc.decode(Y, mask, alpha, beta, w.S)
+    assert np.median(np.abs(out - truth)) < 0.25 * np.median(np.abs(out_dirty - truth))
+
+
+def test_decode_byzantine_status():
+    K, A, S = 2, 1, 1
+    W = 2 * (K + A) + S
+    alpha, beta = orc.chebyshev_nodes(K, W)
+    Y = np.random.default_rng(3).standard_normal((2, W, 3))
+    mask = np.ones((2, W), np.uint8)
+    mask[0, 2] = 0                     # ok: W-S ones
+    out, adv, st = orc.decode_byzantine(Y, mask, alpha, beta, S, A)
+    assert list(st) == [0, 1] and np.all(out[1] == 0) and np.all(adv[1] == -1)
+    assert adv[0, 0] != 2              # a straggler can never be named an adversary
