@@ -1,0 +1,145 @@
+/*
+ * approxifer.h -- C ABI of the ApproxIFER coding layer for AMD MI355X (gfx950).
+ *
+ * ApproxIFER (arXiv 2109.09868) serves K queries of a group with N workers that all
+ * host the same model f: the K queries are encoded into N coded queries, every worker
+ * runs f on one coded query, and the K predictions are rebuilt from whichever workers
+ * answer, after workers that answered wrongly have been located and dropped.
+ *
+ * Naming.  N here is the NUMBER OF WORKERS.  The paper indexes its workers 0..N and so
+ * has N+1 of them (Section 2, "System Architecture"); this library's N is the paper's
+ * N+1.  S is the number of stragglers, A the number of Byzantine workers (the paper's E).
+ * alpha[K] are the query nodes, beta[N] the worker nodes (Section 3, "ApproxIFER
+ * Encoding").
+ *
+ * Conventions common to all entry points
+ *   - d_* arguments are DEVICE pointers owned by the caller; h_* arguments are HOST
+ *     pointers that are read before the call returns and may be freed afterwards.
+ *   - All tensors are dense, row-major, with the last index contiguous.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued on it and the call returns without synchronising.  The library allocates
+ *     no device memory and keeps no state between calls.
+ *   - Return value: APPROXIFER_OK when the kernels were enqueued; a negative
+ *     APPROXIFER_ERR_* code otherwise, in which case nothing was enqueued and no output
+ *     was touched.  approxifer_strerror() turns a code into text.
+ *   - G = 0, D = 0 or C = 0 is a valid empty call: nothing is enqueued, OK is returned.
+ *   - Limits: 1 <= K <= APPROXIFER_MAX_K, 2 <= N <= APPROXIFER_MAX_N; the Byzantine
+ *     decoder additionally needs N - S <= APPROXIFER_MAX_AVAIL_BYZ.
+ *   - Nodes must be finite and pairwise distinct within each set.  A query node may
+ *     coincide with a worker node; the interpolant then passes through the data there.
+ */
+#ifndef APPROXIFER_H
+#define APPROXIFER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define APPROXIFER_MAX_K 64
+#define APPROXIFER_MAX_N 128
+#define APPROXIFER_MAX_AVAIL_BYZ 64
+
+#define APPROXIFER_OK 0
+#define APPROXIFER_ERR_NULL_POINTER (-1)   /* a required pointer is NULL */
+#define APPROXIFER_ERR_BAD_SHAPE (-2)      /* negative size, K < 1, N < 2, S < 0, S >= N, A < 1 ... */
+#define APPROXIFER_ERR_LIMIT (-3)          /* K, N or N-S above the compiled limits */
+#define APPROXIFER_ERR_BAD_NODES (-4)      /* a node is not finite, or two nodes of one set are equal */
+#define APPROXIFER_ERR_TOO_FEW_WORKERS (-5)/* N - S < 2 (K + A): Algorithm 2's system would be under-determined */
+#define APPROXIFER_ERR_BAD_SIGN_MODE (-6)  /* sign_mode is neither 0 nor 1 */
+#define APPROXIFER_ERR_LAUNCH (-7)         /* the HIP runtime refused the launch */
+
+/* Decoder sign conventions, see approxifer_decode(). */
+#define APPROXIFER_SIGN_WORKER_INDEX 0
+#define APPROXIFER_SIGN_SURVIVOR_RANK 1
+
+/* Per-group status values written to d_status. */
+#define APPROXIFER_GROUP_OK 0
+#define APPROXIFER_GROUP_BAD_MASK 1        /* the group's mask does not hold exactly N-S ones */
+
+/*
+ * Chebyshev nodes of Section 3, "ApproxIFER Encoding":
+ *   h_alpha[j] = cos((2j+1) pi / (2K)), j = 0..K-1   (first kind, query nodes)
+ *   h_beta[i]  = cos(i pi / (N-1)),     i = 0..N-1   (second kind, worker nodes)
+ * Both arrays are host memory written by the call.  Returns OK, ERR_NULL_POINTER or
+ * ERR_BAD_SHAPE (K < 1 or N < 2).
+ */
+int approxifer_chebyshev_nodes(int K, int N, double *h_alpha, double *h_beta);
+
+/*
+ * Encoder (Section 3, "ApproxIFER Encoding").  For every group g and worker i
+ *     d_coded[g][i][:] = u_g(beta_i) = sum_j l_j(beta_i) d_queries[g][j][:],
+ *     l_j(z) = ((-1)^j / (z - alpha_j)) / sum_j' ((-1)^j' / (z - alpha_j')),
+ * Berrut's rational interpolant through the K queries, read at the worker nodes.
+ * If beta_i equals some alpha_j exactly, coded query i is query j.
+ *
+ *   d_queries  [G][K][D] float32, device, read only
+ *   d_coded    [G][N][D] float32, device, written; must not overlap d_queries
+ *   h_alpha    [K] float64, host;  h_beta [N] float64, host
+ * The basis functions are evaluated in float64 on the device and rounded to float32;
+ * the contraction over j accumulates in float32.
+ */
+int approxifer_encode(const float *d_queries, float *d_coded,
+                      int64_t G, int K, int N, int64_t D,
+                      const double *h_alpha, const double *h_beta, void *stream);
+
+/*
+ * Decoder (Section 3, "ApproxIFER Decoding", step 2).  For every group g, with F the
+ * set of workers whose mask byte is non-zero, in ascending order,
+ *     d_out[g][j][:] = r_g(alpha_j)
+ *                    = sum_{i in F} w_i d_preds[g][i][:] / sum_{i in F} w_i,
+ *     w_i = s_i / (alpha_j - beta_i).
+ * sign_mode APPROXIFER_SIGN_WORKER_INDEX takes s_i = (-1)^i with i the worker index,
+ * as that formula is printed; APPROXIFER_SIGN_SURVIVOR_RANK takes s_i = (-1)^rank(i in F),
+ * which is Berrut's interpolant (Section 3, eq. (2)) on the surviving nodes.  The two are
+ * equal when no worker is missing.
+ *
+ *   d_preds   [G][N][C] float32, device; rows of workers with mask 0 are never read
+ *   d_mask    [G][N] uint8, device; non-zero = the worker returned
+ *   d_out     [G][K][C] float32, device, written
+ *   d_status  [G] int32, device, written, or NULL.  A group whose mask does not hold
+ *             exactly N-S non-zero bytes gets APPROXIFER_GROUP_BAD_MASK and its d_out
+ *             rows are left untouched; every other group gets APPROXIFER_GROUP_OK.
+ * Weights and accumulation are float64; each output is rounded to float32 once.
+ */
+int approxifer_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_status,
+                      int64_t G, int K, int N, int S, int64_t C,
+                      const double *h_alpha, const double *h_beta, int sign_mode, void *stream);
+
+/*
+ * Byzantine decoder (Section 3, "ApproxIFER Decoding", steps 1-2, Algorithm 2).
+ * For every group: among the N-S available workers locate A adversaries, drop them,
+ * decode over the rest as approxifer_decode() does.
+ * Location, per class c = 0..C-1 (Algorithm 2): with M = K + A and x_i = beta_i,
+ * y_i = d_preds[g][i][c] for the available i, find P (degree M-1) and
+ * Q = 1 + Q_1 x + .. + Q_{M-1} x^{M-1} minimising sum_i (P(x_i) - y_i Q(x_i))^2
+ * (ordinary least squares, float64 Householder QR), set a_i = Q(x_i), and note the A
+ * workers of smallest |a_i| (equal magnitudes: smaller worker index first).  The A workers
+ * noted most often over the C classes (equal counts: smaller worker index first) are the
+ * adversaries.
+ *
+ *   d_adv     [G][A] int32, device, written: located workers in ascending order
+ *   other arguments as approxifer_decode(); groups with a bad mask leave d_out and
+ *   d_adv rows untouched.
+ * Requires A >= 1, N - S >= 2 (K + A) (Section 3, eq. (3), the decoding condition) and
+ * N - S <= APPROXIFER_MAX_AVAIL_BYZ.  A worker whose node is exactly 0 can never be
+ * located, since Q(0) = 1 by construction; the Chebyshev worker nodes contain 0 only
+ * when N is odd.
+ */
+int approxifer_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *d_out,
+                                int32_t *d_adv, int32_t *d_status,
+                                int64_t G, int K, int N, int S, int A, int64_t C,
+                                const double *h_alpha, const double *h_beta, int sign_mode, void *stream);
+
+/* Text for a return code; never NULL.  The string is static. */
+const char *approxifer_strerror(int code);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int approxifer_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* APPROXIFER_H */

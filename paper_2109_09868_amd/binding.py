@@ -1,0 +1,171 @@
+"""ctypes binding of libapproxifer.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch CUDA (ROCm) tensors used purely as device buffers; every step of the
+coding layer runs inside the library's HIP kernels.  There is no CPU fallback: if the
+library is missing the loader raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libapproxifer.so")
+
+MAX_K = 64
+MAX_N = 128
+MAX_AVAIL_BYZ = 64
+SIGN_WORKER_INDEX = 0
+SIGN_SURVIVOR_RANK = 1
+
+EXPORTS = (
+    "approxifer_version",
+    "approxifer_strerror",
+    "approxifer_chebyshev_nodes",
+    "approxifer_encode",
+    "approxifer_decode",
+    "approxifer_decode_byzantine",
+)
+
+_lib = None
+
+
+class ApproxiferError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("approxifer error %d: %s" % (code, text))
+        self.code = code
+
+
+def load() -> ctypes.CDLL:
+    """Load the HIP library built in-tree.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            "%s is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+            "There is no fallback path." % LIB_PATH
+        )
+    lib = ctypes.CDLL(LIB_PATH)
+    c_dp = ctypes.POINTER(ctypes.c_double)
+    vp = ctypes.c_void_p
+    lib.approxifer_version.restype = ctypes.c_int
+    lib.approxifer_version.argtypes = []
+    lib.approxifer_strerror.restype = ctypes.c_char_p
+    lib.approxifer_strerror.argtypes = [ctypes.c_int]
+    lib.approxifer_chebyshev_nodes.restype = ctypes.c_int
+    lib.approxifer_chebyshev_nodes.argtypes = [ctypes.c_int, ctypes.c_int, c_dp, c_dp]
+    lib.approxifer_encode.restype = ctypes.c_int
+    lib.approxifer_encode.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int64, c_dp, c_dp, vp]
+    lib.approxifer_decode.restype = ctypes.c_int
+    lib.approxifer_decode.argtypes = [vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                      ctypes.c_int64, c_dp, c_dp, ctypes.c_int, vp]
+    lib.approxifer_decode_byzantine.restype = ctypes.c_int
+    lib.approxifer_decode_byzantine.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                                ctypes.c_int, ctypes.c_int, ctypes.c_int64, c_dp, c_dp, ctypes.c_int, vp]
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load().approxifer_strerror(int(code)).decode()
+
+
+def _check(code: int) -> None:
+    if code != 0:
+        raise ApproxiferError(code, strerror(code))
+
+
+def _nodes(a) -> tuple:
+    arr = np.ascontiguousarray(a, dtype=np.float64)
+    return arr, arr.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _dev(t, dtype, shape=None):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("expected a tensor in device memory")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise TypeError("expected a contiguous %s tensor, got %s" % (dtype, t.dtype))
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("expected shape %s, got %s" % (tuple(shape), tuple(t.shape)))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def approxifer_chebyshev_nodes(K: int, N: int):
+    """(alpha[K], beta[N]) float64 numpy arrays from the library's own node generator."""
+    alpha = np.empty(max(K, 0), dtype=np.float64)
+    beta = np.empty(max(N, 0), dtype=np.float64)
+    _check(load().approxifer_chebyshev_nodes(int(K), int(N),
+                                             alpha.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                                             beta.ctypes.data_as(ctypes.POINTER(ctypes.c_double))))
+    return alpha, beta
+
+
+def approxifer_encode(queries, alpha, beta, coded=None, stream=None):
+    """queries [G, K, D] float32 device tensor -> coded [G, N, D]; K = len(alpha), N = len(beta)."""
+    import torch
+    a, ap = _nodes(alpha)
+    b, bp = _nodes(beta)
+    G, K, D = queries.shape
+    N = b.size
+    if K != a.size:
+        raise ValueError("queries.shape[1] must equal len(alpha)")
+    if coded is None:
+        coded = torch.empty((G, N, D), dtype=torch.float32, device=queries.device)
+    _check(load().approxifer_encode(_dev(queries, torch.float32), _dev(coded, torch.float32, (G, N, D)),
+                                    G, K, N, D, ap, bp, ctypes.c_void_p(_stream_handle(stream))))
+    return coded
+
+
+def approxifer_decode(preds, mask, alpha, beta, S, sign_mode=SIGN_WORKER_INDEX, out=None, status=None, stream=None):
+    """preds [G, N, C] float32, mask [G, N] uint8 -> (out [G, K, C] float32, status [G] int32)."""
+    import torch
+    a, ap = _nodes(alpha)
+    b, bp = _nodes(beta)
+    G, N, C = preds.shape
+    K = a.size
+    if N != b.size:
+        raise ValueError("preds.shape[1] must equal len(beta)")
+    if out is None:
+        out = torch.zeros((G, K, C), dtype=torch.float32, device=preds.device)
+    if status is None:
+        status = torch.full((G,), -1, dtype=torch.int32, device=preds.device)
+    _check(load().approxifer_decode(_dev(preds, torch.float32), _dev(mask, torch.uint8, (G, N)),
+                                    _dev(out, torch.float32, (G, K, C)), _dev(status, torch.int32, (G,)),
+                                    G, K, N, int(S), C, ap, bp, int(sign_mode),
+                                    ctypes.c_void_p(_stream_handle(stream))))
+    return out, status
+
+
+def approxifer_decode_byzantine(preds, mask, alpha, beta, S, A, sign_mode=SIGN_WORKER_INDEX, out=None, adv=None,
+                                status=None, stream=None):
+    """As approxifer_decode, after locating and dropping A adversaries per group.
+    Returns (out [G, K, C] float32, adv [G, A] int32 ascending, status [G] int32)."""
+    import torch
+    a, ap = _nodes(alpha)
+    b, bp = _nodes(beta)
+    G, N, C = preds.shape
+    K = a.size
+    if N != b.size:
+        raise ValueError("preds.shape[1] must equal len(beta)")
+    if out is None:
+        out = torch.zeros((G, K, C), dtype=torch.float32, device=preds.device)
+    if adv is None:
+        adv = torch.full((G, max(int(A), 0)), -1, dtype=torch.int32, device=preds.device)
+    if status is None:
+        status = torch.full((G,), -1, dtype=torch.int32, device=preds.device)
+    _check(load().approxifer_decode_byzantine(_dev(preds, torch.float32), _dev(mask, torch.uint8, (G, N)),
+                                              _dev(out, torch.float32, (G, K, C)), _dev(adv, torch.int32),
+                                              _dev(status, torch.int32, (G,)), G, K, N, int(S), int(A), C, ap, bp,
+                                              int(sign_mode), ctypes.c_void_p(_stream_handle(stream))))
+    return out, adv, status

@@ -1,0 +1,376 @@
+// ApproxIFER decoder and Byzantine decoder for gfx950 (Section 3, "ApproxIFER Decoding").
+//
+// Decoder: one workgroup per (group, tile of prediction columns).  The group's mask is
+// turned into the ascending survivor list F with wavefront ballots, the K x |F| matrix of
+// basis functions is evaluated in float64 (one wave per query node, the denominator by a
+// wavefront reduction) and kept transposed in LDS, and the contraction over F accumulates
+// in float64 with the weights broadcast from LDS.  Rows of missing workers are never read.
+//
+// Byzantine decoder: one workgroup per group.  Each wave takes classes c = wave, wave+nw, ..
+// and runs Algorithm 2 on them: lane r owns row r of the (N-S) x (2(K+A)-1) system, a
+// Householder QR is applied column by column (row-private storage in LDS, column norms and
+// dot products by wavefront reductions), the Q coefficients come out of the back
+// substitution and are folded into a_r = Q(x_r) by Horner's rule as they appear.  The A
+// smallest |a_r| vote; after the vote the adversaries are removed from the available list
+// and the workgroup decodes the group as above.
+#include "common.h"
+
+namespace approxifer {
+namespace {
+
+constexpr int kColsPerTile = 64;   // vector columns handled by one wave-wide item row
+
+__device__ __forceinline__ int round_up4(int v) { return (v + 3) & ~3; }
+
+// Ascending list of the workers whose mask byte is non-zero.  Called by ONE whole wave.
+// Returns the number of survivors; list[0..n) is written (visible after the next barrier).
+__device__ __forceinline__ int survivors_from_mask(const uint8_t *__restrict__ mask_row, int N, int *list) {
+    const int lane = lane_id();
+    const bool b0 = (lane < N) && (mask_row[lane] != 0);
+    const bool b1 = (lane + kWave < N) && (mask_row[lane + kWave] != 0);
+    const unsigned long long m0 = __ballot(b0);
+    const unsigned long long m1 = __ballot(b1);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    const int n0 = __popcll(m0);
+    if (b0) list[__popcll(m0 & below)] = lane;
+    if (b1) list[n0 + __popcll(m1 & below)] = lane + kWave;
+    return n0 + __popcll(m1);
+}
+
+// Transposed decoder weights WdT[r*KP + j] = l_{F_r}(alpha_j), Section 3 "ApproxIFER Decoding"
+// step 2.  Called by the whole workgroup after F is visible; the caller provides a barrier
+// afterwards.  WdT must have been zeroed for the pad columns j in [K, KP).
+__device__ __forceinline__ void decoder_weights(const Nodes &nodes, const int *F, int nF, int K, int KP,
+                                                int sign_mode, double *WdT) {
+    const int lane = lane_id();
+    const int nwaves = blockDim.x / kWave;
+    for (int j = wave_id(); j < K; j += nwaves) {
+        const double z = nodes.alpha[j];
+        BerrutTerm bt[2];
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int r = p * kWave + lane;
+            const bool valid = r < nF;
+            const int i = valid ? F[r] : 0;
+            const int parity = (sign_mode == APPROXIFER_SIGN_WORKER_INDEX) ? (i & 1) : (r & 1);
+            bt[p] = berrut_term(z, nodes.beta[i], parity ? -1.0 : 1.0, valid);
+        }
+        const double den = wave_sum(bt[0].t + bt[1].t);
+        const bool any_hit = (__ballot(bt[0].hit) | __ballot(bt[1].hit)) != 0ull;
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int r = p * kWave + lane;
+            if (r < nF) WdT[r * KP + j] = any_hit ? (bt[p].hit ? 1.0 : 0.0) : bt[p].t / den;
+        }
+    }
+}
+
+template <int VEC> struct PredVec;
+template <> struct PredVec<4> { typedef v4f type; };
+template <> struct PredVec<1> { typedef float type; };
+
+template <int VEC> __device__ __forceinline__ float vec_get(typename PredVec<VEC>::type v, int e);
+template <> __device__ __forceinline__ float vec_get<4>(v4f v, int e) { return v[e]; }
+template <> __device__ __forceinline__ float vec_get<1>(float v, int) { return v; }
+
+template <int VEC> __device__ __forceinline__ void store_row(float *dst, const double *acc);
+template <> __device__ __forceinline__ void store_row<4>(float *dst, const double *acc) {
+    v4f v;
+    v[0] = static_cast<float>(acc[0]);
+    v[1] = static_cast<float>(acc[1]);
+    v[2] = static_cast<float>(acc[2]);
+    v[3] = static_cast<float>(acc[3]);
+    *reinterpret_cast<v4f *>(dst) = v;
+}
+template <> __device__ __forceinline__ void store_row<1>(float *dst, const double *acc) {
+    *dst = static_cast<float>(acc[0]);
+}
+
+// out[g][j][c] = sum_r WdT[r][j] * preds[g][F_r][c] for the vector columns [cv0, cv1) of one
+// group.  Work items are (quad of query rows, vector column); a wave shares its quad, so the
+// weight reads are LDS broadcasts.  float64 accumulation, one rounding on store.
+template <int VEC>
+__device__ __forceinline__ void contract_tile(const float *__restrict__ pg, float *__restrict__ og, const int *F,
+                                              int nF, int K, int KP, int64_t C, int64_t cv0, int64_t cv1,
+                                              const double *WdT) {
+    typedef typename PredVec<VEC>::type V;
+    const int KQ = KP / 4;
+    const int items = KQ * kColsPerTile;
+    for (int it = threadIdx.x; it < items; it += blockDim.x) {
+        const int q = it / kColsPerTile;
+        const int64_t cv = cv0 + (it % kColsPerTile);
+        if (cv >= cv1) continue;
+        double acc[4][VEC];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[jj][e] = 0.0;
+        for (int r = 0; r < nF; ++r) {
+            const V y = *reinterpret_cast<const V *>(pg + static_cast<size_t>(F[r]) * C + cv * VEC);
+            const double *w = WdT + r * KP + 4 * q;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const double wj = w[jj];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[jj][e] = fma(wj, static_cast<double>(vec_get<VEC>(y, e)), acc[jj][e]);
+            }
+        }
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int j = 4 * q + jj;
+            if (j < K) {
+                store_row<VEC>(og + static_cast<size_t>(j) * C + cv * VEC, acc[jj]);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// decoder kernel
+// ------------------------------------------------------------------------------------
+// dynamic LDS: double WdT[(N-S) * KP] | int F[N] | int n
+template <int VEC>
+__global__ void decode_kernel(const float *__restrict__ preds, const uint8_t *__restrict__ mask,
+                              float *__restrict__ out, int32_t *__restrict__ status, int K, int N, int S,
+                              int64_t C, int64_t Cv, int64_t ctiles, int sign_mode, const Nodes nodes) {
+    extern __shared__ double lds_d[];
+    const int KP = round_up4(K);
+    const int nF_expected = N - S;
+    double *WdT = lds_d;
+    int *F = reinterpret_cast<int *>(WdT + nF_expected * KP);
+    int *n_sh = F + N;
+
+    const int64_t g = blockIdx.x / ctiles;
+    const int64_t ct = blockIdx.x - g * ctiles;
+
+    for (int e = threadIdx.x; e < nF_expected * KP; e += blockDim.x) WdT[e] = 0.0;
+    if (wave_id() == 0) {
+        const int n = survivors_from_mask(mask + g * N, N, F);
+        if (lane_id() == 0) *n_sh = n;
+    }
+    __syncthreads();
+    const int nF = *n_sh;
+    const bool good = nF == nF_expected;
+    if (ct == 0 && threadIdx.x == 0 && status != nullptr)
+        status[g] = good ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
+    if (!good) return;
+
+    decoder_weights(nodes, F, nF, K, KP, sign_mode, WdT);
+    __syncthreads();
+
+    const int64_t cv0 = ct * kColsPerTile;
+    const int64_t cv1 = (cv0 + kColsPerTile < Cv) ? cv0 + kColsPerTile : Cv;
+    contract_tile<VEC>(preds + static_cast<size_t>(g) * N * C, out + static_cast<size_t>(g) * K * C, F, nF, K, KP, C,
+                       cv0, cv1, WdT);
+}
+
+// ------------------------------------------------------------------------------------
+// Byzantine decoder kernel
+// ------------------------------------------------------------------------------------
+// Algorithm 2, steps 1-3 for one class, by one wave.  Lane r < n owns row r:
+// x = beta of its worker, y = its prediction for the class.  `mat` is this wave's LDS
+// scratch of (2M) columns of n doubles, column-major; a lane only ever touches its own row.
+// Returns a_r = Q(x_r) on lanes r < n.
+__device__ __forceinline__ double locator_values_wave(double *mat, int n, int M, double x, double y, bool row) {
+    const int lane = lane_id();
+    const int cols = 2 * M - 1;   // unknowns P_0..P_{M-1}, Q_1..Q_{M-1}; column `cols` is the right-hand side
+
+    if (row) {
+        double p = 1.0;
+        for (int k = 0; k < M; ++k) {
+            mat[k * n + lane] = p;                            // x^k
+            if (k >= 1) mat[(M - 1 + k) * n + lane] = -y * p; // -y x^k
+            p *= x;
+        }
+        mat[cols * n + lane] = y;
+    }
+
+    // Householder QR, least-squares form: reflect column k onto e_k using rows k..n-1 and
+    // apply the reflector to the columns right of it and to the right-hand side.
+    double diag = 0.0;   // R[lane][lane] once column `lane` is done
+    for (int k = 0; k < cols; ++k) {
+        const bool active = row && lane >= k;
+        const double xk = active ? mat[k * n + lane] : 0.0;
+        const double sigma = wave_sum(xk * xk);
+        const double xkk = __shfl(xk, k, kWave);
+        if (sigma == 0.0) continue;   // wave-uniform
+        const double nrm = sqrt(sigma);
+        const double alpha = (xkk >= 0.0) ? -nrm : nrm;
+        const double v = (lane == k) ? xk - alpha : xk;
+        const double scale = 1.0 / (sigma - alpha * xkk);   // 2 / (v^T v)
+        for (int j = k + 1; j <= cols; ++j) {
+            const double aj = active ? mat[j * n + lane] : 0.0;
+            const double d = wave_sum(v * aj);
+            if (active) mat[j * n + lane] = aj - (scale * d) * v;
+        }
+        if (lane == k) diag = alpha;
+    }
+
+    // Back substitution for Q_{M-1} .. Q_1 (unknowns cols-1 .. M); P is not needed.
+    double s = row ? mat[cols * n + lane] : 0.0;
+    double a = 0.0;
+    for (int j = cols - 1; j >= M; --j) {
+        const double sol = __shfl(s / diag, j, kWave);
+        if (row && lane < j) s -= mat[j * n + lane] * sol;
+        a = a * x + sol;
+    }
+    return a * x + 1.0;   // Q_0 = 1
+}
+
+// dynamic LDS: double mats[nw][2M * n] | double WdT[(n-A) * KP] | int avail[N] | int F[N] | int votes[N]
+//              | int sel[N] | int n
+template <int VEC>
+__global__ void decode_byzantine_kernel(const float *__restrict__ preds, const uint8_t *__restrict__ mask,
+                                        float *__restrict__ out, int32_t *__restrict__ adv,
+                                        int32_t *__restrict__ status, int K, int N, int S, int A, int64_t C,
+                                        int64_t Cv, int sign_mode, const Nodes nodes) {
+    extern __shared__ double lds_d[];
+    const int KP = round_up4(K);
+    const int M = K + A;
+    const int n_expected = N - S;
+    const int nF = n_expected - A;
+    const int nw = blockDim.x / kWave;
+    const int mat_doubles = 2 * M * n_expected;
+
+    double *mats = lds_d;
+    double *WdT = mats + static_cast<size_t>(nw) * mat_doubles;
+    int *avail = reinterpret_cast<int *>(WdT + nF * KP);
+    int *F = avail + N;
+    int *votes = F + N;
+    int *sel = votes + N;
+    int *n_sh = sel + N;
+
+    const int64_t g = blockIdx.x;
+    const int lane = lane_id();
+    const int wv = wave_id();
+    const float *pg = preds + static_cast<size_t>(g) * N * C;
+
+    for (int e = threadIdx.x; e < nF * KP; e += blockDim.x) WdT[e] = 0.0;
+    for (int e = threadIdx.x; e < N; e += blockDim.x) votes[e] = 0;
+    if (wv == 0) {
+        const int n = survivors_from_mask(mask + g * N, N, avail);
+        if (lane == 0) *n_sh = n;
+    }
+    __syncthreads();
+    const int n = *n_sh;
+    const bool good = n == n_expected;
+    if (threadIdx.x == 0 && status != nullptr) status[g] = good ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
+    if (!good) return;
+
+    // ---- Algorithm 2: per-class fit, pick, vote ---------------------------------------
+    {
+        const bool row = lane < n;
+        const int worker = row ? avail[lane] : 0;
+        const double x = nodes.beta[worker];
+        double *mat = mats + static_cast<size_t>(wv) * mat_doubles;
+        for (int64_t c = wv; c < C; c += nw) {
+            const double y = row ? static_cast<double>(pg[static_cast<size_t>(worker) * C + c]) : 0.0;
+            const double a = locator_values_wave(mat, n, M, x, y, row);
+            // steps 4-5: the A smallest |a|; equal magnitudes keep ascending worker order
+            const double key = (!row || a != a) ? __builtin_inf() : fabs(a);
+            int rank = 0;
+            for (int r = 0; r < n; ++r) {
+                const double other = __shfl(key, r, kWave);
+                rank += (other < key || (other == key && r < lane)) ? 1 : 0;
+            }
+            if (row && rank < A) atomicAdd(&votes[worker], 1);
+        }
+    }
+    __syncthreads();
+
+    // ---- the A most voted workers (equal counts: smaller index first), ascending -------
+    for (int i = threadIdx.x; i < N; i += blockDim.x) {
+        const int mine = votes[i];
+        int rank = 0;
+        for (int o = 0; o < N; ++o) {
+            const int v = votes[o];
+            rank += (v > mine || (v == mine && o < i)) ? 1 : 0;
+        }
+        sel[i] = rank < A ? 1 : 0;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < N; i += blockDim.x) {
+        if (sel[i]) {
+            int pos = 0;
+            for (int o = 0; o < i; ++o) pos += sel[o];
+            adv[g * A + pos] = i;
+        }
+    }
+    if (wv == 0) {   // F = available workers minus the located ones (n <= 64: one pass)
+        const bool keep = (lane < n) && !sel[avail[lane]];
+        const unsigned long long m = __ballot(keep);
+        if (keep) F[__popcll(m & ((1ull << lane) - 1ull))] = avail[lane];
+    }
+    __syncthreads();
+
+    // ---- decode over F -------------------------------------------------------------------
+    decoder_weights(nodes, F, nF, K, KP, sign_mode, WdT);
+    __syncthreads();
+    float *og = out + static_cast<size_t>(g) * K * C;
+    for (int64_t cv0 = 0; cv0 < Cv; cv0 += kColsPerTile) {
+        const int64_t cv1 = (cv0 + kColsPerTile < Cv) ? cv0 + kColsPerTile : Cv;
+        contract_tile<VEC>(pg, og, F, nF, K, KP, C, cv0, cv1, WdT);
+    }
+}
+
+bool aligned16(const void *p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
+
+}  // namespace
+
+int launch_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_status, int64_t G, int K,
+                  int N, int S, int64_t C, const Nodes &nodes, int sign_mode, hipStream_t stream) {
+    const int KP = (K + 3) & ~3;
+    const bool vec4 = (C % 4 == 0) && aligned16(d_preds) && aligned16(d_out);
+    const int64_t Cv = vec4 ? C / 4 : C;
+    const int64_t ctiles = (Cv + kColsPerTile - 1) / kColsPerTile;
+    const int64_t blocks = G * ctiles;
+    if (blocks > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    int waves = KP / 4;
+    if (waves > 4) waves = 4;
+    const size_t lds = sizeof(double) * static_cast<size_t>(N - S) * KP + sizeof(int) * (static_cast<size_t>(N) + 2);
+    const dim3 grid(static_cast<unsigned>(blocks)), block(waves * kWave);
+    if (lds > 64 * 1024) {   // only K = 64 with more than 127 survivors; gfx950 has 160 KB of LDS per CU
+        const void *fn = vec4 ? reinterpret_cast<const void *>(decode_kernel<4>)
+                              : reinterpret_cast<const void *>(decode_kernel<1>);
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
+            return APPROXIFER_ERR_LAUNCH;
+    }
+    if (vec4)
+        hipLaunchKernelGGL(decode_kernel<4>, grid, block, lds, stream, d_preds, d_mask, d_out, d_status, K, N, S, C,
+                           Cv, ctiles, sign_mode, nodes);
+    else
+        hipLaunchKernelGGL(decode_kernel<1>, grid, block, lds, stream, d_preds, d_mask, d_out, d_status, K, N, S, C,
+                           Cv, ctiles, sign_mode, nodes);
+    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+}
+
+int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
+                            int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C, const Nodes &nodes,
+                            int sign_mode, hipStream_t stream) {
+    const int KP = (K + 3) & ~3;
+    const int n = N - S;
+    const int M = K + A;
+    const bool vec4 = (C % 4 == 0) && aligned16(d_preds) && aligned16(d_out);
+    const int64_t Cv = vec4 ? C / 4 : C;
+    if (G > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+
+    const size_t fixed = sizeof(double) * static_cast<size_t>(n - A) * KP + sizeof(int) * (4 * static_cast<size_t>(N) + 2);
+    const size_t per_wave = sizeof(double) * 2 * static_cast<size_t>(M) * n;
+    const size_t budget = 64 * 1024;
+    if (fixed + per_wave > budget) return APPROXIFER_ERR_LIMIT;
+    int nw = static_cast<int>((budget - fixed) / per_wave);
+    if (nw > 8) nw = 8;
+    if (nw > C) nw = static_cast<int>(C);
+    if (nw < 1) nw = 1;
+    const size_t lds = fixed + nw * per_wave;
+    const dim3 grid(static_cast<unsigned>(G)), block(nw * kWave);
+    if (vec4)
+        hipLaunchKernelGGL(decode_byzantine_kernel<4>, grid, block, lds, stream, d_preds, d_mask, d_out, d_adv,
+                           d_status, K, N, S, A, C, Cv, sign_mode, nodes);
+    else
+        hipLaunchKernelGGL(decode_byzantine_kernel<1>, grid, block, lds, stream, d_preds, d_mask, d_out, d_adv,
+                           d_status, K, N, S, A, C, Cv, sign_mode, nodes);
+    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+}
+
+}  // namespace approxifer

@@ -1,0 +1,112 @@
+"""The C ABI without a GPU: the library loads, exports what the header declares, its host-side
+validation returns the documented codes, and its node generator matches the oracle's."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import approxifer_oracle as orc
+from paper_2109_09868_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "approxifer.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return binding.load()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(approxifer_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = _declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+    assert lib.approxifer_version() >= 100
+
+
+def test_header_constants_match_binding():
+    text = open(HEADER).read()
+    consts = dict(re.findall(r"#define\s+(APPROXIFER_[A-Z_]+)\s+\(?(-?\d+)\)?", text))
+    assert int(consts["APPROXIFER_MAX_K"]) == binding.MAX_K
+    assert int(consts["APPROXIFER_MAX_N"]) == binding.MAX_N
+    assert int(consts["APPROXIFER_MAX_AVAIL_BYZ"]) == binding.MAX_AVAIL_BYZ
+    assert int(consts["APPROXIFER_SIGN_WORKER_INDEX"]) == binding.SIGN_WORKER_INDEX == orc.SIGN_WORKER_INDEX
+    assert int(consts["APPROXIFER_SIGN_SURVIVOR_RANK"]) == binding.SIGN_SURVIVOR_RANK == orc.SIGN_SURVIVOR_RANK
+
+
+@pytest.mark.parametrize("K,N", [(1, 2), (4, 6), (12, 20), (8, 24), (32, 48), (64, 128), (2, 5), (6, 9)])
+def test_library_nodes_match_oracle_nodes(lib, K, N):
+    a, b = binding.approxifer_chebyshev_nodes(K, N)
+    ao, bo = orc.chebyshev_nodes(K, N)
+    # two independent cos() evaluations of the same formula: a few ulp at most
+    assert np.max(np.abs(a - ao)) <= 4 * np.finfo(np.float64).eps
+    assert np.max(np.abs(b - bo)) <= 4 * np.finfo(np.float64).eps
+
+
+def test_strerror_texts(lib):
+    seen = set()
+    for code in range(0, -8, -1):
+        s = binding.strerror(code)
+        assert s and "unknown" not in s
+        seen.add(s)
+    assert len(seen) == 8
+    assert "unknown" in binding.strerror(-99)
+
+
+def _dp(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def test_host_validation_codes(lib):
+    a, b = orc.chebyshev_nodes(4, 6)
+    fake = ctypes.c_void_p(256)          # never dereferenced: every call below fails validation first
+    enc = lib.approxifer_encode
+    assert enc(fake, fake, 1, 4, 6, 8, None, _dp(b), None) == -1
+    assert enc(None, fake, 1, 4, 6, 8, _dp(a), _dp(b), None) == -1
+    assert enc(fake, fake, -1, 4, 6, 8, _dp(a), _dp(b), None) == -2
+    assert enc(fake, fake, 1, 0, 6, 8, _dp(a), _dp(b), None) == -2
+    assert enc(fake, fake, 1, 4, 1, 8, _dp(a), _dp(b), None) == -2
+    big = np.linspace(-1, 1, 200)
+    assert enc(fake, fake, 1, 65, 6, 8, _dp(big), _dp(b), None) == -3
+    assert enc(fake, fake, 1, 4, 129, 8, _dp(a), _dp(big), None) == -3
+    dup = a.copy(); dup[2] = dup[0]
+    assert enc(fake, fake, 1, 4, 6, 8, _dp(dup), _dp(b), None) == -4
+    nan = b.copy(); nan[3] = np.nan
+    assert enc(fake, fake, 1, 4, 6, 8, _dp(a), _dp(nan), None) == -4
+    # empty calls succeed without touching the device
+    assert enc(None, None, 0, 4, 6, 8, _dp(a), _dp(b), None) == 0
+    assert enc(None, None, 3, 4, 6, 0, _dp(a), _dp(b), None) == 0
+
+    dec = lib.approxifer_decode
+    assert dec(fake, fake, fake, None, 1, 4, 6, 6, 3, _dp(a), _dp(b), 0, None) == -2      # S >= N
+    assert dec(fake, fake, fake, None, 1, 4, 6, -1, 3, _dp(a), _dp(b), 0, None) == -2
+    assert dec(fake, fake, fake, None, 1, 4, 6, 2, 3, _dp(a), _dp(b), 2, None) == -6
+    assert dec(fake, None, fake, None, 1, 4, 6, 2, 3, _dp(a), _dp(b), 0, None) == -1
+    assert dec(None, None, None, None, 0, 4, 6, 2, 3, _dp(a), _dp(b), 1, None) == 0
+
+    byz = lib.approxifer_decode_byzantine
+    a8, b24 = orc.chebyshev_nodes(8, 24)
+    assert byz(fake, fake, fake, fake, None, 1, 8, 24, 4, 0, 3, _dp(a8), _dp(b24), 0, None) == -2   # A < 1
+    assert byz(fake, fake, fake, fake, None, 1, 8, 24, 5, 2, 3, _dp(a8), _dp(b24), 0, None) == -5   # 19 < 20
+    assert byz(fake, fake, fake, None, None, 1, 8, 24, 4, 2, 3, _dp(a8), _dp(b24), 0, None) == -1
+    a2, b100 = orc.chebyshev_nodes(2, 100)
+    assert byz(fake, fake, fake, fake, None, 1, 2, 100, 0, 1, 3, _dp(a2), _dp(b100), 0, None) == -3  # N-S > 64
+    assert byz(None, None, None, None, None, 0, 8, 24, 4, 2, 3, _dp(a8), _dp(b24), 0, None) == 0
+
+
+def test_binding_raises_typed_error(lib):
+    with pytest.raises(binding.ApproxiferError) as e:
+        binding.approxifer_chebyshev_nodes(0, 5)
+    assert e.value.code == -2
