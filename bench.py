@@ -1,0 +1,264 @@
+#!/usr/bin/env python3
+"""Benchmark of the ApproxIFER coding layer on one MI355X.
+
+One step = one pass of the coding layer over one batch of the ImageNet-shaped workload
+(G=512 groups, K=12 queries, N=20 workers, S=8 stragglers, 3x224x224 float32 queries,
+1000-class float32 predictions): approxifer_encode on the queries, then approxifer_decode on
+the coded predictions with the group's survivor mask.  Inputs are resident in HBM before the
+timed region.  The headline value is coded queries per second over the whole step; the
+encode kernel (which moves 99.5 % of the step's bytes) carries the roofline entry.
+
+Prints ONE JSON line.  Other workloads (CIFAR-shaped, Byzantine, text) are measured after the
+timed region and reported under "other_workloads".
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def encode_bytes(w):
+    return 4 * w.D * (w.K + w.W) * w.G
+
+
+def decode_bytes(w, byzantine=False):
+    n = w.W - w.S
+    if byzantine:
+        return (4 * w.C * n + w.W + 4 * w.C * w.K + 4 * w.A) * w.G
+    return (4 * w.C * n + w.W + 4 * w.C * w.K) * w.G
+
+
+def event_ms(pairs):
+    return [a.elapsed_time(b) for a, b in pairs]
+
+
+def cpu_baseline(w, alpha, beta, budget_s, sign_mode):
+    """The float64 oracle on the host, on the leading groups of the same workload, 16 groups at a
+    time (encode, then decode of the same groups' predictions) until `budget_s` seconds of wall
+    time are spent or the workload is exhausted."""
+    import psutil
+
+    from oracle import approxifer_oracle as orc
+    from paper_2109_09868_amd import synthetic as syn
+
+    proc = psutil.Process()
+    chunk = 16
+    done = 0
+    t_enc = t_dec = cpu = 0.0
+    while done < w.G and t_enc + t_dec < budget_s:
+        g1 = min(done + chunk, w.G)
+        X = syn.queries(w, done, g1)
+        Y = syn.iid_logits(w, done, g1)
+        mask = syn.masks(w, done, g1)
+        c0 = proc.cpu_times()
+        t0 = time.perf_counter()
+        coded = orc.encode(X, alpha, beta)
+        t1 = time.perf_counter()
+        out, _ = orc.decode(Y, mask, alpha, beta, w.S, sign_mode)
+        t2 = time.perf_counter()
+        c1 = proc.cpu_times()
+        assert coded.shape[1] == w.W and out.shape[1] == w.K
+        t_enc += t1 - t0
+        t_dec += t2 - t1
+        cpu += (c1.user - c0.user) + (c1.system - c0.system)
+        done = g1
+    wall = t_enc + t_dec
+    return {
+        "value": done * w.W / wall,
+        "unit": "coded queries/s",
+        "cores": max(1, int(round(cpu / wall))),
+        "kind": "oracle",
+        "sample": "first %d of %d groups of the same workload, encode %.2f s + decode %.3f s wall, float64 numpy"
+                  % (done, w.G, t_enc, t_dec),
+        "encode_coded_queries_per_s": done * w.W / t_enc,
+        "decode_predictions_per_s": done * w.K / t_dec,
+        "host_cores_available": len(os.sched_getaffinity(0)),
+    }
+
+
+def time_launches(torch, fn, reps, warm=3):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    ms = sorted(event_ms(evs))
+    return {"avg_ms": sum(ms) / len(ms), "median_ms": ms[len(ms) // 2], "min_ms": ms[0]}
+
+
+def other_workloads(torch, binding, syn, orc_nodes, dev, sign_mode):
+    """Encode / decode / Byzantine decode on the remaining workload shapes, HIP-event timed."""
+    import numpy as np
+    res = {}
+    # -- CIFAR-shaped: encode and decode timed separately ----------------------------------
+    w = syn.WORKLOADS["cifar"]
+    alpha, beta = orc_nodes(w.K, w.W)
+    q = torch.from_numpy(syn.queries(w, threads=16)).to(dev)
+    coded = torch.empty((w.G, w.W, w.D), dtype=torch.float32, device=dev)
+    t = time_launches(torch, lambda: binding.approxifer_encode(q, alpha, beta, coded=coded), 20)
+    res["cifar_encode"] = dict(t, coded_queries_per_s=w.G * w.W / (t["avg_ms"] * 1e-3),
+                               hbm_gbs=encode_bytes(w) / (t["avg_ms"] * 1e6))
+    # predictions: the stand-in model applied on the GPU-coded queries (benchmark input only)
+    params = syn.model_params(w)
+    h = torch.relu(coded.reshape(-1, w.D) @ torch.from_numpy(params["M1"]).to(dev) + torch.from_numpy(params["b1"]).to(dev))
+    preds = (h @ torch.from_numpy(params["M2"]).to(dev) + torch.from_numpy(params["b2"]).to(dev)).reshape(w.G, w.W, w.C).contiguous()
+    mask = torch.from_numpy(syn.masks(w)).to(dev)
+    out = torch.empty((w.G, w.K, w.C), dtype=torch.float32, device=dev)
+    st = torch.empty((w.G,), dtype=torch.int32, device=dev)
+    t = time_launches(torch, lambda: binding.approxifer_decode(preds, mask, alpha, beta, w.S, sign_mode, out=out, status=st), 20)
+    res["cifar_decode"] = dict(t, predictions_per_s=w.G * w.K / (t["avg_ms"] * 1e-3),
+                               hbm_gbs=decode_bytes(w) / (t["avg_ms"] * 1e6), note="inputs stay in the last-level cache between launches")
+    del q, coded, h, preds
+
+    # -- Byzantine workload --------------------------------------------------------------------
+    w = syn.WORKLOADS["byzantine"]
+    alpha, beta = orc_nodes(w.K, w.W)
+    q = torch.from_numpy(syn.queries(w, threads=16)).to(dev)
+    coded = binding.approxifer_encode(q, alpha, beta)
+    M = torch.from_numpy(syn.model_params(w)["M"]).to(dev)
+    clean = (coded.double().reshape(-1, w.D) @ M).float().reshape(w.G, w.W, w.C).cpu().numpy()
+    mask_h = syn.masks(w)
+    adv_true = syn.adversaries(w, mask_h)
+    preds = torch.from_numpy(syn.corrupt(w, clean, adv_true)).to(dev)
+    mask = torch.from_numpy(mask_h).to(dev)
+    out = torch.empty((w.G, w.K, w.C), dtype=torch.float32, device=dev)
+    adv = torch.empty((w.G, w.A), dtype=torch.int32, device=dev)
+    st = torch.empty((w.G,), dtype=torch.int32, device=dev)
+    t = time_launches(torch, lambda: binding.approxifer_decode_byzantine(preds, mask, alpha, beta, w.S, w.A, sign_mode,
+                                                                         out=out, adv=adv, status=st), 20)
+    located = bool(np.array_equal(adv.cpu().numpy(), adv_true))
+    res["byzantine_decode"] = dict(t, predictions_per_s=w.G * w.K / (t["avg_ms"] * 1e-3),
+                                   locator_solves_per_s=w.G * w.C / (t["avg_ms"] * 1e-3),
+                                   hbm_gbs=decode_bytes(w, True) / (t["avg_ms"] * 1e6),
+                                   planted_adversaries_located=located)
+    del q, coded
+
+    # -- text shapes: encode only (decode there moves < 1 MB) -----------------------------------
+    for name in ("text", "text_k32"):
+        w = syn.WORKLOADS[name]
+        alpha, beta = orc_nodes(w.K, w.W)
+        q = torch.empty((w.G, w.K, w.D), dtype=torch.float32, device=dev)
+        for g0 in range(0, w.G, 128):
+            q[g0:g0 + 128] = torch.from_numpy(syn.queries(w, g0, g0 + 128, threads=16)).to(dev)
+        coded = torch.empty((w.G, w.W, w.D), dtype=torch.float32, device=dev)
+        t = time_launches(torch, lambda: binding.approxifer_encode(q, alpha, beta, coded=coded), 10, warm=2)
+        res[name + "_encode"] = dict(t, coded_queries_per_s=w.G * w.W / (t["avg_ms"] * 1e-3),
+                                     hbm_gbs=encode_bytes(w) / (t["avg_ms"] * 1e6),
+                                     fp32_tflops=2.0 * w.K * w.W * w.D * w.G / (t["avg_ms"] * 1e9))
+        del q, coded
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--sign-mode", type=int, default=0, choices=[0, 1])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other", action="store_true", help="skip the other workload shapes")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="wall-time budget of the CPU-oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2109_09868_amd import binding, synthetic as syn
+
+    binding.load()                       # raises if the HIP library is not built
+    dev = torch.device("cuda:0")
+    w = syn.WORKLOADS["imagenet"]
+    alpha, beta = binding.approxifer_chebyshev_nodes(w.K, w.W)
+
+    # ---- inputs, resident in HBM before timing ----------------------------------------------
+    queries = torch.empty((w.G, w.K, w.D), dtype=torch.float32, device=dev)
+    for g0 in range(0, w.G, 64):
+        queries[g0:g0 + 64] = torch.from_numpy(syn.queries(w, g0, g0 + 64, threads=16)).to(dev)
+    preds = torch.from_numpy(syn.iid_logits(w)).to(dev)
+    mask = torch.from_numpy(syn.masks(w)).to(dev)
+    coded = torch.empty((w.G, w.W, w.D), dtype=torch.float32, device=dev)
+    out = torch.empty((w.G, w.K, w.C), dtype=torch.float32, device=dev)
+    status = torch.empty((w.G,), dtype=torch.int32, device=dev)
+
+    def step(ev=None):
+        if ev is not None:
+            ev[0].record()
+        binding.approxifer_encode(queries, alpha, beta, coded=coded)
+        if ev is not None:
+            ev[1].record()
+        binding.approxifer_decode(preds, mask, alpha, beta, w.S, args.sign_mode, out=out, status=status)
+        if ev is not None:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(evs[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    assert int(status.sum().item()) == 0
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    enc_ms = event_ms([(e[0], e[1]) for e in evs])
+    dec_ms = event_ms([(e[1], e[2]) for e in evs])
+    enc_avg = sum(enc_ms) / len(enc_ms)
+    dec_avg = sum(dec_ms) / len(dec_ms)
+    achieved = encode_bytes(w) / (enc_avg * 1e6)          # GB/s
+
+    result = {
+        "metric": "coded queries/s + decoded predictions/s per GPU; achieved HBM GB/s vs peak",
+        "value": w.G * w.W / (ms_per_step * 1e-3),
+        "unit": "coded queries/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "imagenet-shaped: G=512 K=12 N=20 S=8 D=3x224x224 C=1000, encode + decode per step",
+                   "G": w.G, "K": w.K, "N": w.W, "S": w.S, "A": 0, "D": w.D, "C": w.C,
+                   "sign_mode": args.sign_mode, "nodes": "chebyshev first kind (queries) / second kind (workers)"},
+        "decoded_predictions_per_s": w.G * w.K / (ms_per_step * 1e-3),
+        "encode": {"avg_ms": enc_avg, "min_ms": min(enc_ms), "coded_queries_per_s": w.G * w.W / (enc_avg * 1e-3),
+                   "hbm_gbs": achieved, "fp32_tflops": 2.0 * w.K * w.W * w.D * w.G / (enc_avg * 1e9)},
+        "decode": {"avg_ms": dec_avg, "min_ms": min(dec_ms), "predictions_per_s": w.G * w.K / (dec_avg * 1e-3),
+                   "hbm_gbs": decode_bytes(w) / (dec_avg * 1e6)},
+        "roofline": {"bound": "hbm", "kernel": "encode_kernel<12,4,1>", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": encode_bytes(w)},
+    }
+    if not args.no_other:
+        result["other_workloads"] = other_workloads(torch, binding, syn, binding.approxifer_chebyshev_nodes, dev,
+                                                    args.sign_mode)
+    del queries, coded
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, alpha, beta, args.cpu_seconds, args.sign_mode)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
