@@ -246,7 +246,7 @@ def main():
                    "hbm_gbs": achieved, "fp32_tflops": 2.0 * w.K * w.W * w.D * w.G / (enc_avg * 1e9)},
         "decode": {"avg_ms": dec_avg, "min_ms": min(dec_ms), "predictions_per_s": w.G * w.K / (dec_avg * 1e-3),
                    "hbm_gbs": decode_bytes(w) / (dec_avg * 1e6)},
-        "roofline": {"bound": "hbm", "kernel": "encode_kernel<12,4,1>", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "encode_kernel<12,4>", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "algorithmic_bytes_per_launch": encode_bytes(w)},
     }

@@ -20,11 +20,48 @@ struct Nodes {
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v2f __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+// ---- wavefront reductions -------------------------------------------------------------
+// Data-parallel-primitive (DPP) lane exchanges inside a row of 16 lanes; no LDS round trip.
+constexpr int kDppQuadXor1 = 0xB1;       // quad_perm:[1,0,3,2]
+constexpr int kDppQuadXor2 = 0x4E;       // quad_perm:[2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141; // lane i <-> 7-i inside each half row
+constexpr int kDppRowMirror = 0x140;     // lane i <-> 15-i inside each row
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_exchange(double v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double read_lane(double v, int lane) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+    return __hiloint2double(hi, lo);
+}
+
+// Sum of v over each aligned group of 16 lanes, returned in every lane of the group.
+// Fixed association: ((x0+x1)+(x2+x3)) + ((x4+x5)+(x6+x7)) ... as a butterfly.
+__device__ __forceinline__ double row16_sum(double v) {
+    v += dpp_exchange<kDppQuadXor1>(v);
+    v += dpp_exchange<kDppQuadXor2>(v);
+    v += dpp_exchange<kDppRowHalfMirror>(v);   // quads are uniform by now: adds the other quad of the half row
+    v += dpp_exchange<kDppRowMirror>(v);       // half rows are uniform: adds the other half row
     return v;
 }
+
+// Sum over each aligned group of WIDTH lanes (16, 32 or 64), returned in every lane of the group.
+template <int WIDTH>
+__device__ __forceinline__ double group_sum(double v) {
+    static_assert(WIDTH == 16 || WIDTH == 32 || WIDTH == 64, "group width");
+    v = row16_sum(v);
+    if (WIDTH == 16) return v;
+    const double r0 = read_lane(v, 0), r1 = read_lane(v, 16), r2 = read_lane(v, 32), r3 = read_lane(v, 48);
+    if (WIDTH == 32) return (threadIdx.x & 32) ? (r2 + r3) : (r0 + r1);
+    return (r0 + r1) + (r2 + r3);
+}
+
+__device__ __forceinline__ double wave_sum(double v) { return group_sum<64>(v); }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
