@@ -25,6 +25,28 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
+# HBM traffic of one encode launch at the imagenet shape, from two rocprofv3 --pmc runs
+# (profiles/encode_imagenet_hbm_counters.md).  Valid only for the kernel sources hashed here.
+ENCODE_KERNEL_SOURCES = ("paper_2109_09868_amd/csrc/encode.hip", "paper_2109_09868_amd/csrc/common.h")
+ENCODE_TRAFFIC = {
+    "sources_sha256": "0485ce661586c31a50c0ea0ad36afc77ac0479b4d20a7f85a8987fca6c199a15",
+    "fetch_size_kib": 1806386.5, "fetch_factor": 2.0000,     # counter reads half the bytes of a known copy
+    "write_size_kib": 6022434.6, "write_factor": 1.0000,
+}
+
+
+def measured_traffic_bytes():
+    """Counter-derived HBM bytes per encode launch, or None if the kernel changed since they were taken."""
+    import hashlib
+    h = hashlib.sha256()
+    for rel in ENCODE_KERNEL_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    if h.hexdigest() != ENCODE_TRAFFIC["sources_sha256"]:
+        return None
+    t = ENCODE_TRAFFIC
+    return 1024.0 * (t["fetch_size_kib"] * t["fetch_factor"] + t["write_size_kib"] * t["write_factor"])
+
 
 def encode_bytes(w):
     return 4 * w.D * (w.K + w.W) * w.G
@@ -247,7 +269,7 @@ def main():
         "decode": {"avg_ms": dec_avg, "min_ms": min(dec_ms), "predictions_per_s": w.G * w.K / (dec_avg * 1e-3),
                    "hbm_gbs": decode_bytes(w) / (dec_avg * 1e6)},
         "roofline": {"bound": "hbm", "kernel": "encode_kernel<12,4>", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic_bytes(),
                      "algorithmic_bytes_per_launch": encode_bytes(w)},
     }
     if not args.no_other:
