@@ -40,6 +40,14 @@ __device__ __forceinline__ double read_lane(double v, int lane) {
     return __hiloint2double(hi, lo);
 }
 
+// Marks a wave-uniform value as such (it then lives in scalar registers, and a load that
+// produces it stays a scalar load instead of being merged into a per-lane address select).
+__device__ __forceinline__ double wave_uniform(double v) {
+    const int lo = __builtin_amdgcn_readfirstlane(__double2loint(v));
+    const int hi = __builtin_amdgcn_readfirstlane(__double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+
 // Sum of v over each aligned group of 16 lanes, returned in every lane of the group.
 // Fixed association: ((x0+x1)+(x2+x3)) + ((x4+x5)+(x6+x7)) ... as a butterfly.
 __device__ __forceinline__ double row16_sum(double v) {
