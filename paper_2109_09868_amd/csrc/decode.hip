@@ -6,13 +6,16 @@
 // wavefront reduction) and kept transposed in LDS, and the contraction over F accumulates
 // in float64 with the weights broadcast from LDS.  Rows of missing workers are never read.
 //
-// Byzantine decoder: one workgroup per group.  Each wave takes classes c = wave, wave+nw, ..
-// and runs Algorithm 2 on them: lane r owns row r of the (N-S) x (2(K+A)-1) system, a
-// Householder QR is applied column by column (row-private storage in LDS, column norms and
-// dot products by wavefront reductions), the Q coefficients come out of the back
-// substitution and are folded into a_r = Q(x_r) by Horner's rule as they appear.  The A
-// smallest |a_r| vote; after the vote the adversaries are removed from the available list
-// and the workgroup decodes the group as above.
+// Byzantine decoder: one workgroup per group.  Algorithm 2 runs on several classes per wave:
+// a class owns 2(K+A) neighbouring lanes, lane j of a class owns COLUMN j of its
+// (N-S) x (2(K+A)-1) system (the last lane owns the right-hand side), and the matrix sits in
+// LDS row-major so that the lanes of a class touch consecutive addresses.  A Householder step
+// then needs no cross-lane reduction at all: every lane walks down the pivot column (an LDS
+// broadcast) accumulating the column norm and its own dot product, and updates its own
+// column.  The Q coefficients come out of a back substitution restricted to the trailing
+// block, a_r = Q(x_r) is evaluated by Horner's rule with one lane per row, the A smallest
+// |a_r| vote; after the vote the adversaries are removed from the available list and the
+// workgroup decodes the group as above.
 #include "common.h"
 
 namespace approxifer {
@@ -167,74 +170,134 @@ __global__ void decode_kernel(const float *__restrict__ preds, const uint8_t *__
 // ------------------------------------------------------------------------------------
 // Byzantine decoder kernel
 // ------------------------------------------------------------------------------------
-// Algorithm 2, steps 1-3 for one class, by one wave.  Lane r < n owns row r:
-// x = beta of its worker, y = its prediction for the class.  `mat` is this wave's LDS
-// scratch of (2M) columns of n doubles, column-major; a lane only ever touches its own row.
-// Returns a_r = Q(x_r) on lanes r < n.
-__device__ __forceinline__ double locator_values_wave(double *mat, int n, int M, double x, double y, bool row) {
+// Algorithm 2, steps 1-5, for the classes c0 .. c0+cpw-1 of one group, by one wave.
+//   n        available workers (rows), M = K + A, W2 = 2M columns including the right-hand side
+//   xs[n]    worker nodes of the available workers (LDS, shared by the workgroup)
+//   scratch  this wave's LDS: per class  mat[n][W2] | coef[M] | key[n]
+// Lane (cl, j) = (lane / W2, lane % W2) works on class c0 + cl; lanes beyond cpw classes idle.
+// Votes for the A smallest |Q(x_r)| of every class are added to votes[worker].
+__device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg, int64_t C, int64_t c0, int cpw,
+                                                    const int *avail, const double *xs, int n, int M, int A,
+                                                    double *scratch, int *votes) {
     const int lane = lane_id();
-    const int cols = 2 * M - 1;   // unknowns P_0..P_{M-1}, Q_1..Q_{M-1}; column `cols` is the right-hand side
+    const int W2 = 2 * M;
+    const int cols = W2 - 1;                 // unknowns P_0..P_{M-1}, Q_1..Q_{M-1}; column `cols` is the rhs
+    const int cl = lane / W2;
+    const int j = lane - cl * W2;
+    const int64_t c = c0 + cl;
+    const bool live = cl < cpw && c < C;     // this lane's class exists
+    const int per_class = n * W2 + M + n;
+    double *mat = scratch + (live ? cl : 0) * per_class;
+    double *coef = mat + n * W2;
+    double *key = coef + M;
 
-    if (row) {
-        double p = 1.0;
-        for (int k = 0; k < M; ++k) {
-            mat[k * n + lane] = p;                            // x^k
-            if (k >= 1) mat[(M - 1 + k) * n + lane] = -y * p; // -y x^k
-            p *= x;
+    // ---- steps 1-2: the system, one lane per row (rows j, j+W2, ..) -------------------
+    if (live) {
+        for (int r = j; r < n; r += W2) {
+            const double x = xs[r];
+            const double y = static_cast<double>(pg[static_cast<size_t>(avail[r]) * C + c]);
+            double *row = mat + r * W2;
+            double p = 1.0;
+            for (int k = 0; k < M; ++k) {
+                row[k] = p;                               // x^k
+                if (k >= 1) row[M - 1 + k] = -y * p;      // -y x^k
+                p *= x;
+            }
+            row[cols] = y;
         }
-        mat[cols * n + lane] = y;
     }
+    __builtin_amdgcn_wave_barrier();
 
-    // Householder QR, least-squares form: reflect column k onto e_k using rows k..n-1 and
-    // apply the reflector to the columns right of it and to the right-hand side.
-    double diag = 0.0;   // R[lane][lane] once column `lane` is done
+    // ---- Householder QR in least-squares form, one lane per column ---------------------
+    // Step k reflects column k onto e_k over rows k..n-1 and applies the reflector to the
+    // columns right of it (and to the right-hand side).
     for (int k = 0; k < cols; ++k) {
-        const bool active = row && lane >= k;
-        const double xk = active ? mat[k * n + lane] : 0.0;
-        const double sigma = wave_sum(xk * xk);
-        const double xkk = __shfl(xk, k, kWave);
-        if (sigma == 0.0) continue;   // wave-uniform
+        double sigma = 0.0, d = 0.0;
+#pragma unroll 4
+        for (int r = k; r < n; ++r) {
+            const double vr = mat[r * W2 + k];            // broadcast inside the class
+            const double arj = mat[r * W2 + j];
+            sigma = fma(vr, vr, sigma);
+            d = fma(vr, arj, d);
+        }
+        const double xkk = mat[k * W2 + k];
+        const double akj = mat[k * W2 + j];
+        const bool degenerate = !(sigma > 0.0);
         const double nrm = sqrt(sigma);
         const double alpha = (xkk >= 0.0) ? -nrm : nrm;
-        const double v = (lane == k) ? xk - alpha : xk;
-        const double scale = 1.0 / (sigma - alpha * xkk);   // 2 / (v^T v)
-        for (int j = k + 1; j <= cols; ++j) {
-            const double aj = active ? mat[j * n + lane] : 0.0;
-            const double d = wave_sum(v * aj);
-            if (active) mat[j * n + lane] = aj - (scale * d) * v;
+        const double scale = 1.0 / (sigma - alpha * xkk);   // 2 / (v^T v), v = x - alpha e_k
+        const double f = scale * (d - alpha * akj);          // 2 v^T a_j / (v^T v)
+        __builtin_amdgcn_wave_barrier();
+        if (live && !degenerate) {
+            if (j > k) {
+#pragma unroll 4
+                for (int r = k; r < n; ++r) {
+                    const double vr = (r == k) ? xkk - alpha : mat[r * W2 + k];
+                    mat[r * W2 + j] = fma(-f, vr, mat[r * W2 + j]);
+                }
+            } else if (j == k) {
+                mat[k * W2 + k] = alpha;                  // R[k][k]
+            }
         }
-        if (lane == k) diag = alpha;
+        __builtin_amdgcn_wave_barrier();
     }
 
-    // Back substitution for Q_{M-1} .. Q_1 (unknowns cols-1 .. M); P is not needed.
-    double s = row ? mat[cols * n + lane] : 0.0;
-    double a = 0.0;
-    for (int j = cols - 1; j >= M; --j) {
-        const double sol = __shfl(s / diag, j, kWave);
-        if (row && lane < j) s -= mat[j * n + lane] * sol;
-        a = a * x + sol;
+    // ---- back substitution for Q_{M-1} .. Q_1 (unknowns cols-1 .. M); P is not needed ----
+    // lane j holds the transformed right-hand side entry of row j.
+    double s = (live && j < cols) ? mat[j * W2 + cols] : 0.0;
+    const double diag = (live && j < cols) ? mat[j * W2 + j] : 1.0;
+    for (int t = cols - 1; t >= M; --t) {
+        if (live && j == t) coef[t - M] = s / diag;       // Q_{t-M+1}
+        __builtin_amdgcn_wave_barrier();
+        const double sol = coef[t - M];
+        if (live && j < t) s = fma(-mat[j * W2 + t], sol, s);
+        __builtin_amdgcn_wave_barrier();
     }
-    return a * x + 1.0;   // Q_0 = 1
+
+    // ---- step 3: a_r = Q(x_r), Horner, one lane per row; steps 4-5: the A smallest |a_r| ----
+    if (live) {
+        for (int r = j; r < n; r += W2) {
+            const double x = xs[r];
+            double a = 0.0;
+            for (int t = cols - 1; t >= M; --t) a = fma(a, x, coef[t - M]);
+            a = fma(a, x, 1.0);                           // Q_0 = 1
+            key[r] = (a != a) ? __builtin_inf() : fabs(a);
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    if (live) {
+        for (int r = j; r < n; r += W2) {
+            const double mine = key[r];
+            int rank = 0;                                  // equal magnitudes keep ascending worker order
+            for (int o = 0; o < n; ++o) {
+                const double other = key[o];
+                rank += (other < mine || (other == mine && o < r)) ? 1 : 0;
+            }
+            if (rank < A) atomicAdd(&votes[avail[r]], 1);
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
 }
 
-// dynamic LDS: double mats[nw][2M * n] | double WdT[(n-A) * KP] | int avail[N] | int F[N] | int votes[N]
-//              | int sel[N] | int n
+// dynamic LDS: double scratch[nw][cpw * (n*2M + M + n)] | double WdT[(n-A) * KP] | double xs[n]
+//              | int avail[N] | int F[N] | int votes[N] | int sel[N] | int n
 template <int VEC>
 __global__ void decode_byzantine_kernel(const float *__restrict__ preds, const uint8_t *__restrict__ mask,
                                         float *__restrict__ out, int32_t *__restrict__ adv,
                                         int32_t *__restrict__ status, int K, int N, int S, int A, int64_t C,
-                                        int64_t Cv, int sign_mode, const Nodes nodes) {
+                                        int64_t Cv, int sign_mode, int cpw, const Nodes nodes) {
     extern __shared__ double lds_d[];
     const int KP = round_up4(K);
     const int M = K + A;
     const int n_expected = N - S;
     const int nF = n_expected - A;
     const int nw = blockDim.x / kWave;
-    const int mat_doubles = 2 * M * n_expected;
+    const int wave_doubles = cpw * (n_expected * 2 * M + M + n_expected);
 
-    double *mats = lds_d;
-    double *WdT = mats + static_cast<size_t>(nw) * mat_doubles;
-    int *avail = reinterpret_cast<int *>(WdT + nF * KP);
+    double *scratch = lds_d;
+    double *WdT = scratch + static_cast<size_t>(nw) * wave_doubles;
+    double *xs = WdT + nF * KP;
+    int *avail = reinterpret_cast<int *>(xs + n_expected);
     int *F = avail + N;
     int *votes = F + N;
     int *sel = votes + N;
@@ -258,24 +321,10 @@ __global__ void decode_byzantine_kernel(const float *__restrict__ preds, const u
     if (!good) return;
 
     // ---- Algorithm 2: per-class fit, pick, vote ---------------------------------------
-    {
-        const bool row = lane < n;
-        const int worker = row ? avail[lane] : 0;
-        const double x = nodes.beta[worker];
-        double *mat = mats + static_cast<size_t>(wv) * mat_doubles;
-        for (int64_t c = wv; c < C; c += nw) {
-            const double y = row ? static_cast<double>(pg[static_cast<size_t>(worker) * C + c]) : 0.0;
-            const double a = locator_values_wave(mat, n, M, x, y, row);
-            // steps 4-5: the A smallest |a|; equal magnitudes keep ascending worker order
-            const double key = (!row || a != a) ? __builtin_inf() : fabs(a);
-            int rank = 0;
-            for (int r = 0; r < n; ++r) {
-                const double other = __shfl(key, r, kWave);
-                rank += (other < key || (other == key && r < lane)) ? 1 : 0;
-            }
-            if (row && rank < A) atomicAdd(&votes[worker], 1);
-        }
-    }
+    for (int r = threadIdx.x; r < n; r += blockDim.x) xs[r] = nodes.beta[avail[r]];
+    __syncthreads();
+    for (int64_t c0 = static_cast<int64_t>(wv) * cpw; c0 < C; c0 += static_cast<int64_t>(nw) * cpw)
+        locate_classes_wave(pg, C, c0, cpw, avail, xs, n, M, A, scratch + static_cast<size_t>(wv) * wave_doubles, votes);
     __syncthreads();
 
     // ---- the A most voted workers (equal counts: smaller index first), ascending -------
@@ -354,22 +403,28 @@ int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *
     const int64_t Cv = vec4 ? C / 4 : C;
     if (G > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
 
-    const size_t fixed = sizeof(double) * static_cast<size_t>(n - A) * KP + sizeof(int) * (4 * static_cast<size_t>(N) + 2);
-    const size_t per_wave = sizeof(double) * 2 * static_cast<size_t>(M) * n;
+    // classes per wave: a class takes 2M lanes; waves per workgroup: enough for all classes, at most 4
+    int cpw = kWave / (2 * M);
+    if (cpw < 1) cpw = 1;
+    if (cpw > C) cpw = static_cast<int>(C);
+    const size_t fixed = sizeof(double) * (static_cast<size_t>(n - A) * KP + n) + sizeof(int) * (4 * static_cast<size_t>(N) + 2);
+    const size_t per_class = sizeof(double) * (static_cast<size_t>(n) * 2 * M + M + n);
     const size_t budget = 64 * 1024;
+    while (cpw > 1 && fixed + cpw * per_class > budget) --cpw;
+    const size_t per_wave = cpw * per_class;
     if (fixed + per_wave > budget) return APPROXIFER_ERR_LIMIT;
-    int nw = static_cast<int>((budget - fixed) / per_wave);
-    if (nw > 8) nw = 8;
-    if (nw > C) nw = static_cast<int>(C);
+    int nw = static_cast<int>((C + cpw - 1) / cpw);
+    if (nw > 4) nw = 4;
+    if (nw > static_cast<int>((budget - fixed) / per_wave)) nw = static_cast<int>((budget - fixed) / per_wave);
     if (nw < 1) nw = 1;
     const size_t lds = fixed + nw * per_wave;
     const dim3 grid(static_cast<unsigned>(G)), block(nw * kWave);
     if (vec4)
         hipLaunchKernelGGL(decode_byzantine_kernel<4>, grid, block, lds, stream, d_preds, d_mask, d_out, d_adv,
-                           d_status, K, N, S, A, C, Cv, sign_mode, nodes);
+                           d_status, K, N, S, A, C, Cv, sign_mode, cpw, nodes);
     else
         hipLaunchKernelGGL(decode_byzantine_kernel<1>, grid, block, lds, stream, d_preds, d_mask, d_out, d_adv,
-                           d_status, K, N, S, A, C, Cv, sign_mode, nodes);
+                           d_status, K, N, S, A, C, Cv, sign_mode, cpw, nodes);
     return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
 }
 

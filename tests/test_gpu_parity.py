@@ -417,3 +417,62 @@ def test_byzantine_nonlinear_model_votes(gpu):
     same = np.all(adv == adv_ref, axis=1)
     assert same.mean() >= 0.97
     assert group_err(out[same], ref[same]).max() <= TOL
+
+
+# --------------------------------------------------------------------------------------
+# the paper's own operating points (Section 4.2; Appendix B), on synthetic stand-in data
+# --------------------------------------------------------------------------------------
+@pytest.mark.parametrize("K", [8, 10, 12])
+@pytest.mark.parametrize("S", [1, 2, 3])
+@pytest.mark.parametrize("shape", [(1, 28, 28), (3, 32, 32)])
+def test_straggler_operating_points(gpu, K, S, shape):
+    # K = 8, 10, 12 queries with S = 1, 2, 3 stragglers (N = K + S workers), 10 classes, MNIST- and
+    # CIFAR-sized queries: encode, a non-linear stand-in model, every single mask decoded in both modes
+    torch, binding, dev = gpu
+    N, C, G = K + S, 10, 24
+    D = int(np.prod(shape))
+    rng = np.random.default_rng(K * 10 + S + D)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    X = rng.uniform(0, 1, (G, K, D)).astype(np.float32)
+    coded = binding.approxifer_encode(torch.from_numpy(X).to(dev), alpha, beta).cpu().numpy()
+    ref_coded = orc.encode(X, alpha, beta)
+    assert group_err(coded, ref_coded).max() <= TOL
+    Mf = rng.standard_normal((D, C)) * (4.0 / np.sqrt(D))
+    z = ref_coded @ Mf
+    Y = (np.exp(z - z.max(-1, keepdims=True)) / np.exp(z - z.max(-1, keepdims=True)).sum(-1, keepdims=True)).astype(np.float32)
+    mask = np.zeros((G, N), np.uint8)
+    for g in range(G):
+        mask[g, rng.permutation(N)[:K]] = 1
+    for mode in (0, 1):
+        out, st, ref, st_ref = _decode_both(gpu, Y, mask, alpha, beta, S, mode)
+        assert np.all(st == 0) and np.array_equal(st, st_ref)
+        assert group_err(out, ref).max() <= TOL
+        # top-1 decisions, the paper's accuracy metric, agree wherever the oracle's margin is not a rounding tie
+        top2 = np.sort(ref, axis=-1)[..., -2:]
+        clear = (top2[..., 1] - top2[..., 0]) > 1e-4 * np.abs(ref).max()
+        assert np.array_equal(out.argmax(-1)[clear], ref.argmax(-1)[clear])
+
+
+@pytest.mark.parametrize("E", [1, 2, 3])
+@pytest.mark.parametrize("sigma", [1.0, 10.0, 100.0])
+def test_byzantine_operating_points(gpu, E, sigma):
+    # K = 12, S = 0, E = 1, 2, 3 adversaries adding zero-mean Gaussian noise of scale sigma = 1, 10, 100
+    # (Section 4.2 "Byzantine-Robustness", Appendix B); N = 2(K + E) workers, 10 classes, linear stand-in model
+    K, S, C, G = 12, 0, 10, 32
+    N = 2 * (K + E)
+    rng = np.random.default_rng(1000 * E + int(sigma))
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    X = rng.uniform(0, 1, (G, K, 784))
+    Mf = rng.standard_normal((784, C)) / 28.0
+    clean = (orc.encode(X, alpha, beta) @ Mf).astype(np.float32)
+    mask = np.ones((G, N), np.uint8)
+    adv_true = np.zeros((G, E), np.int32)
+    Y = clean.copy()
+    for g in range(G):
+        adv_true[g] = np.sort(rng.permutation(N)[:E])
+        Y[g, adv_true[g]] += (sigma * rng.standard_normal((E, C))).astype(np.float32)
+    out, adv, st, ref, adv_ref, st_ref = _byz_both(gpu, Y, mask, alpha, beta, S, E)
+    assert np.all(st == 0)
+    assert np.array_equal(adv, adv_ref)
+    assert np.array_equal(adv, adv_true)
+    assert group_err(out, ref).max() <= TOL
