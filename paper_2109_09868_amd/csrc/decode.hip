@@ -43,12 +43,38 @@ __device__ __forceinline__ int survivors_from_mask(const uint8_t *__restrict__ m
 // Transposed decoder weights WdT[r*KP + j] = l_{F_r}(alpha_j), Section 3 "ApproxIFER Decoding"
 // step 2.  Called by the whole workgroup after F is visible; the caller provides a barrier
 // afterwards.  WdT must have been zeroed for the pad columns j in [K, KP).
-__device__ __forceinline__ void decoder_weights(const Nodes &nodes, const int *F, int nF, int K, int KP,
-                                                int sign_mode, double *WdT) {
+// Up to 64 survivors: a group of LPR = 16/32/64 lanes per query node, several nodes per pass.
+template <int LPR>
+__device__ __forceinline__ void decoder_weights_grouped(const double *alpha_s, const double *beta_s, const int *F, int nF, int K, int KP,
+                                                        int sign_mode, double *WdT) {
+    const int tid = threadIdx.x;
+    const int r = tid % LPR;
+    const int sub = tid / LPR;
+    const int rows_per_pass = blockDim.x / LPR;
+    const bool valid = r < nF;
+    const int i = valid ? F[r] : 0;
+    const double xb = beta_s[i];
+    const int parity = (sign_mode == APPROXIFER_SIGN_WORKER_INDEX) ? (i & 1) : (r & 1);
+    const double sign = parity ? -1.0 : 1.0;
+    const unsigned long long group_mask =
+        (LPR == 64) ? ~0ull : ((1ull << (LPR & 63)) - 1ull) << ((tid & 63) / LPR * LPR);
+    for (int j0 = 0; j0 < K; j0 += rows_per_pass) {
+        const int j = j0 + sub;
+        const bool row = j < K;
+        const BerrutTerm bt = berrut_term(alpha_s[row ? j : 0], xb, sign, valid && row);
+        const double rden = 1.0 / group_sum<LPR>(bt.t);
+        const bool any_hit = (__ballot(bt.hit) & group_mask) != 0ull;
+        if (valid && row) WdT[r * KP + j] = any_hit ? (bt.hit ? 1.0 : 0.0) : bt.t * rden;
+    }
+}
+
+// More than 64 survivors: one wave per query node, two lanes-worth of survivors per lane.
+__device__ __forceinline__ void decoder_weights_wide(const double *alpha_s, const double *beta_s, const int *F, int nF, int K, int KP,
+                                                     int sign_mode, double *WdT) {
     const int lane = lane_id();
     const int nwaves = blockDim.x / kWave;
     for (int j = wave_id(); j < K; j += nwaves) {
-        const double z = nodes.alpha[j];
+        const double z = alpha_s[j];
         BerrutTerm bt[2];
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
@@ -56,15 +82,33 @@ __device__ __forceinline__ void decoder_weights(const Nodes &nodes, const int *F
             const bool valid = r < nF;
             const int i = valid ? F[r] : 0;
             const int parity = (sign_mode == APPROXIFER_SIGN_WORKER_INDEX) ? (i & 1) : (r & 1);
-            bt[p] = berrut_term(z, nodes.beta[i], parity ? -1.0 : 1.0, valid);
+            bt[p] = berrut_term(z, beta_s[i], parity ? -1.0 : 1.0, valid);
         }
-        const double den = wave_sum(bt[0].t + bt[1].t);
+        const double rden = 1.0 / wave_sum(bt[0].t + bt[1].t);
         const bool any_hit = (__ballot(bt[0].hit) | __ballot(bt[1].hit)) != 0ull;
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             const int r = p * kWave + lane;
-            if (r < nF) WdT[r * KP + j] = any_hit ? (bt[p].hit ? 1.0 : 0.0) : bt[p].t / den;
+            if (r < nF) WdT[r * KP + j] = any_hit ? (bt[p].hit ? 1.0 : 0.0) : bt[p].t * rden;
         }
+    }
+}
+
+__device__ __forceinline__ void decoder_weights(const double *alpha_s, const double *beta_s, const int *F, int nF, int K, int KP,
+                                                int sign_mode, double *WdT) {
+    if (nF <= 16) decoder_weights_grouped<16>(alpha_s, beta_s, F, nF, K, KP, sign_mode, WdT);
+    else if (nF <= 32) decoder_weights_grouped<32>(alpha_s, beta_s, F, nF, K, KP, sign_mode, WdT);
+    else if (nF <= 64) decoder_weights_grouped<64>(alpha_s, beta_s, F, nF, K, KP, sign_mode, WdT);
+    else decoder_weights_wide(alpha_s, beta_s, F, nF, K, KP, sign_mode, WdT);
+}
+
+// The nodes arrive in the kernel-argument segment; the decoders index them per lane, so every
+// workgroup first copies them to LDS (alpha_s[K], beta_s[N]) with one load per thread, issued
+// together with the mask load instead of later in the dependency chain.
+__device__ __forceinline__ void stage_nodes(const Nodes &nodes, int K, int N, double *alpha_s, double *beta_s) {
+    for (int t = threadIdx.x; t < K + N; t += blockDim.x) {
+        if (t < K) alpha_s[t] = nodes.alpha[t];
+        else beta_s[t - K] = nodes.beta[t - K];
     }
 }
 
@@ -89,13 +133,31 @@ template <> __device__ __forceinline__ void store_row<1>(float *dst, const doubl
     *dst = static_cast<float>(acc[0]);
 }
 
+constexpr int kRowChunk = 8;   // prediction rows a lane keeps in flight at once
+
+// Loads of one chunk of surviving rows for one vector column.  Rows past the end of F are
+// clamped to the last survivor (always a valid address); their values are never used.
+template <int VEC>
+__device__ __forceinline__ void load_row_chunk(const float *__restrict__ pg, const int *F, int nF, int r0, int64_t C,
+                                               int64_t cv, typename PredVec<VEC>::type (&y)[kRowChunk]) {
+    typedef typename PredVec<VEC>::type V;
+#pragma unroll
+    for (int u = 0; u < kRowChunk; ++u) {
+        const int r = (r0 + u < nF) ? r0 + u : nF - 1;
+        y[u] = *reinterpret_cast<const V *>(pg + static_cast<size_t>(F[r]) * C + cv * VEC);
+    }
+}
+
 // out[g][j][c] = sum_r WdT[r][j] * preds[g][F_r][c] for the vector columns [cv0, cv1) of one
 // group.  Work items are (quad of query rows, vector column); a wave shares its quad, so the
-// weight reads are LDS broadcasts.  float64 accumulation, one rounding on store.
-template <int VEC>
+// weight reads are LDS broadcasts.  Rows are fetched kRowChunk at a time so that a lane has
+// that many loads in flight; float64 accumulation, one rounding on store.
+// PREFETCHED: the caller already issued the first chunk of this lane's first item into `first`
+// (before it evaluated the weights, to overlap the two).
+template <int VEC, bool PREFETCHED>
 __device__ __forceinline__ void contract_tile(const float *__restrict__ pg, float *__restrict__ og, const int *F,
                                               int nF, int K, int KP, int64_t C, int64_t cv0, int64_t cv1,
-                                              const double *WdT) {
+                                              const double *WdT, typename PredVec<VEC>::type (&first)[kRowChunk]) {
     typedef typename PredVec<VEC>::type V;
     const int KQ = KP / 4;
     const int items = KQ * kColsPerTile;
@@ -108,22 +170,32 @@ __device__ __forceinline__ void contract_tile(const float *__restrict__ pg, floa
         for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc[jj][e] = 0.0;
-        for (int r = 0; r < nF; ++r) {
-            const V y = *reinterpret_cast<const V *>(pg + static_cast<size_t>(F[r]) * C + cv * VEC);
-            const double *w = WdT + r * KP + 4 * q;
+        for (int r0 = 0; r0 < nF; r0 += kRowChunk) {
+            V y[kRowChunk];
+            if (PREFETCHED && r0 == 0 && it == static_cast<int>(threadIdx.x)) {
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                const double wj = w[jj];
+                for (int u = 0; u < kRowChunk; ++u) y[u] = first[u];
+            } else {
+                load_row_chunk<VEC>(pg, F, nF, r0, C, cv, y);
+            }
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) acc[jj][e] = fma(wj, static_cast<double>(vec_get<VEC>(y, e)), acc[jj][e]);
+            for (int u = 0; u < kRowChunk; ++u) {
+                if (r0 + u < nF) {
+                    const double *w = WdT + (r0 + u) * KP + 4 * q;
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) {
+                        const double wj = w[jj];
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e)
+                            acc[jj][e] = fma(wj, static_cast<double>(vec_get<VEC>(y[u], e)), acc[jj][e]);
+                    }
+                }
             }
         }
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int j = 4 * q + jj;
-            if (j < K) {
-                store_row<VEC>(og + static_cast<size_t>(j) * C + cv * VEC, acc[jj]);
-            }
+            if (j < K) store_row<VEC>(og + static_cast<size_t>(j) * C + cv * VEC, acc[jj]);
         }
     }
 }
@@ -131,7 +203,7 @@ __device__ __forceinline__ void contract_tile(const float *__restrict__ pg, floa
 // ------------------------------------------------------------------------------------
 // decoder kernel
 // ------------------------------------------------------------------------------------
-// dynamic LDS: double WdT[(N-S) * KP] | int F[N] | int n
+// dynamic LDS: double WdT[(N-S) * KP] | double alpha_s[K] | double beta_s[N] | int F[N] | int n
 template <int VEC>
 __global__ void decode_kernel(const float *__restrict__ preds, const uint8_t *__restrict__ mask,
                               float *__restrict__ out, int32_t *__restrict__ status, int K, int N, int S,
@@ -140,12 +212,15 @@ __global__ void decode_kernel(const float *__restrict__ preds, const uint8_t *__
     const int KP = round_up4(K);
     const int nF_expected = N - S;
     double *WdT = lds_d;
-    int *F = reinterpret_cast<int *>(WdT + nF_expected * KP);
+    double *alpha_s = WdT + nF_expected * KP;
+    double *beta_s = alpha_s + K;
+    int *F = reinterpret_cast<int *>(beta_s + N);
     int *n_sh = F + N;
 
     const int64_t g = blockIdx.x / ctiles;
     const int64_t ct = blockIdx.x - g * ctiles;
 
+    stage_nodes(nodes, K, N, alpha_s, beta_s);
     for (int e = threadIdx.x; e < nF_expected * KP; e += blockDim.x) WdT[e] = 0.0;
     if (wave_id() == 0) {
         const int n = survivors_from_mask(mask + g * N, N, F);
@@ -158,13 +233,20 @@ __global__ void decode_kernel(const float *__restrict__ preds, const uint8_t *__
         status[g] = good ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
     if (!good) return;
 
-    decoder_weights(nodes, F, nF, K, KP, sign_mode, WdT);
-    __syncthreads();
-
+    // first chunk of this lane's prediction rows: issued now, consumed after the weights exist
     const int64_t cv0 = ct * kColsPerTile;
     const int64_t cv1 = (cv0 + kColsPerTile < Cv) ? cv0 + kColsPerTile : Cv;
-    contract_tile<VEC>(preds + static_cast<size_t>(g) * N * C, out + static_cast<size_t>(g) * K * C, F, nF, K, KP, C,
-                       cv0, cv1, WdT);
+    const float *pg = preds + static_cast<size_t>(g) * N * C;
+    typename PredVec<VEC>::type first[kRowChunk];
+    {
+        const int64_t cv = cv0 + (threadIdx.x % kColsPerTile);
+        load_row_chunk<VEC>(pg, F, nF, 0, C, cv < cv1 ? cv : cv0, first);
+    }
+
+    decoder_weights(alpha_s, beta_s, F, nF, K, KP, sign_mode, WdT);
+    __syncthreads();
+
+    contract_tile<VEC, true>(pg, out + static_cast<size_t>(g) * K * C, F, nF, K, KP, C, cv0, cv1, WdT, first);
 }
 
 // ------------------------------------------------------------------------------------
@@ -280,6 +362,7 @@ __device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg
 }
 
 // dynamic LDS: double scratch[nw][cpw * (n*2M + M + n)] | double WdT[(n-A) * KP] | double xs[n]
+//              | double alpha_s[K] | double beta_s[N]
 //              | int avail[N] | int F[N] | int votes[N] | int sel[N] | int n
 template <int VEC>
 __global__ void decode_byzantine_kernel(const float *__restrict__ preds, const uint8_t *__restrict__ mask,
@@ -297,7 +380,9 @@ __global__ void decode_byzantine_kernel(const float *__restrict__ preds, const u
     double *scratch = lds_d;
     double *WdT = scratch + static_cast<size_t>(nw) * wave_doubles;
     double *xs = WdT + nF * KP;
-    int *avail = reinterpret_cast<int *>(xs + n_expected);
+    double *alpha_s = xs + n_expected;
+    double *beta_s = alpha_s + K;
+    int *avail = reinterpret_cast<int *>(beta_s + N);
     int *F = avail + N;
     int *votes = F + N;
     int *sel = votes + N;
@@ -308,6 +393,7 @@ __global__ void decode_byzantine_kernel(const float *__restrict__ preds, const u
     const int wv = wave_id();
     const float *pg = preds + static_cast<size_t>(g) * N * C;
 
+    stage_nodes(nodes, K, N, alpha_s, beta_s);
     for (int e = threadIdx.x; e < nF * KP; e += blockDim.x) WdT[e] = 0.0;
     for (int e = threadIdx.x; e < N; e += blockDim.x) votes[e] = 0;
     if (wv == 0) {
@@ -321,7 +407,7 @@ __global__ void decode_byzantine_kernel(const float *__restrict__ preds, const u
     if (!good) return;
 
     // ---- Algorithm 2: per-class fit, pick, vote ---------------------------------------
-    for (int r = threadIdx.x; r < n; r += blockDim.x) xs[r] = nodes.beta[avail[r]];
+    for (int r = threadIdx.x; r < n; r += blockDim.x) xs[r] = beta_s[avail[r]];
     __syncthreads();
     for (int64_t c0 = static_cast<int64_t>(wv) * cpw; c0 < C; c0 += static_cast<int64_t>(nw) * cpw)
         locate_classes_wave(pg, C, c0, cpw, avail, xs, n, M, A, scratch + static_cast<size_t>(wv) * wave_doubles, votes);
@@ -353,12 +439,13 @@ __global__ void decode_byzantine_kernel(const float *__restrict__ preds, const u
     __syncthreads();
 
     // ---- decode over F -------------------------------------------------------------------
-    decoder_weights(nodes, F, nF, K, KP, sign_mode, WdT);
+    decoder_weights(alpha_s, beta_s, F, nF, K, KP, sign_mode, WdT);
     __syncthreads();
     float *og = out + static_cast<size_t>(g) * K * C;
     for (int64_t cv0 = 0; cv0 < Cv; cv0 += kColsPerTile) {
         const int64_t cv1 = (cv0 + kColsPerTile < Cv) ? cv0 + kColsPerTile : Cv;
-        contract_tile<VEC>(pg, og, F, nF, K, KP, C, cv0, cv1, WdT);
+        typename PredVec<VEC>::type unused[kRowChunk];
+        contract_tile<VEC, false>(pg, og, F, nF, K, KP, C, cv0, cv1, WdT, unused);
     }
 }
 
@@ -376,7 +463,7 @@ int launch_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int
     if (blocks > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
     int waves = KP / 4;
     if (waves > 4) waves = 4;
-    const size_t lds = sizeof(double) * static_cast<size_t>(N - S) * KP + sizeof(int) * (static_cast<size_t>(N) + 2);
+    const size_t lds = sizeof(double) * (static_cast<size_t>(N - S) * KP + K + N) + sizeof(int) * (static_cast<size_t>(N) + 2);
     const dim3 grid(static_cast<unsigned>(blocks)), block(waves * kWave);
     if (lds > 64 * 1024) {   // only K = 64 with more than 127 survivors; gfx950 has 160 KB of LDS per CU
         const void *fn = vec4 ? reinterpret_cast<const void *>(decode_kernel<4>)
@@ -407,7 +494,7 @@ int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *
     int cpw = kWave / (2 * M);
     if (cpw < 1) cpw = 1;
     if (cpw > C) cpw = static_cast<int>(C);
-    const size_t fixed = sizeof(double) * (static_cast<size_t>(n - A) * KP + n) + sizeof(int) * (4 * static_cast<size_t>(N) + 2);
+    const size_t fixed = sizeof(double) * (static_cast<size_t>(n - A) * KP + n + K + N) + sizeof(int) * (4 * static_cast<size_t>(N) + 2);
     const size_t per_class = sizeof(double) * (static_cast<size_t>(n) * 2 * M + M + n);
     const size_t budget = 64 * 1024;
     while (cpw > 1 && fixed + cpw * per_class > budget) --cpw;
