@@ -133,6 +133,24 @@ int approxifer_decode_byzantine(const float *d_preds, const uint8_t *d_mask, flo
                                 int64_t G, int K, int N, int S, int A, int64_t C,
                                 const double *h_alpha, const double *h_beta, int sign_mode, void *stream);
 
+/*
+ * Fused decoder + top-1 (Section 4.1, "Performance metric": the paper scores the class of the
+ * largest decoded soft label).  Decodes exactly as approxifer_decode() does, in float64, and for
+ * every group g and query j writes only
+ *     d_top1[g][j]  = argmax_c r_g(alpha_j)[c]      (equal values: the smallest c)
+ *     d_score[g][j] = that largest decoded value, rounded to float32 (d_score may be NULL)
+ * The [G][K][C] prediction tensor is never written.  The argmax is taken on the float64
+ * accumulators, before any rounding.
+ *
+ *   d_top1    [G][K] int32, device, written
+ *   d_score   [G][K] float32, device, written, or NULL
+ *   other arguments, status values and errors as approxifer_decode(); groups with a bad mask
+ *   leave their d_top1 / d_score rows untouched.
+ */
+int approxifer_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_top1, float *d_score,
+                           int32_t *d_status, int64_t G, int K, int N, int S, int64_t C,
+                           const double *h_alpha, const double *h_beta, int sign_mode, void *stream);
+
 /* Text for a return code; never NULL.  The string is static. */
 const char *approxifer_strerror(int code);
 

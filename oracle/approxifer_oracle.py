@@ -158,6 +158,17 @@ def decode(Y, mask, alpha, beta, S, sign_mode=SIGN_WORKER_INDEX):
     return out, status
 
 
+def decode_top1(Y, mask, alpha, beta, S, sign_mode=SIGN_WORKER_INDEX):
+    """Class of the largest decoded soft label of every query, the quantity the paper scores
+    (Section 4.1, "Performance metric").  Equal values: the smallest class index.
+    Returns (top1 [G, K] int32 with -1 for groups whose mask is bad, score [G, K] float64, status)."""
+    out, status = decode(Y, mask, alpha, beta, S, sign_mode)
+    top1 = np.argmax(out, axis=2).astype(np.int32)      # first occurrence of the maximum
+    score = np.max(out, axis=2)
+    top1[status != 0] = -1
+    return top1, score, status
+
+
 # --------------------------------------------------------------------------
 # adversary location (Algorithm 2)
 # --------------------------------------------------------------------------

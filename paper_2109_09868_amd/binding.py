@@ -26,6 +26,7 @@ EXPORTS = (
     "approxifer_chebyshev_nodes",
     "approxifer_encode",
     "approxifer_decode",
+    "approxifer_decode_top1",
     "approxifer_decode_byzantine",
 )
 
@@ -62,6 +63,9 @@ def load() -> ctypes.CDLL:
     lib.approxifer_decode.restype = ctypes.c_int
     lib.approxifer_decode.argtypes = [vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_int64, c_dp, c_dp, ctypes.c_int, vp]
+    lib.approxifer_decode_top1.restype = ctypes.c_int
+    lib.approxifer_decode_top1.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_int64, c_dp, c_dp, ctypes.c_int, vp]
     lib.approxifer_decode_byzantine.restype = ctypes.c_int
     lib.approxifer_decode_byzantine.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                                 ctypes.c_int, ctypes.c_int, ctypes.c_int64, c_dp, c_dp, ctypes.c_int, vp]
@@ -145,6 +149,30 @@ def approxifer_decode(preds, mask, alpha, beta, S, sign_mode=SIGN_WORKER_INDEX, 
                                     G, K, N, int(S), C, ap, bp, int(sign_mode),
                                     ctypes.c_void_p(_stream_handle(stream))))
     return out, status
+
+
+def approxifer_decode_top1(preds, mask, alpha, beta, S, sign_mode=SIGN_WORKER_INDEX, top1=None, score=None, status=None,
+                           stream=None, want_score=True):
+    """Fused decode + argmax over classes: (top1 [G, K] int32, score [G, K] float32 or None, status [G] int32)."""
+    import torch
+    a, ap = _nodes(alpha)
+    b, bp = _nodes(beta)
+    G, N, C = preds.shape
+    K = a.size
+    if N != b.size:
+        raise ValueError("preds.shape[1] must equal len(beta)")
+    if top1 is None:
+        top1 = torch.full((G, K), -1, dtype=torch.int32, device=preds.device)
+    if score is None and want_score:
+        score = torch.zeros((G, K), dtype=torch.float32, device=preds.device)
+    if status is None:
+        status = torch.full((G,), -1, dtype=torch.int32, device=preds.device)
+    _check(load().approxifer_decode_top1(_dev(preds, torch.float32), _dev(mask, torch.uint8, (G, N)),
+                                         _dev(top1, torch.int32, (G, K)),
+                                         _dev(score, torch.float32, (G, K)) if score is not None else None,
+                                         _dev(status, torch.int32, (G,)), G, K, N, int(S), C, ap, bp, int(sign_mode),
+                                         ctypes.c_void_p(_stream_handle(stream))))
+    return top1, score, status
 
 
 def approxifer_decode_byzantine(preds, mask, alpha, beta, S, A, sign_mode=SIGN_WORKER_INDEX, out=None, adv=None,

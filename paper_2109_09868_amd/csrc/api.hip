@@ -87,6 +87,23 @@ int approxifer_decode(const float *d_preds, const uint8_t *d_mask, float *d_out,
                                      static_cast<hipStream_t>(stream));
 }
 
+int approxifer_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_top1, float *d_score,
+                           int32_t *d_status, int64_t G, int K, int N, int S, int64_t C, const double *h_alpha,
+                           const double *h_beta, int sign_mode, void *stream) {
+    if (G < 0 || C < 0) return APPROXIFER_ERR_BAD_SHAPE;
+    Nodes nodes;
+    const int rc = check_common(K, N, h_alpha, h_beta, &nodes);
+    if (rc != APPROXIFER_OK) return rc;
+    if (S < 0 || S >= N) return APPROXIFER_ERR_BAD_SHAPE;
+    if (sign_mode != APPROXIFER_SIGN_WORKER_INDEX && sign_mode != APPROXIFER_SIGN_SURVIVOR_RANK)
+        return APPROXIFER_ERR_BAD_SIGN_MODE;
+    if (C > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;   // class indices are int32
+    if (G == 0 || C == 0) return APPROXIFER_OK;
+    if (d_mask == nullptr || d_preds == nullptr || d_top1 == nullptr) return APPROXIFER_ERR_NULL_POINTER;
+    return approxifer::launch_decode_top1(d_preds, d_mask, d_top1, d_score, d_status, G, K, N, S, C, nodes,
+                                          sign_mode, static_cast<hipStream_t>(stream));
+}
+
 int approxifer_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
                                 int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C,
                                 const double *h_alpha, const double *h_beta, int sign_mode, void *stream) {

@@ -97,6 +97,9 @@ int launch_encode(const float *d_queries, float *d_coded, int64_t G, int K, int 
 int launch_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_status,
                   int64_t G, int K, int N, int S, int64_t C, const Nodes &nodes, int sign_mode,
                   hipStream_t stream);
+int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_top1, float *d_score,
+                       int32_t *d_status, int64_t G, int K, int N, int S, int64_t C, const Nodes &nodes,
+                       int sign_mode, hipStream_t stream);
 int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
                             int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C,
                             const Nodes &nodes, int sign_mode, hipStream_t stream);

@@ -250,6 +250,114 @@ __global__ void decode_kernel(const float *__restrict__ preds, const uint8_t *__
 }
 
 // ------------------------------------------------------------------------------------
+// fused decoder + top-1 kernel
+// ------------------------------------------------------------------------------------
+struct Best {
+    double v;
+    int i;
+};
+__device__ __forceinline__ bool better(double v, int i, const Best &b) { return v > b.v || (v == b.v && i < b.i); }
+
+// One workgroup per group, one wave per quad of query rows.  A lane walks vector columns
+// lane, lane+64, .. of its quad, decodes them in float64 exactly as contract_tile does and
+// keeps the largest value (smallest class on equal values) per query row; a wavefront
+// butterfly merges the 64 candidates.  Nothing but [K] class indices (and scores) is written.
+// dynamic LDS: as decode_kernel.
+template <int VEC>
+__global__ void decode_top1_kernel(const float *__restrict__ preds, const uint8_t *__restrict__ mask,
+                                   int32_t *__restrict__ top1, float *__restrict__ score,
+                                   int32_t *__restrict__ status, int K, int N, int S, int64_t C, int64_t Cv,
+                                   int sign_mode, const Nodes nodes) {
+    typedef typename PredVec<VEC>::type V;
+    extern __shared__ double lds_d[];
+    const int KP = round_up4(K);
+    const int nF_expected = N - S;
+    double *WdT = lds_d;
+    double *alpha_s = WdT + nF_expected * KP;
+    double *beta_s = alpha_s + K;
+    int *F = reinterpret_cast<int *>(beta_s + N);
+    int *n_sh = F + N;
+    const int64_t g = blockIdx.x;
+
+    stage_nodes(nodes, K, N, alpha_s, beta_s);
+    for (int e = threadIdx.x; e < nF_expected * KP; e += blockDim.x) WdT[e] = 0.0;
+    if (wave_id() == 0) {
+        const int n = survivors_from_mask(mask + g * N, N, F);
+        if (lane_id() == 0) *n_sh = n;
+    }
+    __syncthreads();
+    const int nF = *n_sh;
+    const bool good = nF == nF_expected;
+    if (threadIdx.x == 0 && status != nullptr) status[g] = good ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
+    if (!good) return;
+    decoder_weights(alpha_s, beta_s, F, nF, K, KP, sign_mode, WdT);
+    __syncthreads();
+
+    const float *pg = preds + static_cast<size_t>(g) * N * C;
+    const int lane = lane_id();
+    const int nwaves = blockDim.x / kWave;
+    for (int q = wave_id(); q < KP / 4; q += nwaves) {
+        Best best[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            best[jj].v = -__builtin_inf();
+            best[jj].i = 0x7fffffff;
+        }
+        for (int64_t cv = lane; cv < Cv; cv += kWave) {
+            double acc[4][VEC];
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[jj][e] = 0.0;
+            for (int r0 = 0; r0 < nF; r0 += kRowChunk) {
+                V y[kRowChunk];
+                load_row_chunk<VEC>(pg, F, nF, r0, C, cv, y);
+#pragma unroll
+                for (int u = 0; u < kRowChunk; ++u) {
+                    if (r0 + u < nF) {
+                        const double *w = WdT + (r0 + u) * KP + 4 * q;
+#pragma unroll
+                        for (int jj = 0; jj < 4; ++jj) {
+                            const double wj = w[jj];
+#pragma unroll
+                            for (int e = 0; e < VEC; ++e)
+                                acc[jj][e] = fma(wj, static_cast<double>(vec_get<VEC>(y[u], e)), acc[jj][e]);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const int idx = static_cast<int>(cv * VEC + e);
+                    if (better(acc[jj][e], idx, best[jj])) {
+                        best[jj].v = acc[jj][e];
+                        best[jj].i = idx;
+                    }
+                }
+        }
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const double ov = __shfl_xor(best[jj].v, off, kWave);
+                const int oi = __shfl_xor(best[jj].i, off, kWave);
+                if (better(ov, oi, best[jj])) {
+                    best[jj].v = ov;
+                    best[jj].i = oi;
+                }
+            }
+            const int j = 4 * q + jj;
+            if (lane == 0 && j < K) {
+                top1[g * K + j] = best[jj].i == 0x7fffffff ? 0 : best[jj].i;
+                if (score != nullptr) score[g * K + j] = static_cast<float>(best[jj].v);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
 // Byzantine decoder kernel
 // ------------------------------------------------------------------------------------
 // Algorithm 2, steps 1-5, for the classes c0 .. c0+cpw-1 of one group, by one wave.
@@ -477,6 +585,32 @@ int launch_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int
     else
         hipLaunchKernelGGL(decode_kernel<1>, grid, block, lds, stream, d_preds, d_mask, d_out, d_status, K, N, S, C,
                            Cv, ctiles, sign_mode, nodes);
+    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+}
+
+int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_top1, float *d_score,
+                       int32_t *d_status, int64_t G, int K, int N, int S, int64_t C, const Nodes &nodes,
+                       int sign_mode, hipStream_t stream) {
+    const int KP = (K + 3) & ~3;
+    const bool vec4 = (C % 4 == 0) && aligned16(d_preds);
+    const int64_t Cv = vec4 ? C / 4 : C;
+    if (G > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    int waves = KP / 4;
+    if (waves > 4) waves = 4;
+    const size_t lds = sizeof(double) * (static_cast<size_t>(N - S) * KP + K + N) + sizeof(int) * (static_cast<size_t>(N) + 2);
+    const dim3 grid(static_cast<unsigned>(G)), block(waves * kWave);
+    if (lds > 64 * 1024) {
+        const void *fn = vec4 ? reinterpret_cast<const void *>(decode_top1_kernel<4>)
+                              : reinterpret_cast<const void *>(decode_top1_kernel<1>);
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
+            return APPROXIFER_ERR_LAUNCH;
+    }
+    if (vec4)
+        hipLaunchKernelGGL(decode_top1_kernel<4>, grid, block, lds, stream, d_preds, d_mask, d_top1, d_score, d_status,
+                           K, N, S, C, Cv, sign_mode, nodes);
+    else
+        hipLaunchKernelGGL(decode_top1_kernel<1>, grid, block, lds, stream, d_preds, d_mask, d_top1, d_score, d_status,
+                           K, N, S, C, Cv, sign_mode, nodes);
     return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
 }
 

@@ -25,7 +25,7 @@ def lib():
 def _declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(approxifer_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(approxifer_[a-z_0-9]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported(lib):
@@ -95,6 +95,13 @@ def test_host_validation_codes(lib):
     assert dec(fake, fake, fake, None, 1, 4, 6, 2, 3, _dp(a), _dp(b), 2, None) == -6
     assert dec(fake, None, fake, None, 1, 4, 6, 2, 3, _dp(a), _dp(b), 0, None) == -1
     assert dec(None, None, None, None, 0, 4, 6, 2, 3, _dp(a), _dp(b), 1, None) == 0
+
+    top = lib.approxifer_decode_top1
+    assert top(fake, fake, fake, None, None, 1, 4, 6, 6, 3, _dp(a), _dp(b), 0, None) == -2
+    assert top(fake, fake, None, None, None, 1, 4, 6, 2, 3, _dp(a), _dp(b), 0, None) == -1
+    assert top(fake, fake, fake, None, None, 1, 4, 6, 2, 3, _dp(a), _dp(b), 5, None) == -6
+    assert top(fake, fake, fake, None, None, 1, 4, 6, 2, 2 ** 31, _dp(a), _dp(b), 0, None) == -3
+    assert top(None, None, None, None, None, 0, 4, 6, 2, 3, _dp(a), _dp(b), 0, None) == 0
 
     byz = lib.approxifer_decode_byzantine
     a8, b24 = orc.chebyshev_nodes(8, 24)

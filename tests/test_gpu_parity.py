@@ -306,6 +306,87 @@ def test_decode_text_full_size(gpu, name):
 
 
 # --------------------------------------------------------------------------------------
+# fused decoder + top-1
+# --------------------------------------------------------------------------------------
+def _top1_both(gpu, Y, mask, alpha, beta, S, mode):
+    torch, binding, dev = gpu
+    top1, score, st = binding.approxifer_decode_top1(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev),
+                                                     alpha, beta, S, mode)
+    ref_top1, ref_score, st_ref = orc.decode_top1(Y, mask, alpha, beta, S, mode)
+    return top1.cpu().numpy(), score.cpu().numpy(), st.cpu().numpy(), ref_top1, ref_score, st_ref
+
+
+def _assert_top1(Y, mask, alpha, beta, S, mode, top1, score, st, ref_top1, ref_score, st_ref):
+    assert np.array_equal(st, st_ref)
+    good = st_ref == 0
+    # both sides take the decision on float64 values; where the oracle's top two are further apart than
+    # float64 rounding of the contraction can explain the indices must be identical
+    out, _ = orc.decode(Y, mask, alpha, beta, S, mode)
+    top2 = np.sort(out, axis=-1)[..., -2:] if out.shape[-1] > 1 else np.stack([out[..., 0] - 1, out[..., 0]], -1)
+    clear = ((top2[..., 1] - top2[..., 0]) > 1e-9 * np.abs(out).max(axis=-1)) & good[:, None]
+    assert np.array_equal(top1[clear], ref_top1[clear])
+    assert clear[good].mean() > 0.999
+    same = (top1 == ref_top1) & good[:, None]
+    scale = np.abs(ref_score[good]).max()
+    assert np.max(np.abs(score[same] - ref_score[same])) <= TOL * scale
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("name", ["tiny", "imagenet"])
+def test_decode_top1_workloads(gpu, name, mode):
+    w = syn.WORKLOADS[name]
+    alpha, beta = orc.chebyshev_nodes(w.K, w.W)
+    if name == "tiny":
+        Y = syn.model_apply(w, syn.model_params(w), orc.encode(syn.queries(w), alpha, beta))
+    else:
+        Y = syn.iid_logits(w)
+    mask = syn.masks(w)
+    _assert_top1(Y, mask, alpha, beta, w.S, mode, *_top1_both(gpu, Y, mask, alpha, beta, w.S, mode))
+
+
+@pytest.mark.parametrize("K,N,S,C,G", [(1, 2, 1, 1, 3), (2, 3, 1, 7, 4), (5, 100, 10, 33, 2), (12, 20, 8, 1003, 2),
+                                       (32, 48, 12, 2, 5), (64, 128, 0, 12, 2), (9, 70, 3, 516, 2), (8, 9, 1, 10, 300)])
+def test_decode_top1_shapes_and_bad_masks(gpu, K, N, S, C, G):
+    torch, binding, dev = gpu
+    rng = np.random.default_rng(K + 3 * N + S)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    Y = rng.standard_normal((G, N, C)).astype(np.float32)
+    mask = np.zeros((G, N), np.uint8)
+    for g in range(G):
+        mask[g, rng.permutation(N)[: N - S]] = 1
+    if S > 0:
+        mask[G - 1, np.nonzero(mask[G - 1] == 0)[0][0]] = 1          # one survivor too many in the last group
+    Y[mask == 0] = np.nan
+    top1 = torch.full((G, K), -9, dtype=torch.int32, device=dev)
+    score = torch.full((G, K), -9.0, dtype=torch.float32, device=dev)
+    t, sc, st = binding.approxifer_decode_top1(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev), alpha, beta,
+                                               S, 1, top1=top1, score=score)
+    ref = orc.decode_top1(Y, mask, alpha, beta, S, 1)
+    t, sc, st = t.cpu().numpy(), sc.cpu().numpy(), st.cpu().numpy()
+    _assert_top1(Y, mask, alpha, beta, S, 1, t, sc, st, *ref)
+    if S > 0:
+        assert st[G - 1] == 1 and np.all(t[G - 1] == -9) and np.all(sc[G - 1] == -9.0)
+    # score pointer may be NULL
+    t2, none, _ = binding.approxifer_decode_top1(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev), alpha, beta,
+                                                 S, 1, want_score=False)
+    assert none is None and np.array_equal(t2.cpu().numpy()[st == 0], t[st == 0])
+
+
+def test_decode_top1_exact_ties_take_smallest_class(gpu):
+    K, N, C = 4, 6, 12
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    rng = np.random.default_rng(2)
+    base = rng.standard_normal((3, N, 1)).astype(np.float32)
+    Y = np.repeat(base, C, axis=2)                       # every class column identical -> all decoded values tie
+    Y[..., 7] += 2.0
+    Y[..., 9] = Y[..., 7]                                # classes 7 and 9 tie
+    mask = np.ones((3, N), np.uint8)
+    top1, score, st, ref_top1, ref_score, _ = _top1_both(gpu, Y, mask, alpha, beta, 0, 0)
+    assert np.array_equal(top1, ref_top1)
+    assert set(np.unique(top1)) <= {0, 7}
+
+
+# --------------------------------------------------------------------------------------
 # Byzantine decoder
 # --------------------------------------------------------------------------------------
 def _byzantine_inputs(w):

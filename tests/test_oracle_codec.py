@@ -224,3 +224,53 @@ def test_decode_error_shrinks_with_more_workers():
         out, _ = orc.decode(Y, np.ones((1, W), np.uint8), alpha, beta, 0)
         errs.append(np.max(np.abs(out - f(X))))
     assert errs[0] > errs[1] > errs[2]
+
+
+def test_decode_top1_definition_and_ties():
+    # Section 4.1, "Performance metric": the class of the largest decoded soft label
+    rng = np.random.default_rng(31)
+    K, W, S, C = 3, 5, 1, 7
+    alpha, beta = orc.chebyshev_nodes(K, W)
+    Y = rng.standard_normal((4, W, C))
+    mask = np.ones((4, W), np.uint8)
+    mask[:, 2] = 0
+    mask[3, 1] = 0                                   # bad popcount
+    top1, score, st = orc.decode_top1(Y, mask, alpha, beta, S, 1)
+    out, _ = orc.decode(Y, mask, alpha, beta, S, 1)
+    assert top1.dtype == np.int32 and list(st) == [0, 0, 0, 1] and np.all(top1[3] == -1)
+    for g in range(3):
+        for j in range(K):
+            row = list(out[g, j])
+            assert top1[g, j] == row.index(max(row)) and score[g, j] == max(row)
+    # identical class columns decode to identical values: the smallest class index wins
+    Yt = np.repeat(rng.standard_normal((1, W, 1)), C, axis=2)
+    Yt[..., 5] += 1.0
+    Yt[..., 6] = Yt[..., 5]
+    t, _, _ = orc.decode_top1(Yt, np.ones((1, W), np.uint8), alpha, beta, 0)
+    o, _ = orc.decode(Yt, np.ones((1, W), np.uint8), alpha, beta, 0)
+    assert np.array_equal(o[..., 5], o[..., 6])
+    for j in range(K):
+        assert t[0, j] == (5 if o[0, j, 5] > o[0, j, 0] else 0)
+    # exact recovery case (K=2, W=3, affine model, survivor-rank signs): top-1 equals the true top-1
+    alpha, beta = orc.chebyshev_nodes(2, 3)
+    X = rng.standard_normal((5, 2, 6))
+    Mf, b = rng.standard_normal((6, 4)), rng.standard_normal(4)
+    Yc = orc.encode(X, alpha, beta) @ Mf + b
+    m = np.ones((5, 3), np.uint8)
+    m[:, 1] = 0
+    t, _, _ = orc.decode_top1(Yc, m, alpha, beta, 1, 1)
+    assert np.array_equal(t, np.argmax(X @ Mf + b, axis=2))
+
+
+def test_worker_index_signs_can_have_a_real_pole():
+    # K=3, five workers, the middle worker missing: with the printed worker-index signs the survivors
+    # carry (+,-,-,+) on the symmetric nodes (1, a, -a, -1), and at the middle query node alpha_1 = 0 the
+    # denominator 1/(0-1) - 1/(0-a) - 1/(0+a) + 1/(0+1) cancels exactly: r has a pole there.  Berrut's
+    # alternation by rank (+,-,+,-) has none (Section 3, background: no pole on the real line).
+    alpha, beta = orc.chebyshev_nodes(3, 5)
+    F = [0, 1, 3, 4]
+    with np.errstate(divide="ignore", invalid="ignore"):
+        w0 = orc.decode_weights(alpha, beta, F, 0)
+    w1 = orc.decode_weights(alpha, beta, F, 1)
+    assert not np.all(np.isfinite(w0[1]))
+    assert np.all(np.isfinite(w1)) and np.allclose(w1.sum(axis=1), 1.0)
