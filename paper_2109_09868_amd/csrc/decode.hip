@@ -261,8 +261,10 @@ __device__ __forceinline__ bool better(double v, int i, const Best &b) { return 
 // One workgroup per group, one wave per quad of query rows.  A lane walks vector columns
 // lane, lane+64, .. of its quad, decodes them in float64 exactly as contract_tile does and
 // keeps the largest value (smallest class on equal values) per query row; a wavefront
-// butterfly merges the 64 candidates.  Nothing but [K] class indices (and scores) is written.
-// dynamic LDS: as decode_kernel.
+// butterfly merges the 64 candidates; when the workgroup has more waves than quads, the waves
+// of a quad split its columns and their winners are merged through LDS.  Nothing but [K] class
+// indices (and scores) is written.
+// dynamic LDS: as decode_kernel, then pad to 16 bytes | Best merged[KP][slices].
 template <int VEC>
 __global__ void decode_top1_kernel(const float *__restrict__ preds, const uint8_t *__restrict__ mask,
                                    int32_t *__restrict__ top1, float *__restrict__ score,
@@ -295,15 +297,20 @@ __global__ void decode_top1_kernel(const float *__restrict__ preds, const uint8_
 
     const float *pg = preds + static_cast<size_t>(g) * N * C;
     const int lane = lane_id();
+    const int KQ = KP / 4;
     const int nwaves = blockDim.x / kWave;
-    for (int q = wave_id(); q < KP / 4; q += nwaves) {
+    const int slices = nwaves >= KQ ? nwaves / KQ : 1;          // waves that share one quad split its columns
+    const int qwaves = nwaves >= KQ ? KQ : nwaves;              // quads processed concurrently
+    const int slice = wave_id() / qwaves;
+    Best *merged = reinterpret_cast<Best *>((reinterpret_cast<uintptr_t>(n_sh + 1) + 15) & ~static_cast<uintptr_t>(15));   // [KP][slices]
+    for (int q = wave_id() % qwaves; q < KQ && slice < slices; q += qwaves) {
         Best best[4];
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             best[jj].v = -__builtin_inf();
             best[jj].i = 0x7fffffff;
         }
-        for (int64_t cv = lane; cv < Cv; cv += kWave) {
+        for (int64_t cv = static_cast<int64_t>(slice) * kWave + lane; cv < Cv; cv += static_cast<int64_t>(slices) * kWave) {
             double acc[4][VEC];
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj)
@@ -348,12 +355,18 @@ __global__ void decode_top1_kernel(const float *__restrict__ preds, const uint8_
                     best[jj].i = oi;
                 }
             }
-            const int j = 4 * q + jj;
-            if (lane == 0 && j < K) {
-                top1[g * K + j] = best[jj].i == 0x7fffffff ? 0 : best[jj].i;
-                if (score != nullptr) score[g * K + j] = static_cast<float>(best[jj].v);
-            }
+            if (lane == 0) merged[(4 * q + jj) * slices + slice] = best[jj];
         }
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < K; j += blockDim.x) {
+        Best b = merged[j * slices];
+        for (int sl = 1; sl < slices; ++sl) {
+            const Best o = merged[j * slices + sl];
+            if (better(o.v, o.i, b)) b = o;
+        }
+        top1[g * K + j] = b.i == 0x7fffffff ? 0 : b.i;
+        if (score != nullptr) score[g * K + j] = static_cast<float>(b.v);
     }
 }
 
@@ -595,9 +608,15 @@ int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_t
     const bool vec4 = (C % 4 == 0) && aligned16(d_preds);
     const int64_t Cv = vec4 ? C / 4 : C;
     if (G > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
-    int waves = KP / 4;
-    if (waves > 4) waves = 4;
-    const size_t lds = sizeof(double) * (static_cast<size_t>(N - S) * KP + K + N) + sizeof(int) * (static_cast<size_t>(N) + 2);
+    const int KQ = KP / 4;
+    int slices = static_cast<int>((Cv + kWave - 1) / kWave);     // column slices worth a wave of their own
+    if (slices > 4) slices = 4;
+    if (slices * KQ > 16) slices = 16 / KQ;
+    if (slices < 1) slices = 1;
+    const int waves = KQ <= 16 ? KQ * slices : 16;
+    // int F[N] | int n | 1 pad int  keeps the Best array that follows 16-byte aligned when N is even; round up
+    size_t lds = sizeof(double) * (static_cast<size_t>(N - S) * KP + K + N) + sizeof(int) * (static_cast<size_t>(N) + 3);
+    lds += 16 + sizeof(double) * 2 * static_cast<size_t>(KP) * (waves >= KQ ? waves / KQ : 1);
     const dim3 grid(static_cast<unsigned>(G)), block(waves * kWave);
     if (lds > 64 * 1024) {
         const void *fn = vec4 ? reinterpret_cast<const void *>(decode_top1_kernel<4>)

@@ -1,0 +1,61 @@
+"""Run one library call on one synthetic workload shape a few times (for profilers).
+
+    python3 -m paper_2109_09868_amd.run_workload --workload text_k32 --op encode --reps 5
+    rocprofv3 --kernel-trace --stats -- python3 -m paper_2109_09868_amd.run_workload --workload byzantine --op decode_byzantine
+
+Inputs are drawn on the device with torch (values do not matter to a profile; shapes, masks and
+launch configuration are those of the named workload).
+"""
+from __future__ import annotations
+
+import argparse
+
+import numpy as np
+
+
+def main():
+    import torch
+
+    from . import binding, synthetic as syn
+
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", default="imagenet", choices=sorted(syn.WORKLOADS))
+    ap.add_argument("--op", default="encode", choices=["encode", "decode", "decode_top1", "decode_byzantine"])
+    ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--sign-mode", type=int, default=0)
+    args = ap.parse_args()
+
+    w = syn.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    alpha, beta = binding.approxifer_chebyshev_nodes(w.K, w.W)
+    gen = torch.Generator(device=dev).manual_seed(syn.BASE_SEED + w.index)
+    if args.op == "encode":
+        q = torch.rand((w.G, w.K, w.D), dtype=torch.float32, device=dev, generator=gen)
+        coded = torch.empty((w.G, w.W, w.D), dtype=torch.float32, device=dev)
+        fn = lambda: binding.approxifer_encode(q, alpha, beta, coded=coded)
+    else:
+        mask_h = syn.masks(w)
+        mask = torch.from_numpy(mask_h).to(dev)
+        preds = torch.randn((w.G, w.W, w.C), dtype=torch.float32, device=dev, generator=gen)
+        out = torch.empty((w.G, w.K, w.C), dtype=torch.float32, device=dev)
+        st = torch.empty((w.G,), dtype=torch.int32, device=dev)
+        if args.op == "decode":
+            fn = lambda: binding.approxifer_decode(preds, mask, alpha, beta, w.S, args.sign_mode, out=out, status=st)
+        elif args.op == "decode_top1":
+            top1 = torch.empty((w.G, w.K), dtype=torch.int32, device=dev)
+            fn = lambda: binding.approxifer_decode_top1(preds, mask, alpha, beta, w.S, args.sign_mode, top1=top1,
+                                                        status=st, want_score=False)
+        else:
+            if w.A < 1:
+                raise SystemExit("workload %s has no adversaries" % w.name)
+            adv = torch.empty((w.G, w.A), dtype=torch.int32, device=dev)
+            fn = lambda: binding.approxifer_decode_byzantine(preds, mask, alpha, beta, w.S, w.A, args.sign_mode, out=out,
+                                                             adv=adv, status=st)
+    for _ in range(args.reps):
+        fn()
+    torch.cuda.synchronize()
+    print("%s %s x%d done" % (args.workload, args.op, args.reps))
+
+
+if __name__ == "__main__":
+    main()

@@ -51,6 +51,8 @@ WORKLOADS = {
     "imagenet": Workload("imagenet", 2, 512, 12, 20, 8, 0, (3, 224, 224), 1000, "clipped_normal", "iid_logits"),
     "byzantine": Workload("byzantine", 3, 2048, 8, 24, 4, 2, (3, 32, 32), 10, "uniform01", "linear"),
     "text": Workload("text", 4, 1024, 16, 24, 6, 0, (128, 768), 2, "normal", "meanpool_linear"),
+    # the paper's own operating point (Section 4.2): MNIST-sized queries, K = 8, one straggler, 10 classes
+    "mnist_k8": Workload("mnist_k8", 6, 16384, 8, 9, 1, 0, (1, 28, 28), 10, "uniform01", "linear_softmax"),
     "text_k32": Workload("text_k32", 5, 1024, 32, 48, 12, 0, (128, 768), 2, "normal", "meanpool_linear"),
 }
 
@@ -135,8 +137,9 @@ def model_params(w: Workload) -> dict:
     rng = _rng(w, _STREAM_MODEL)
     D = w.D
     if w.model in ("linear_softmax", "linear"):
-        # the "byzantine" workload reuses the linear map of the "tiny" workload
-        rng = _rng(WORKLOADS["tiny"], _STREAM_MODEL)
+        if D == WORKLOADS["tiny"].D:
+            # the "byzantine" workload reuses the linear map of the "tiny" workload
+            rng = _rng(WORKLOADS["tiny"], _STREAM_MODEL)
         return {"M": rng.standard_normal((D, w.C)) / np.sqrt(D), "b": np.zeros(w.C)}
     if w.model == "mlp":
         H = 512
