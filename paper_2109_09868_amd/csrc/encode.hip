@@ -34,6 +34,12 @@ namespace {
 #ifndef APPROXIFER_ENCODE_BLOCKS_PER_CU_LARGE_K
 #define APPROXIFER_ENCODE_BLOCKS_PER_CU_LARGE_K 2    // K > 16: four-wave workgroups
 #endif
+#ifndef APPROXIFER_ENCODE_MFMA_MIN_K
+#define APPROXIFER_ENCODE_MFMA_MIN_K 17            // smallest K served by the matrix-core variant
+#endif
+#ifndef APPROXIFER_ENCODE_MFMA_BLOCKS_PER_CU
+#define APPROXIFER_ENCODE_MFMA_BLOCKS_PER_CU 4       // K > 16, matrix-core variant (four waves of 64 columns)
+#endif
 constexpr int kLdsPerCu = 160 * 1024;                // gfx950
 
 template <int VEC> struct VecOf;
@@ -127,6 +133,131 @@ __global__ __launch_bounds__(THREADS) void encode_kernel(
     }
 }
 
+// ---- matrix-core variant for K > 16 -----------------------------------------------------
+// At K = 32, N = 48 the vector kernel above issues VALU instructions on 95 % of all cycles
+// (SQ_INSTS_VALU x 4 against SIMD-cycles): the contraction, not HBM, bounds it there.  This
+// variant forms coded = W (N x K) * X (K x columns) with v_mfma_f32_16x16x4_f32, whose fp32 rate is
+// twice the plain vector FMA rate, and leaves the vector ALUs to address arithmetic.
+//
+// Operand layout of v_mfma_f32_16x16x4_f32 (D[16x16] += A[16x4] * B[4x16]), lane l of the wave:
+//   A: element (row l%16, k l/16)       B: element (k l/16, column l%16)
+//   D: register r holds element (row 4*(l/16) + r, column l%16)
+// A wave owns 64 consecutive columns of a group.  One 128-bit load gives lane l the four columns
+// 4*(l%16)..+3 of query row 4s + l/16, so component e of that register IS the B operand of k-step
+// s for the column set {4c + e}: no shuffles.  The four column sets give, in register r of their
+// accumulators, four consecutive columns of worker row 16*mt + 4*(l/16) + r: one 128-bit store.
+// The weights sit in LDS already in A-operand order, wA[(mt*KS + s)*64 + l].
+constexpr int kMfmaThreads = 256;
+
+template <int KS>   // KS = ceil(K / 4) k-steps
+__global__ __launch_bounds__(kMfmaThreads) void encode_mfma_kernel(
+    const float *__restrict__ queries, float *__restrict__ coded, int K, int N, int64_t D, int64_t Dv,
+    int64_t chunks, const Nodes nodes) {
+    constexpr int LPR = KS <= 8 ? 32 : 64;                    // lanes per weight row (K <= 32 / K <= 64)
+    constexpr int ROWS_PER_PASS = kMfmaThreads / LPR;
+    extern __shared__ float wA[];                             // [ceil(N/16)][KS][64]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wv = tid >> 6;
+    const int64_t g = blockIdx.x / chunks;
+    const int64_t ch = blockIdx.x - g * chunks;
+    const int64_t col = (ch * (kMfmaThreads / 64) + wv) * 16 + (lane & 15);   // this lane's vector column
+    const bool ok = col < Dv;
+    const int krow = lane >> 4;                               // row offset inside a k-step
+    const float *xg = queries + static_cast<size_t>(g) * K * D + (ok ? col : 0) * 4;
+    float *og = coded + static_cast<size_t>(g) * N * D + col * 4;
+
+    // ---- query rows 4s + krow, columns 4*col..+3; rows past K are clamped (their weights are 0) ----
+    v4f x[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        const int row = (4 * s + krow < K) ? 4 * s + krow : K - 1;
+        x[s] = load_stream<4>(xg + static_cast<size_t>(row) * D);
+    }
+
+    // ---- l_j(beta_i) in float64 (scalar node loads only, see encode_kernel), stored in A order ----
+    {
+        const int j = tid % LPR;
+        const int sub = tid / LPR;
+        const bool valid = j < K;
+        double xa = 0.0;
+#pragma unroll
+        for (int jj = 0; jj < 4 * KS; ++jj) {
+            const double a = wave_uniform(nodes.alpha[jj]);   // entries past K are zero-filled by the host
+            if (j == jj) xa = a;
+        }
+        const double sign = (j & 1) ? -1.0 : 1.0;
+        const int n16 = (N + 15) & ~15;
+        for (int i0 = 0; i0 < n16; i0 += ROWS_PER_PASS) {     // n16 <= 128 = APPROXIFER_MAX_N: reads stay in bounds
+            double z = wave_uniform(nodes.beta[i0]);
+#pragma unroll
+            for (int r = 1; r < ROWS_PER_PASS; ++r) {
+                const double zr = wave_uniform(nodes.beta[i0 + r]);
+                if (sub == r) z = zr;
+            }
+            const int i = i0 + sub;
+            const bool row = i < N;
+            const BerrutTerm bt = berrut_term(z, xa, sign, valid && row);
+            const double den = group_sum<LPR>(bt.t);
+            const unsigned long long hits = __ballot(bt.hit);
+            const unsigned long long group_mask =
+                (LPR == 64) ? ~0ull : ((1ull << (LPR & 63)) - 1ull) << ((tid & 63) / LPR * LPR);
+            const bool any_hit = (hits & group_mask) != 0ull;
+            const double w = any_hit ? (bt.hit ? 1.0 : 0.0) : bt.t * (1.0 / den);
+            if (j < 4 * KS)   // rows N..n16-1 and columns K..4KS-1 hold zeros
+                wA[((i >> 4) * KS + (j >> 2)) * 64 + (j & 3) * 16 + (i & 15)] = (valid && row) ? static_cast<float>(w) : 0.0f;
+        }
+    }
+    __syncthreads();
+
+    const int mtiles = (N + 15) >> 4;
+    for (int mt = 0; mt < mtiles; ++mt) {
+        v4f acc[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] = v4f(0.0f);
+        const float *wmt = wA + mt * KS * 64 + lane;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const float a = wmt[s * 64];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, x[s][e], acc[e], 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int i = 16 * mt + 4 * krow + r;
+            if (ok && i < N) {
+                v4f v;
+                v[0] = acc[0][r];
+                v[1] = acc[1][r];
+                v[2] = acc[2][r];
+                v[3] = acc[3][r];
+                store_stream<4>(og + static_cast<size_t>(i) * D, v);
+            }
+        }
+    }
+}
+
+template <int KS>
+int run_encode_mfma(const float *d_queries, float *d_coded, int64_t G, int K, int N, int64_t D, const Nodes &nodes,
+                    hipStream_t stream) {
+    const int64_t Dv = D / 4;
+    const int64_t cols_per_block = (kMfmaThreads / 64) * 16;           // vector columns per workgroup
+    const int64_t chunks = (Dv + cols_per_block - 1) / cols_per_block;
+    const int64_t tiles = G * chunks;
+    if (tiles > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    const size_t lds_used = static_cast<size_t>((N + 15) / 16) * KS * 64 * sizeof(float);
+    size_t lds = (static_cast<size_t>(kLdsPerCu / APPROXIFER_ENCODE_MFMA_BLOCKS_PER_CU) / 512) * 512;
+    if (lds < lds_used) lds = lds_used;
+    if (lds > 64 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_mfma_kernel<KS>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
+        return APPROXIFER_ERR_LAUNCH;
+    hipLaunchKernelGGL((encode_mfma_kernel<KS>), dim3(static_cast<unsigned>(tiles)), dim3(kMfmaThreads), lds, stream,
+                       d_queries, d_coded, K, N, D, Dv, chunks, nodes);
+    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+}
+
 template <int K, int VEC>
 int run_encode(const float *d_queries, float *d_coded, int64_t G, int N, int64_t D, const Nodes &nodes,
                hipStream_t stream) {
@@ -155,7 +286,11 @@ int run_encode_k(const float *d_queries, float *d_coded, int64_t G, int N, int64
                  hipStream_t stream) {
     const bool aligned16 = (reinterpret_cast<uintptr_t>(d_queries) % 16 == 0) &&
                            (reinterpret_cast<uintptr_t>(d_coded) % 16 == 0) && (D % 4 == 0);
-    if (aligned16) return run_encode<K, 4>(d_queries, d_coded, G, N, D, nodes, stream);
+    if constexpr (K >= APPROXIFER_ENCODE_MFMA_MIN_K) {
+        if (aligned16) return run_encode_mfma<(K + 3) / 4>(d_queries, d_coded, G, K, N, D, nodes, stream);
+    } else {
+        if (aligned16) return run_encode<K, 4>(d_queries, d_coded, G, N, D, nodes, stream);
+    }
     return run_encode<K, 1>(d_queries, d_coded, G, N, D, nodes, stream);
 }
 

@@ -49,6 +49,9 @@ def test_encode_tiny_workload(gpu):
     (1, 2, 5, 2), (2, 3, 1000, 3), (3, 5, 4100, 2), (5, 9, 1023, 3), (7, 16, 2048, 2), (12, 20, 4 * 700, 3),
     (16, 24, 4 * 300 + 4, 2), (17, 21, 777, 2), (32, 48, 4 * 513, 2), (33, 40, 258, 1), (64, 128, 4 * 260, 2),
     (8, 12, 3, 5), (12, 20, 1, 4),
+    # K > 16 with 16-byte rows: the matrix-core kernel; K % 4 != 0, N % 16 != 0, ragged column tiles
+    (17, 21, 4 * 100, 3), (20, 33, 4 * 65, 2), (22, 16, 4 * 64, 2), (24, 36, 4 * 700 + 4, 2), (31, 47, 4 * 3, 3),
+    (32, 48, 4 * 1024, 2), (47, 100, 4 * 129, 1), (63, 127, 4 * 77, 2), (64, 65, 4 * 64, 1), (18, 2, 4 * 50, 2),
 ])
 def test_encode_shapes_with_ragged_tails(gpu, K, N, D, G):
     torch, binding, dev = gpu
