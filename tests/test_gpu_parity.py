@@ -560,3 +560,76 @@ def test_byzantine_operating_points(gpu, E, sigma):
     assert np.array_equal(adv, adv_ref)
     assert np.array_equal(adv, adv_true)
     assert group_err(out, ref).max() <= TOL
+
+
+# --------------------------------------------------------------------------------------
+# seeded random shapes: every entry point, every limit in play
+# --------------------------------------------------------------------------------------
+def test_random_shapes_all_entry_points(gpu):
+    torch, binding, dev = gpu
+    rng = np.random.default_rng(20210909)
+    for trial in range(60):
+        K = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 11, 12, 13, 16, 17, 19, 24, 31, 32, 40, 64]))
+        S = int(rng.integers(0, 6))
+        N = int(min(128, max(2, K + S + int(rng.integers(0, 4)))))
+        S = min(S, N - 1)
+        D = int(rng.choice([1, 2, 3, 4, 7, 8, 60, 64, 252, 256, 260, 1000, 1023, 1024, 1028, 3072]))
+        C = int(rng.choice([1, 2, 3, 4, 5, 8, 10, 100, 252, 256, 260, 1000]))
+        G = int(rng.integers(1, 6))
+        mode = int(rng.integers(0, 2))
+        print("trial", trial, dict(K=K, N=N, S=S, D=D, C=C, G=G, mode=mode), flush=True)
+        alpha, beta = orc.chebyshev_nodes(K, N)
+        X = rng.standard_normal((G, K, D)).astype(np.float32)
+        coded = binding.approxifer_encode(torch.from_numpy(X).to(dev), alpha, beta).cpu().numpy()
+        assert group_err(coded, orc.encode(X, alpha, beta)).max() <= TOL
+        Y = rng.standard_normal((G, N, C)).astype(np.float32)
+        mask = np.zeros((G, N), np.uint8)
+        for g in range(G):
+            mask[g, rng.permutation(N)[: N - S]] = 1
+        Y[mask == 0] = np.nan
+        with np.errstate(all="ignore"):
+            ref, st_ref = orc.decode(Y, mask, alpha, beta, S, mode)
+        finite = np.all(np.isfinite(ref.reshape(G, -1)), axis=1)       # worker-index signs can hit an exact pole
+        out, st = binding.approxifer_decode(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev), alpha, beta, S, mode)
+        assert np.array_equal(st.cpu().numpy(), st_ref)
+        if finite.any():
+            assert group_err(out.cpu().numpy()[finite], ref[finite]).max() <= TOL
+        top1, score, st = binding.approxifer_decode_top1(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev),
+                                                         alpha, beta, S, mode)
+        if finite.any() and C > 1:
+            srt = np.sort(ref[finite], axis=-1)
+            clear = (srt[..., -1] - srt[..., -2]) > 1e-9 * np.abs(ref[finite]).max(axis=-1)
+            assert np.array_equal(top1.cpu().numpy()[finite][clear], ref[finite].argmax(-1)[clear])
+        # Byzantine decoder on a shape that satisfies its counting rule
+        A = int(rng.integers(1, 3))
+        Kb = int(rng.integers(1, 9))
+        Sb = int(rng.integers(0, 4))
+        Nb = 2 * (Kb + A) + Sb + int(rng.integers(0, 3))
+        if Nb % 2 == 1:
+            Nb += 1                                                     # keep the zero node out (Q(0) = 1)
+        alpha, beta = orc.chebyshev_nodes(Kb, Nb)
+        Xb = rng.uniform(0, 1, (G, Kb, 32))
+        Mf = rng.standard_normal((32, C))
+        clean = (orc.encode(Xb, alpha, beta) @ Mf).astype(np.float32)
+        maskb = np.zeros((G, Nb), np.uint8)
+        Yb = clean.copy()
+        for g in range(G):
+            avail = np.sort(rng.permutation(Nb)[: Nb - Sb])
+            maskb[g, avail] = 1
+            bad = rng.permutation(avail)[:A]
+            Yb[g, bad] += (10 * (clean.std() + 1e-3) * rng.standard_normal((A, C))).astype(np.float32)
+        outb, advb, stb = binding.approxifer_decode_byzantine(torch.from_numpy(Yb).to(dev), torch.from_numpy(maskb).to(dev),
+                                                              alpha, beta, Sb, A, 1)
+        refb, adv_ref, st_refb = orc.decode_byzantine(Yb, maskb, alpha, beta, Sb, A, 1)
+        assert np.array_equal(stb.cpu().numpy(), st_refb)
+        same = np.all(advb.cpu().numpy() == adv_ref, axis=1)
+        # with a single class, or tiny separations, a pick may sit on a rounding tie: demand agreement wherever
+        # the oracle's own vote is decisive, and never less than 90 % of groups
+        decisive = np.zeros(G, bool)
+        for g in range(G):
+            _, _, counts = orc.locate(Yb[g], np.nonzero(maskb[g])[0], beta, Kb, A)
+            top = np.sort(counts)[::-1]
+            decisive[g] = top[A - 1] - top[A] >= 2
+        assert np.all(same[decisive])
+        if same.any():
+            assert group_err(outb.cpu().numpy()[same], refb[same]).max() <= TOL
