@@ -55,9 +55,12 @@ extern "C" {
 #define APPROXIFER_SIGN_WORKER_INDEX 0
 #define APPROXIFER_SIGN_SURVIVOR_RANK 1
 
+/* Passed as S to the decoders: every group has its own number of stragglers, read off its mask. */
+#define APPROXIFER_S_FROM_MASK (-1)
+
 /* Per-group status values written to d_status. */
 #define APPROXIFER_GROUP_OK 0
-#define APPROXIFER_GROUP_BAD_MASK 1        /* the group's mask does not hold exactly N-S ones */
+#define APPROXIFER_GROUP_BAD_MASK 1        /* the group's mask does not hold an acceptable number of ones */
 
 /*
  * Chebyshev nodes of Section 3, "ApproxIFER Encoding":
@@ -102,6 +105,9 @@ int approxifer_encode(const float *d_queries, float *d_coded,
  *   d_status  [G] int32, device, written, or NULL.  A group whose mask does not hold
  *             exactly N-S non-zero bytes gets APPROXIFER_GROUP_BAD_MASK and its d_out
  *             rows are left untouched; every other group gets APPROXIFER_GROUP_OK.
+ *   S         number of stragglers of every group, 0 <= S < N, or APPROXIFER_S_FROM_MASK:
+ *             groups may then differ in how many workers returned (the formula of Section 3
+ *             holds for any non-empty F); only a group with no survivor at all is a bad mask.
  * Weights and accumulation are float64; each output is rounded to float32 once.
  */
 int approxifer_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_status,
@@ -124,7 +130,9 @@ int approxifer_decode(const float *d_preds, const uint8_t *d_mask, float *d_out,
  *   other arguments as approxifer_decode(); groups with a bad mask leave d_out and
  *   d_adv rows untouched.
  * Requires A >= 1, N - S >= 2 (K + A) (Section 3, eq. (3), the decoding condition) and
- * N - S <= APPROXIFER_MAX_AVAIL_BYZ.  A worker whose node is exactly 0 can never be
+ * N - S <= APPROXIFER_MAX_AVAIL_BYZ.  With S = APPROXIFER_S_FROM_MASK a group is decoded when its
+ * own number of available workers n satisfies 2 (K + A) <= n <= APPROXIFER_MAX_AVAIL_BYZ and gets
+ * APPROXIFER_GROUP_BAD_MASK otherwise.  A worker whose node is exactly 0 can never be
  * located, since Q(0) = 1 by construction; the Chebyshev worker nodes contain 0 only
  * when N is odd.
  */

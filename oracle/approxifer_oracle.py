@@ -139,7 +139,8 @@ def decode(Y, mask, alpha, beta, S, sign_mode=SIGN_WORKER_INDEX):
     Y is [G, W, C] coded predictions (rows of missing workers are never read),
     mask is [G, W] with 1 = returned.  Returns (out [G, K, C] float64, status [G]).
     status 0: decoded; status 1: the group's mask does not hold exactly W-S ones,
-    its output row is left at zero.
+    its output row is left at zero.  S = None (or negative): every group brings its own
+    straggler count; only a group without any survivor is refused.
     Section 3, "ApproxIFER Decoding", step 2: Y_hat_j = r(alpha_j).
     """
     Y = np.asarray(Y)
@@ -150,7 +151,7 @@ def decode(Y, mask, alpha, beta, S, sign_mode=SIGN_WORKER_INDEX):
     status = np.zeros(G, dtype=np.int32)
     for g in range(G):
         F = np.nonzero(mask[g] != 0)[0]
-        if F.size != W - S:
+        if (F.size != W - S) if (S is not None and S >= 0) else (F.size < 1):
             status[g] = 1
             continue
         Wd = decode_weights(alpha, beta, F, sign_mode)    # [K, |F|]
@@ -247,8 +248,8 @@ def decode_byzantine(Y, mask, alpha, beta, S, A, sign_mode=SIGN_WORKER_INDEX):
     status = np.zeros(G, dtype=np.int32)
     for g in range(G):
         avail = np.nonzero(mask[g] != 0)[0]
-        if avail.size != W - S:
-            status[g] = 1
+        if (avail.size != W - S) if (S is not None and S >= 0) else (avail.size < 2 * (K + A)):
+            status[g] = 1                                 # S None/negative: per-group count, Section 3 eq. (3) must hold
             continue
         adv[g], _, _ = locate(Y[g], avail, beta, K, A)
         F = np.setdiff1d(avail, adv[g])

@@ -19,6 +19,7 @@ MAX_N = 128
 MAX_AVAIL_BYZ = 64
 SIGN_WORKER_INDEX = 0
 SIGN_SURVIVOR_RANK = 1
+S_FROM_MASK = -1
 
 EXPORTS = (
     "approxifer_version",

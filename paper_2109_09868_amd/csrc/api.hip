@@ -42,7 +42,7 @@ const char *approxifer_strerror(int code) {
     switch (code) {
         case APPROXIFER_OK: return "ok";
         case APPROXIFER_ERR_NULL_POINTER: return "a required pointer is NULL";
-        case APPROXIFER_ERR_BAD_SHAPE: return "bad shape: need G,D,C >= 0, K >= 1, N >= 2, 0 <= S < N, A >= 1";
+        case APPROXIFER_ERR_BAD_SHAPE: return "bad shape: need G,D,C >= 0, K >= 1, N >= 2, -1 <= S < N, A >= 1";
         case APPROXIFER_ERR_LIMIT: return "size above the compiled limits (K <= 64, N <= 128, N-S <= 64 for the Byzantine decoder)";
         case APPROXIFER_ERR_BAD_NODES: return "nodes must be finite and pairwise distinct within each set";
         case APPROXIFER_ERR_TOO_FEW_WORKERS: return "the Byzantine decoder needs N - S >= 2 (K + A) available workers";
@@ -78,7 +78,7 @@ int approxifer_decode(const float *d_preds, const uint8_t *d_mask, float *d_out,
     Nodes nodes;
     const int rc = check_common(K, N, h_alpha, h_beta, &nodes);
     if (rc != APPROXIFER_OK) return rc;
-    if (S < 0 || S >= N) return APPROXIFER_ERR_BAD_SHAPE;
+    if (S < APPROXIFER_S_FROM_MASK || S >= N) return APPROXIFER_ERR_BAD_SHAPE;
     if (sign_mode != APPROXIFER_SIGN_WORKER_INDEX && sign_mode != APPROXIFER_SIGN_SURVIVOR_RANK)
         return APPROXIFER_ERR_BAD_SIGN_MODE;
     if (G == 0 || C == 0) return APPROXIFER_OK;
@@ -94,7 +94,7 @@ int approxifer_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t 
     Nodes nodes;
     const int rc = check_common(K, N, h_alpha, h_beta, &nodes);
     if (rc != APPROXIFER_OK) return rc;
-    if (S < 0 || S >= N) return APPROXIFER_ERR_BAD_SHAPE;
+    if (S < APPROXIFER_S_FROM_MASK || S >= N) return APPROXIFER_ERR_BAD_SHAPE;
     if (sign_mode != APPROXIFER_SIGN_WORKER_INDEX && sign_mode != APPROXIFER_SIGN_SURVIVOR_RANK)
         return APPROXIFER_ERR_BAD_SIGN_MODE;
     if (C > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;   // class indices are int32
@@ -111,11 +111,12 @@ int approxifer_decode_byzantine(const float *d_preds, const uint8_t *d_mask, flo
     Nodes nodes;
     const int rc = check_common(K, N, h_alpha, h_beta, &nodes);
     if (rc != APPROXIFER_OK) return rc;
-    if (S < 0 || S >= N || A < 1) return APPROXIFER_ERR_BAD_SHAPE;
+    if (S < APPROXIFER_S_FROM_MASK || S >= N || A < 1) return APPROXIFER_ERR_BAD_SHAPE;
     if (sign_mode != APPROXIFER_SIGN_WORKER_INDEX && sign_mode != APPROXIFER_SIGN_SURVIVOR_RANK)
         return APPROXIFER_ERR_BAD_SIGN_MODE;
-    if (N - S < 2 * (K + A)) return APPROXIFER_ERR_TOO_FEW_WORKERS;
-    if (N - S > APPROXIFER_MAX_AVAIL_BYZ) return APPROXIFER_ERR_LIMIT;
+    const int most_available = S < 0 ? N : N - S;
+    if (most_available < 2 * (K + A)) return APPROXIFER_ERR_TOO_FEW_WORKERS;
+    if (S >= 0 && N - S > APPROXIFER_MAX_AVAIL_BYZ) return APPROXIFER_ERR_LIMIT;
     if (G == 0 || C == 0) return APPROXIFER_OK;
     if (d_mask == nullptr || d_adv == nullptr || d_preds == nullptr || d_out == nullptr)
         return APPROXIFER_ERR_NULL_POINTER;

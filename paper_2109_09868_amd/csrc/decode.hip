@@ -210,9 +210,9 @@ __global__ void decode_kernel(const float *__restrict__ preds, const uint8_t *__
                               int64_t C, int64_t Cv, int64_t ctiles, int sign_mode, const Nodes nodes) {
     extern __shared__ double lds_d[];
     const int KP = round_up4(K);
-    const int nF_expected = N - S;
+    const int nF_cap = S < 0 ? N : N - S;          // S < 0: every group brings its own straggler count
     double *WdT = lds_d;
-    double *alpha_s = WdT + nF_expected * KP;
+    double *alpha_s = WdT + nF_cap * KP;
     double *beta_s = alpha_s + K;
     int *F = reinterpret_cast<int *>(beta_s + N);
     int *n_sh = F + N;
@@ -221,14 +221,14 @@ __global__ void decode_kernel(const float *__restrict__ preds, const uint8_t *__
     const int64_t ct = blockIdx.x - g * ctiles;
 
     stage_nodes(nodes, K, N, alpha_s, beta_s);
-    for (int e = threadIdx.x; e < nF_expected * KP; e += blockDim.x) WdT[e] = 0.0;
+    for (int e = threadIdx.x; e < nF_cap * KP; e += blockDim.x) WdT[e] = 0.0;
     if (wave_id() == 0) {
         const int n = survivors_from_mask(mask + g * N, N, F);
         if (lane_id() == 0) *n_sh = n;
     }
     __syncthreads();
     const int nF = *n_sh;
-    const bool good = nF == nF_expected;
+    const bool good = S < 0 ? nF >= 1 : nF == nF_cap;
     if (ct == 0 && threadIdx.x == 0 && status != nullptr)
         status[g] = good ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
     if (!good) return;
@@ -273,23 +273,23 @@ __global__ void decode_top1_kernel(const float *__restrict__ preds, const uint8_
     typedef typename PredVec<VEC>::type V;
     extern __shared__ double lds_d[];
     const int KP = round_up4(K);
-    const int nF_expected = N - S;
+    const int nF_cap = S < 0 ? N : N - S;          // S < 0: every group brings its own straggler count
     double *WdT = lds_d;
-    double *alpha_s = WdT + nF_expected * KP;
+    double *alpha_s = WdT + nF_cap * KP;
     double *beta_s = alpha_s + K;
     int *F = reinterpret_cast<int *>(beta_s + N);
     int *n_sh = F + N;
     const int64_t g = blockIdx.x;
 
     stage_nodes(nodes, K, N, alpha_s, beta_s);
-    for (int e = threadIdx.x; e < nF_expected * KP; e += blockDim.x) WdT[e] = 0.0;
+    for (int e = threadIdx.x; e < nF_cap * KP; e += blockDim.x) WdT[e] = 0.0;
     if (wave_id() == 0) {
         const int n = survivors_from_mask(mask + g * N, N, F);
         if (lane_id() == 0) *n_sh = n;
     }
     __syncthreads();
     const int nF = *n_sh;
-    const bool good = nF == nF_expected;
+    const bool good = S < 0 ? nF >= 1 : nF == nF_cap;
     if (threadIdx.x == 0 && status != nullptr) status[g] = good ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
     if (!good) return;
     decoder_weights(alpha_s, beta_s, F, nF, K, KP, sign_mode, WdT);
@@ -493,15 +493,15 @@ __global__ void decode_byzantine_kernel(const float *__restrict__ preds, const u
     extern __shared__ double lds_d[];
     const int KP = round_up4(K);
     const int M = K + A;
-    const int n_expected = N - S;
-    const int nF = n_expected - A;
+    const int n_cap = S < 0 ? (N < APPROXIFER_MAX_AVAIL_BYZ ? N : APPROXIFER_MAX_AVAIL_BYZ) : N - S;   // layout capacity
+    const int nF_cap = n_cap - A;
     const int nw = blockDim.x / kWave;
-    const int wave_doubles = cpw * (n_expected * 2 * M + M + n_expected);
+    const int wave_doubles = cpw * (n_cap * 2 * M + M + n_cap);
 
     double *scratch = lds_d;
     double *WdT = scratch + static_cast<size_t>(nw) * wave_doubles;
-    double *xs = WdT + nF * KP;
-    double *alpha_s = xs + n_expected;
+    double *xs = WdT + nF_cap * KP;
+    double *alpha_s = xs + n_cap;
     double *beta_s = alpha_s + K;
     int *avail = reinterpret_cast<int *>(beta_s + N);
     int *F = avail + N;
@@ -515,7 +515,7 @@ __global__ void decode_byzantine_kernel(const float *__restrict__ preds, const u
     const float *pg = preds + static_cast<size_t>(g) * N * C;
 
     stage_nodes(nodes, K, N, alpha_s, beta_s);
-    for (int e = threadIdx.x; e < nF * KP; e += blockDim.x) WdT[e] = 0.0;
+    for (int e = threadIdx.x; e < nF_cap * KP; e += blockDim.x) WdT[e] = 0.0;
     for (int e = threadIdx.x; e < N; e += blockDim.x) votes[e] = 0;
     if (wv == 0) {
         const int n = survivors_from_mask(mask + g * N, N, avail);
@@ -523,7 +523,8 @@ __global__ void decode_byzantine_kernel(const float *__restrict__ preds, const u
     }
     __syncthreads();
     const int n = *n_sh;
-    const bool good = n == n_expected;
+    const bool good = S < 0 ? (n >= 2 * M && n <= n_cap) : n == n_cap;
+    const int nF = n - A;
     if (threadIdx.x == 0 && status != nullptr) status[g] = good ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
     if (!good) return;
 
@@ -584,7 +585,7 @@ int launch_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int
     if (blocks > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
     int waves = KP / 4;
     if (waves > 4) waves = 4;
-    const size_t lds = sizeof(double) * (static_cast<size_t>(N - S) * KP + K + N) + sizeof(int) * (static_cast<size_t>(N) + 2);
+    const size_t lds = sizeof(double) * (static_cast<size_t>(S < 0 ? N : N - S) * KP + K + N) + sizeof(int) * (static_cast<size_t>(N) + 2);
     const dim3 grid(static_cast<unsigned>(blocks)), block(waves * kWave);
     if (lds > 64 * 1024) {   // only K = 64 with more than 127 survivors; gfx950 has 160 KB of LDS per CU
         const void *fn = vec4 ? reinterpret_cast<const void *>(decode_kernel<4>)
@@ -615,7 +616,7 @@ int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_t
     if (slices < 1) slices = 1;
     const int waves = KQ <= 16 ? KQ * slices : 16;
     // int F[N] | int n | 1 pad int  keeps the Best array that follows 16-byte aligned when N is even; round up
-    size_t lds = sizeof(double) * (static_cast<size_t>(N - S) * KP + K + N) + sizeof(int) * (static_cast<size_t>(N) + 3);
+    size_t lds = sizeof(double) * (static_cast<size_t>(S < 0 ? N : N - S) * KP + K + N) + sizeof(int) * (static_cast<size_t>(N) + 3);
     lds += 16 + sizeof(double) * 2 * static_cast<size_t>(KP) * (waves >= KQ ? waves / KQ : 1);
     const dim3 grid(static_cast<unsigned>(G)), block(waves * kWave);
     if (lds > 64 * 1024) {
@@ -637,7 +638,7 @@ int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *
                             int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C, const Nodes &nodes,
                             int sign_mode, hipStream_t stream) {
     const int KP = (K + 3) & ~3;
-    const int n = N - S;
+    const int n = S < 0 ? (N < APPROXIFER_MAX_AVAIL_BYZ ? N : APPROXIFER_MAX_AVAIL_BYZ) : N - S;   // capacity
     const int M = K + A;
     const bool vec4 = (C % 4 == 0) && aligned16(d_preds) && aligned16(d_out);
     const int64_t Cv = vec4 ? C / 4 : C;

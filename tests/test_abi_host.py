@@ -42,6 +42,7 @@ def test_header_constants_match_binding():
     assert int(consts["APPROXIFER_MAX_K"]) == binding.MAX_K
     assert int(consts["APPROXIFER_MAX_N"]) == binding.MAX_N
     assert int(consts["APPROXIFER_MAX_AVAIL_BYZ"]) == binding.MAX_AVAIL_BYZ
+    assert int(consts["APPROXIFER_S_FROM_MASK"]) == binding.S_FROM_MASK == -1
     assert int(consts["APPROXIFER_SIGN_WORKER_INDEX"]) == binding.SIGN_WORKER_INDEX == orc.SIGN_WORKER_INDEX
     assert int(consts["APPROXIFER_SIGN_SURVIVOR_RANK"]) == binding.SIGN_SURVIVOR_RANK == orc.SIGN_SURVIVOR_RANK
 
@@ -91,7 +92,7 @@ def test_host_validation_codes(lib):
 
     dec = lib.approxifer_decode
     assert dec(fake, fake, fake, None, 1, 4, 6, 6, 3, _dp(a), _dp(b), 0, None) == -2      # S >= N
-    assert dec(fake, fake, fake, None, 1, 4, 6, -1, 3, _dp(a), _dp(b), 0, None) == -2
+    assert dec(fake, fake, fake, None, 1, 4, 6, -2, 3, _dp(a), _dp(b), 0, None) == -2
     assert dec(fake, fake, fake, None, 1, 4, 6, 2, 3, _dp(a), _dp(b), 2, None) == -6
     assert dec(fake, None, fake, None, 1, 4, 6, 2, 3, _dp(a), _dp(b), 0, None) == -1
     assert dec(None, None, None, None, 0, 4, 6, 2, 3, _dp(a), _dp(b), 1, None) == 0
@@ -107,6 +108,9 @@ def test_host_validation_codes(lib):
     a8, b24 = orc.chebyshev_nodes(8, 24)
     assert byz(fake, fake, fake, fake, None, 1, 8, 24, 4, 0, 3, _dp(a8), _dp(b24), 0, None) == -2   # A < 1
     assert byz(fake, fake, fake, fake, None, 1, 8, 24, 5, 2, 3, _dp(a8), _dp(b24), 0, None) == -5   # 19 < 20
+    a8b, b18 = orc.chebyshev_nodes(8, 18)
+    assert byz(fake, fake, fake, fake, None, 1, 8, 18, -1, 2, 3, _dp(a8b), _dp(b18), 0, None) == -5   # even all 18 < 20
+    assert byz(fake, fake, fake, fake, None, 1, 8, 24, -2, 2, 3, _dp(a8), _dp(b24), 0, None) == -2
     assert byz(fake, fake, fake, None, None, 1, 8, 24, 4, 2, 3, _dp(a8), _dp(b24), 0, None) == -1
     a2, b100 = orc.chebyshev_nodes(2, 100)
     assert byz(fake, fake, fake, fake, None, 1, 2, 100, 0, 1, 3, _dp(a2), _dp(b100), 0, None) == -3  # N-S > 64

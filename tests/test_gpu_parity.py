@@ -563,6 +563,74 @@ def test_byzantine_operating_points(gpu, E, sigma):
 
 
 # --------------------------------------------------------------------------------------
+# per-group straggler counts (S = APPROXIFER_S_FROM_MASK): ragged masks
+# --------------------------------------------------------------------------------------
+@pytest.mark.parametrize("K,N,C,G", [(3, 9, 5, 12), (8, 12, 100, 40), (12, 20, 1000, 24), (16, 70, 36, 10), (5, 128, 3, 9)])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_decode_ragged_masks(gpu, K, N, C, G, mode):
+    torch, binding, dev = gpu
+    rng = np.random.default_rng(K * 17 + N + mode)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    Y = rng.standard_normal((G, N, C)).astype(np.float32)
+    mask = np.zeros((G, N), np.uint8)
+    counts = rng.integers(1, N + 1, G)
+    counts[0], counts[1], counts[2] = N, 1, 0                 # everyone, a single survivor, nobody
+    for g in range(G):
+        mask[g, rng.permutation(N)[: counts[g]]] = 1
+    Y[mask == 0] = np.nan
+    out = torch.full((G, K, C), -9.0, dtype=torch.float32, device=dev)
+    out, st = binding.approxifer_decode(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev), alpha, beta,
+                                        binding.S_FROM_MASK, mode, out=out)
+    with np.errstate(all="ignore"):
+        ref, st_ref = orc.decode(Y, mask, alpha, beta, None, mode)
+    out, st = out.cpu().numpy(), st.cpu().numpy()
+    assert np.array_equal(st, st_ref) and st[2] == 1 and st.sum() == 1
+    assert np.all(out[2] == -9.0)
+    finite = np.all(np.isfinite(ref.reshape(G, -1)), axis=1) & (st == 0)
+    assert finite.sum() >= G - 3
+    assert group_err(out[finite], ref[finite]).max() <= TOL
+    assert np.array_equal(out[1], np.broadcast_to(Y[1, np.nonzero(mask[1])[0][0]], (K, C)))
+    top1, score, st1 = binding.approxifer_decode_top1(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev),
+                                                      alpha, beta, binding.S_FROM_MASK, mode)
+    assert np.array_equal(st1.cpu().numpy(), st_ref)
+    if C > 1:
+        srt = np.sort(ref[finite], axis=-1)
+        clear = (srt[..., -1] - srt[..., -2]) > 1e-9 * np.abs(ref[finite]).max(axis=-1)
+        assert np.array_equal(top1.cpu().numpy()[finite][clear], ref[finite].argmax(-1)[clear])
+
+
+def test_byzantine_ragged_masks(gpu):
+    torch, binding, dev = gpu
+    K, A, N, C, G = 4, 2, 20, 10, 48
+    rng = np.random.default_rng(404)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    X = rng.uniform(0, 1, (G, K, 64))
+    Mf = rng.standard_normal((64, C)) / 8
+    clean = (orc.encode(X, alpha, beta) @ Mf).astype(np.float32)
+    mask = np.zeros((G, N), np.uint8)
+    Y = clean.copy()
+    counts = rng.integers(2 * (K + A), N + 1, G)
+    counts[0], counts[1], counts[2] = N, 2 * (K + A), 2 * (K + A) - 1   # all, the minimum of eq. (3), one too few
+    adv_true = np.full((G, A), -1, np.int32)
+    for g in range(G):
+        avail = np.sort(rng.permutation(N)[: counts[g]])
+        mask[g, avail] = 1
+        adv_true[g] = np.sort(rng.permutation(avail)[:A])
+        Y[g, adv_true[g]] += (10 * clean.std() * rng.standard_normal((A, C))).astype(np.float32)
+    out = torch.full((G, K, C), -3.0, dtype=torch.float32, device=dev)
+    adv = torch.full((G, A), -7, dtype=torch.int32, device=dev)
+    out, adv, st = binding.approxifer_decode_byzantine(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev),
+                                                       alpha, beta, binding.S_FROM_MASK, A, 1, out=out, adv=adv)
+    ref, adv_ref, st_ref = orc.decode_byzantine(Y, mask, alpha, beta, None, A, 1)
+    out, adv, st = out.cpu().numpy(), adv.cpu().numpy(), st.cpu().numpy()
+    assert np.array_equal(st, st_ref) and st[2] == 1 and st.sum() == 1
+    assert np.all(out[2] == -3.0) and np.all(adv[2] == -7)
+    good = st == 0
+    assert np.array_equal(adv[good], adv_ref[good]) and np.array_equal(adv[good], adv_true[good])
+    assert group_err(out[good], ref[good]).max() <= TOL
+
+
+# --------------------------------------------------------------------------------------
 # seeded random shapes: every entry point, every limit in play
 # --------------------------------------------------------------------------------------
 def test_random_shapes_all_entry_points(gpu):

@@ -274,3 +274,31 @@ def test_worker_index_signs_can_have_a_real_pole():
     w1 = orc.decode_weights(alpha, beta, F, 1)
     assert not np.all(np.isfinite(w0[1]))
     assert np.all(np.isfinite(w1)) and np.allclose(w1.sum(axis=1), 1.0)
+
+
+def test_decode_with_per_group_straggler_counts():
+    # S = None: each group is decoded over however many workers its own mask names; that must equal
+    # decoding the group alone with its own count, and a mask without survivors is refused
+    K, W, C = 3, 9, 5
+    alpha, beta = orc.chebyshev_nodes(K, W)
+    rng = np.random.default_rng(21)
+    Y = rng.standard_normal((6, W, C))
+    mask = np.zeros((6, W), np.uint8)
+    counts = [9, 1, 4, 0, 3, 7]
+    for g, n in enumerate(counts):
+        mask[g, rng.permutation(W)[:n]] = 1
+    for mode in (0, 1):
+        out, st = orc.decode(Y, mask, alpha, beta, None, mode)
+        assert list(st) == [0, 0, 0, 1, 0, 0]
+        assert np.all(out[3] == 0)
+        for g, n in enumerate(counts):
+            if n == 0:
+                continue
+            one, st1 = orc.decode(Y[g:g + 1], mask[g:g + 1], alpha, beta, W - n, mode)
+            assert st1[0] == 0 and np.array_equal(out[g], one[0])
+        # a single survivor: every query gets that worker's prediction (replication, weights = 1)
+        only = np.nonzero(mask[1])[0][0]
+        assert np.allclose(out[1], Y[1, only][None, :], rtol=0, atol=0)
+    out_neg, st_neg = orc.decode(Y, mask, alpha, beta, -1, 0)
+    ref, _ = orc.decode(Y, mask, alpha, beta, None, 0)
+    assert np.array_equal(out_neg, ref)

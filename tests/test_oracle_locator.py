@@ -196,3 +196,29 @@ def test_decode_byzantine_status():
     out, adv, st = orc.decode_byzantine(Y, mask, alpha, beta, S, A)
     assert list(st) == [0, 1] and np.all(out[1] == 0) and np.all(adv[1] == -1)
     assert adv[0, 0] != 2              # a straggler can never be named an adversary
+
+
+def test_decode_byzantine_with_per_group_straggler_counts():
+    # S = None: groups differ in how many workers returned; each needs 2(K+A) of them (eq. (3))
+    K, A, W, C = 2, 1, 10, 4
+    alpha, beta = orc.chebyshev_nodes(K, W)
+    rng = np.random.default_rng(8)
+    X = rng.uniform(0, 1, (4, K, 16))
+    Mf = rng.standard_normal((16, C))
+    Y = orc.encode(X, alpha, beta) @ Mf                    # exactly rational in beta
+    mask = np.zeros((4, W), np.uint8)
+    counts = [10, 6, 5, 8]                                 # 5 < 2(K+A) = 6: refused
+    planted = []
+    for g, n in enumerate(counts):
+        avail = np.sort(rng.permutation(W)[:n])
+        mask[g, avail] = 1
+        bad = int(rng.permutation(avail)[0])
+        planted.append(bad)
+        Y[g, bad] += 5.0 * rng.standard_normal(C)
+    out, adv, st = orc.decode_byzantine(Y, mask, alpha, beta, None, A)
+    assert list(st) == [0, 0, 1, 0]
+    assert np.all(out[2] == 0) and adv[2, 0] == -1
+    for g in (0, 1, 3):
+        assert adv[g, 0] == planted[g]
+        one, adv1, st1 = orc.decode_byzantine(Y[g:g + 1], mask[g:g + 1], alpha, beta, W - counts[g], A)
+        assert st1[0] == 0 and np.array_equal(out[g], one[0]) and np.array_equal(adv[g], adv1[0])
