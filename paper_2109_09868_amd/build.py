@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libapproxifer.so")
-SOURCES = ["api.hip", "encode.hip", "decode.hip"]
+SOURCES = ["api.hip", "encode.hip", "decode.hip", "byzantine.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",

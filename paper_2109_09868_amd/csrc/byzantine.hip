@@ -1,0 +1,690 @@
+// ApproxIFER Byzantine decoder for gfx950: Algorithm 2 (error locator) followed by the decoder of
+// Section 3, "ApproxIFER Decoding", one workgroup per group.
+//
+// Algorithm 2 fits, per class c, polynomials P (degree M-1) and Q (degree M-1, Q_0 = 1), M = K+A, to
+//     P(x_r) - y_rc Q(x_r) = 0        over the n available workers (x_r their nodes),
+// in the least-squares sense, reads a_r = Q(x_r), lets the A smallest |a_r| of every class vote and
+// returns the A most voted workers.  The system is  V p + C_c q = y_c  with V the n x M Vandermonde
+// matrix of the nodes and C_c = -diag(y_c) V[:, 1:].
+//
+// Two kernels compute the same thing:
+//
+//  * decode_byzantine_proj_kernel (K+A <= 16, at most 48 available workers, n-M <= 32).  V is the
+//    same for every class of a group, so its Householder QR is done ONCE per group, by one wave
+//    with one lane per column of [V | I] held in registers (pivot columns travel by v_readlane):
+//    that leaves U = the last n-M rows of Q^T, an orthonormal basis of range(V)'s complement, in
+//    LDS.  Eliminating p exactly, class c only has to solve the (n-M) x (M-1) problem
+//        min_q || U C_c q - U y_c ||,
+//    so a class needs 16 lanes (lane = column, 15 = right-hand side), four classes share a wave, the
+//    projected system is formed with U broadcast from LDS, and its Householder QR runs entirely in
+//    registers: the pivot column reaches the other lanes of the class through DPP row broadcasts.
+//    No LDS traffic and no barrier inside either factorisation.
+//
+//  * decode_byzantine_general_kernel (everything else up to 64 available workers).  A class owns
+//    2M neighbouring lanes, lane j owns COLUMN j of the full n x (2M-1) system, which sits in LDS
+//    row-major; a Householder step walks down the pivot column (an LDS broadcast).
+//
+// Both finish the same way: Q by back substitution, a_r = Q(x_r) by Horner's rule, rank of |a_r| by
+// counting (equal magnitudes: smaller worker index first), votes in an LDS histogram, the A most
+// voted workers (equal counts: smaller index first) leave the available list, and the workgroup
+// decodes the group over the rest.
+#include "decode_common.h"
+
+namespace approxifer {
+namespace {
+
+// ------------------------------------------------------------------------------------------------
+// shared tail: vote -> located adversaries -> F -> decode
+// ------------------------------------------------------------------------------------------------
+// Called by the whole workgroup after every vote has been added (and a barrier).  sel/F are LDS
+// scratch of N ints each; n <= 64.
+template <int VEC>
+__device__ __forceinline__ void contract_group(const float *__restrict__ pg, float *__restrict__ og, const int *F, int nF,
+                                               int K, int KP, int64_t C, int64_t Cv, const double *WdT) {
+    for (int64_t cv0 = 0; cv0 < Cv; cv0 += kColsPerTile) {
+        const int64_t cv1 = (cv0 + kColsPerTile < Cv) ? cv0 + kColsPerTile : Cv;
+        typename PredVec<VEC>::type unused[kRowChunk];
+        contract_tile<VEC, false>(pg, og, F, nF, K, KP, C, cv0, cv1, WdT, unused);
+    }
+}
+
+// The A most voted workers (equal counts: smaller index first) go to adv_g in ascending order; F = the
+// available workers without them (ascending), Fpos = their positions in `avail`.  Called by the whole
+// workgroup after every vote has been added and a barrier; ends with a barrier.  n <= 64.
+__device__ __forceinline__ void select_adversaries(int32_t *__restrict__ adv_g, const int *avail, int n, int N, int A,
+                                                   const int *votes, int *sel, int *F, int *Fpos) {
+    for (int i = threadIdx.x; i < N; i += blockDim.x) {
+        const int mine = votes[i];
+        int rank = 0;
+#pragma unroll 8
+        for (int o = 0; o < N; ++o) {
+            const int v = votes[o];
+            rank += (v > mine || (v == mine && o < i)) ? 1 : 0;
+        }
+        sel[i] = rank < A ? 1 : 0;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < N; i += blockDim.x) {
+        if (sel[i]) {
+            int pos = 0;
+            for (int o = 0; o < i; ++o) pos += sel[o];
+            adv_g[pos] = i;
+        }
+    }
+    if (wave_id() == 0) {
+        const int lane = lane_id();
+        const bool keep = (lane < n) && !sel[avail[lane]];
+        const unsigned long long m = __ballot(keep);
+        if (keep) {
+            const int pos = __popcll(m & ((1ull << lane) - 1ull));
+            F[pos] = avail[lane];
+            Fpos[pos] = lane;
+        }
+    }
+    __syncthreads();
+}
+
+// vec4: prediction rows are 16-byte aligned and C % 4 == 0, Cv = C / 4; else Cv = C.
+__device__ __forceinline__ void finish_group(const float *__restrict__ pg, float *__restrict__ og,
+                                             int32_t *__restrict__ adv_g, const int *avail, int n, int N, int A, int K,
+                                             int KP, int64_t C, int64_t Cv, bool vec4, int sign_mode,
+                                             const double *alpha_s, const double *beta_s, const int *votes, int *sel,
+                                             int *F, int *Fpos, double *WdT) {
+    select_adversaries(adv_g, avail, n, N, A, votes, sel, F, Fpos);
+    const int nF = n - A;
+    decoder_weights(alpha_s, beta_s, F, nF, K, KP, sign_mode, WdT);
+    __syncthreads();
+    if (vec4) contract_group<4>(pg, og, F, nF, K, KP, C, Cv, WdT);
+    else contract_group<1>(pg, og, F, nF, K, KP, C, Cv, WdT);
+}
+
+// Rank of |a_r| among the n rows of one class (LDS key[n]); the A smallest vote for their worker.
+// Called by the lanes of one class, lane j of `width` handling rows j, j+width, ..
+__device__ __forceinline__ void pick_and_vote(const double *key, const int *avail, int n, int A, int j, int width,
+                                              int *votes) {
+    for (int r = j; r < n; r += width) {
+        const double mine = key[r];
+        int rank = 0;                                  // equal magnitudes keep ascending worker order
+        for (int o = 0; o < n; ++o) {
+            const double other = key[o];
+            rank += (other < mine || (other == mine && o < r)) ? 1 : 0;
+        }
+        if (rank < A) atomicAdd(&votes[avail[r]], 1);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// projected kernel: shared QR of the Vandermonde block, per-class QR in registers
+// ------------------------------------------------------------------------------------------------
+constexpr int kClsLanes = 16;      // lanes per class (one DPP row)
+constexpr int kClsPerWave = 4;
+constexpr int kPwStride = 16;      // powers table row: x^0 .. x^15
+constexpr int kProjMaxM = 16;      // M - 1 <= 15 unknown columns in lanes 0..14, right-hand side in lane 15
+
+template <int LANE>
+__device__ __forceinline__ double row_bcast(double v) {   // lane LANE of every 16-lane row, to the whole row
+    // all rows and banks enabled and every source lane exists: the 'old' operand is never used, and with
+    // bound_ctrl set the compiler knows it and does not materialise it
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), 0x150 + LANE, 0xF, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), 0x150 + LANE, 0xF, 0xF, true);
+    return __hiloint2double(hi, lo);
+}
+
+// Householder reflector of a pivot column x (rows k..): returns alpha = -sign(x_k) ||x|| and the factor
+// f = 2 v^T a / (v^T v) for a column a, v = x - alpha e_k, given sigma = x^T x, d = x^T a.
+struct Reflector {
+    double alpha, f;
+    bool degenerate;
+};
+__device__ __forceinline__ Reflector reflector(double sigma, double d, double xkk, double akj) {
+    Reflector h;
+    h.degenerate = !(sigma > 0.0);
+    const double nrm = sqrt(sigma);
+    h.alpha = (xkk >= 0.0) ? -nrm : nrm;
+    const double scale = 1.0 / (sigma - h.alpha * xkk);   // 2 / (v^T v)
+    h.f = scale * (d - h.alpha * akj);
+    return h;
+}
+
+// ---- once per group: U = rows M..n-1 of Q^T, V = Q R (one wave; lane = column of [V | I]) ----------
+template <int K0, int NB>
+struct SharedQrSteps {
+    static __device__ __forceinline__ void run(double (&col)[NB], int lane, int M) {
+        if (K0 < M) {
+            double sg[2] = {0.0, 0.0}, dt[2] = {0.0, 0.0};   // two partial sums each: shorter dependency chains
+#pragma unroll
+            for (int r = K0; r < NB; ++r) {
+                const double vr = read_lane(col[r], K0);
+                sg[(r - K0) & 1] = fma(vr, vr, sg[(r - K0) & 1]);
+                dt[(r - K0) & 1] = fma(vr, col[r], dt[(r - K0) & 1]);
+            }
+            const double xkk = read_lane(col[K0], K0);
+            const Reflector h = reflector(sg[0] + sg[1], dt[0] + dt[1], xkk, col[K0]);
+            if (!h.degenerate && lane > K0) {
+                col[K0] = fma(-h.f, xkk - h.alpha, col[K0]);
+#pragma unroll
+                for (int r = K0 + 1; r < NB; ++r) col[r] = fma(-h.f, read_lane(col[r], K0), col[r]);
+            }
+            SharedQrSteps<K0 + 1, NB>::run(col, lane, M);
+        }
+    }
+};
+template <int NB>
+struct SharedQrSteps<kProjMaxM, NB> {
+    static __device__ __forceinline__ void run(double (&)[NB], int, int) {}
+};
+
+// Pw[r][e] = x_r^e (LDS), n rows, M <= 16 columns.  Writes Ush[i][r] = U[i][r], i < RM, row stride NB.
+template <int NB, int RM>
+__device__ __forceinline__ void shared_complement_basis(const double *Pw, int n, int M, double *Ush) {
+    const int lane = lane_id();
+    double col[NB];
+    const bool vandermonde = lane < M;                // lanes 0..M-1: V; lanes M..M+n-1: the identity
+    const int e = vandermonde ? lane : 0;
+#pragma unroll
+    for (int r = 0; r < NB; ++r) {
+        const double p = Pw[(r < n ? r : 0) * kPwStride + e];
+        col[r] = (r < n) ? (vandermonde ? p : (lane - M == r ? 1.0 : 0.0)) : 0.0;
+    }
+    SharedQrSteps<0, NB>::run(col, lane, M);
+    const int r_out = lane - M;                     // this lane holds column r_out of Q^T
+    if (r_out >= 0 && r_out < n) {
+#pragma unroll
+        for (int row = 2; row < NB; ++row) {        // M >= 2 always
+            const int i = row - M;
+            if (i >= 0 && i < RM) Ush[i * NB + r_out] = col[row];
+        }
+    }
+}
+
+// ---- per class: Householder QR of the projected system, in registers ----------------------------
+// Steps K0 .. KEND-1 (those below `cols`); KEND = min(15, RM - 1) bounds the unrolling: cols <= R - 1 <= RM - 1.
+template <int K0, int KEND, int RM>
+struct ClassQrSteps {
+    static __device__ __forceinline__ void run(double (&a)[RM], int j, int cols) {
+        if (K0 < cols) {
+            double v[RM];
+            double sg[2] = {0.0, 0.0}, dt[2] = {0.0, 0.0};   // two partial sums each: shorter dependency chains
+#pragma unroll
+            for (int r = K0; r < RM; ++r) {
+                v[r] = row_bcast<K0>(a[r]);
+                sg[(r - K0) & 1] = fma(v[r], v[r], sg[(r - K0) & 1]);
+                dt[(r - K0) & 1] = fma(v[r], a[r], dt[(r - K0) & 1]);
+            }
+            const Reflector h = reflector(sg[0] + sg[1], dt[0] + dt[1], v[K0], a[K0]);
+            if (!h.degenerate) {
+                if (j > K0) {
+                    a[K0] = fma(-h.f, v[K0] - h.alpha, a[K0]);
+#pragma unroll
+                    for (int r = K0 + 1; r < RM; ++r) a[r] = fma(-h.f, v[r], a[r]);
+                } else if (j == K0) {
+                    a[K0] = h.alpha;                // R[k][k]
+                }
+            }
+            ClassQrSteps<K0 + 1, KEND, RM>::run(a, j, cols);
+        }
+    }
+};
+template <int KEND, int RM>
+struct ClassQrSteps<KEND, KEND, RM> {
+    static __device__ __forceinline__ void run(double (&)[RM], int, int) {}
+};
+
+// Back substitution R q = rhs over the first `cols` rows; column t of R sits in lane t of the row, the
+// transformed right-hand side in lane 15.  Every lane of the class ends with the whole solution.
+template <int T, int NS, int RM>
+struct BackSubst {
+    static __device__ __forceinline__ void run(const double (&a)[RM], double (&s)[NS], double (&q)[NS], int cols) {
+        if (T < cols) {
+            q[T] = s[T] / row_bcast<T>(a[T]);
+#pragma unroll
+            for (int i = 0; i < T; ++i) s[i] = fma(-row_bcast<T>(a[i]), q[T], s[i]);
+        }
+        BackSubst<T - 1, NS, RM>::run(a, s, q, cols);
+    }
+};
+template <int NS, int RM>
+struct BackSubst<-1, NS, RM> {
+    static __device__ __forceinline__ void run(const double (&)[RM], double (&)[NS], double (&)[NS], int) {}
+};
+
+// (value, row) minimum over the 16 lanes of a class: smaller value first, equal values: smaller row.
+template <int CTRL>
+__device__ __forceinline__ void row_min_step(double &v, int &i) {
+    const double ov = dpp_exchange<CTRL>(v);
+    const int oi = __builtin_amdgcn_update_dpp(0, i, CTRL, 0xF, 0xF, true);
+    const bool take = ov < v || (ov == v && oi < i);
+    v = take ? ov : v;
+    i = take ? oi : i;
+}
+
+// Algorithm 2, steps 1-5, for the four classes c_rel..c_rel+3 of the staged class tile, by one wave.
+//   Ysh[NB][CW] float: predictions of the available workers, row r = r-th available worker, zero past n and
+//   past the last class;  Ush[RM][NB], Pw[NB][16] (rows past n zero), xs[n]: the group's LDS.
+template <int NB, int RM>
+__device__ __forceinline__ void locate_classes_proj(const float *Ysh, int CW, int c_rel, bool live, const int *avail,
+                                                    const double *xs, const double *Pw, const double *Ush, int n,
+                                                    int M, int A, int *votes) {
+    typedef double v2d __attribute__((ext_vector_type(2)));
+    const int lane = lane_id();
+    const int cl = lane / kClsLanes;
+    const int j = lane % kClsLanes;
+    const int cols = M - 1;                               // unknowns Q_1 .. Q_{M-1}
+    const float *ysc = Ysh + c_rel + cl;                  // this class's column of the tile
+
+    // column of this lane: -y x^(j+1) for the unknown Q_(j+1), y for the right-hand side, 0 on idle lanes
+    const int e = j < cols ? j + 1 : 0;
+    const double sgn = j < cols ? -1.0 : (j == kClsLanes - 1 ? 1.0 : 0.0);
+    double a[RM];
+#pragma unroll
+    for (int i = 0; i < RM; ++i) a[i] = 0.0;
+    const v2d *U2 = reinterpret_cast<const v2d *>(Ush);   // NB is even: row stride NB/2 pairs
+    // rows past n contribute exact zeros (Ysh, Pw and the columns of Ush are zero there): no bound on r,
+    // so every load of this block is independent of every other and can be issued ahead of the arithmetic
+#pragma unroll
+    for (int r = 0; r < NB; r += 2) {
+        const double c0v = sgn * static_cast<double>(ysc[r * CW]) * Pw[r * kPwStride + e];
+        const double c1v = sgn * static_cast<double>(ysc[(r + 1) * CW]) * Pw[(r + 1) * kPwStride + e];
+#pragma unroll
+        for (int i = 0; i < RM; ++i) {
+            const v2d u = U2[(i * NB + r) >> 1];
+            a[i] = fma(u.x, c0v, a[i]);
+            a[i] = fma(u.y, c1v, a[i]);
+        }
+    }
+
+    constexpr int kSteps = RM - 1 < kProjMaxM - 1 ? RM - 1 : kProjMaxM - 1;   // most unknowns this tile can hold
+    ClassQrSteps<0, kSteps, RM>::run(a, j, cols);
+
+    double s[kSteps], q[kSteps];
+#pragma unroll
+    for (int i = 0; i < kSteps; ++i) {
+        s[i] = row_bcast<kClsLanes - 1>(a[i]);
+        q[i] = 0.0;
+    }
+    BackSubst<kSteps - 1, kSteps, RM>::run(a, s, q, cols);
+
+    // a_r = Q(x_r) = 1 + sum_t q[t] x^(t+1) (q[t] = 0 for t >= cols), rows j, j+16, .. of this lane
+    constexpr int PR = (NB + kClsLanes - 1) / kClsLanes;
+    double kv[PR];
+    int ki[PR];
+#pragma unroll
+    for (int p = 0; p < PR; ++p) {
+        const int r = j + p * kClsLanes;
+        const double x = xs[r < n ? r : 0];
+        double av = 0.0;
+#pragma unroll
+        for (int t = kSteps - 1; t >= 0; --t) av = fma(av, x, q[t]);
+        av = fma(av, x, 1.0);
+        kv[p] = (r < n && av == av) ? fabs(av) : __builtin_inf();
+        ki[p] = r;
+    }
+    // the A smallest |a_r| (equal magnitudes: smaller worker index, i.e. smaller row, first) vote
+    for (int pick = 0; pick < A; ++pick) {
+        double bv = kv[0];
+        int bi = ki[0];
+#pragma unroll
+        for (int p = 1; p < PR; ++p) {
+            const bool take = kv[p] < bv || (kv[p] == bv && ki[p] < bi);
+            bv = take ? kv[p] : bv;
+            bi = take ? ki[p] : bi;
+        }
+        row_min_step<kDppQuadXor1>(bv, bi);
+        row_min_step<kDppQuadXor2>(bv, bi);
+        row_min_step<kDppRowHalfMirror>(bv, bi);
+        row_min_step<kDppRowMirror>(bv, bi);
+        if (live && j == 0) atomicAdd(&votes[avail[bi]], 1);   // bi < n: at least A < n rows are real
+#pragma unroll
+        for (int p = 0; p < PR; ++p) {
+            if (ki[p] == bi) {
+                kv[p] = __builtin_inf();
+                ki[p] = 0x7fffffff;
+            }
+        }
+    }
+}
+
+// dynamic LDS (doubles): Ush[RM*NB] | Pw[NB*16] | xs[NB] | WdT[(n_cap-A)*KP] | alpha_s[K] | beta_s[N]
+//               then float Ysh[NB*CW], then ints: avail[N] | F[N] | Fpos[N] | votes[N] | sel[N] | n
+template <int NB, int RM>
+__global__ __launch_bounds__(256) void decode_byzantine_proj_kernel(
+    const float *__restrict__ preds, const uint8_t *__restrict__ mask, float *__restrict__ out,
+    int32_t *__restrict__ adv, int32_t *__restrict__ status, int K, int N, int S, int A, int64_t C, int64_t Cv,
+    int vec4, int sign_mode, int n_cap, int cw_log2, const Nodes nodes) {
+    extern __shared__ __align__(16) double lds_d[];
+    const int KP = round_up4(K);
+    const int M = K + A;
+    const int nw = blockDim.x / kWave;
+    const int CW = 1 << cw_log2;                          // classes per staged tile (16, 32 or 64)
+    double *Ush = lds_d;
+    double *Pw = Ush + RM * NB;
+    double *xs = Pw + NB * kPwStride;
+    double *WdT = xs + NB;
+    double *alpha_s = WdT + (n_cap - A) * KP;
+    double *beta_s = alpha_s + K;
+    float *Ysh = reinterpret_cast<float *>(beta_s + N);
+    int *avail = reinterpret_cast<int *>(Ysh + NB * CW);
+    int *F = avail + N;
+    int *Fpos = F + N;
+    int *votes = Fpos + N;
+    int *sel = votes + N;
+    int *n_sh = sel + N;
+
+    const int64_t g = blockIdx.x;
+    const int wv = wave_id();
+    const int tid = threadIdx.x;
+    const float *pg = preds + static_cast<size_t>(g) * N * C;
+
+    stage_nodes(nodes, K, N, alpha_s, beta_s);
+    for (int e = tid; e < (n_cap - A) * KP; e += blockDim.x) WdT[e] = 0.0;
+    for (int e = tid; e < RM * NB; e += blockDim.x) Ush[e] = 0.0;
+    for (int e = tid; e < N; e += blockDim.x) votes[e] = 0;
+    if (wv == 0) {
+        const int cnt = survivors_from_mask(mask + g * N, N, avail);
+        if (lane_id() == 0) *n_sh = cnt;
+    }
+    __syncthreads();
+    const int n = *n_sh;
+    const bool good = S < 0 ? (n >= 2 * M && n <= n_cap) : n == n_cap;
+    if (tid == 0 && status != nullptr) status[g] = good ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
+    if (!good) return;
+
+    // first class tile: the loads are issued now and land in LDS after the shared factorisation
+    constexpr int kPrefetch = 8;
+    const int slots = NB * CW;                            // slot = (row r, class c) = (slot >> cw_log2, slot & (CW-1))
+    float pf[kPrefetch];
+#pragma unroll
+    for (int u = 0; u < kPrefetch; ++u) {
+        const int slot = tid + u * blockDim.x;
+        const int r = slot >> cw_log2, c = slot & (CW - 1);
+        pf[u] = (slot < slots && r < n && c < C) ? pg[static_cast<size_t>(avail[r]) * C + c] : 0.0f;
+    }
+
+    // powers of the available workers' nodes, x^e by repeated multiplication; rows past n are zero
+    for (int r = tid; r < NB; r += blockDim.x) {
+        const double x = r < n ? beta_s[avail[r]] : 0.0;
+        if (r < n) xs[r] = x;
+        double p = r < n ? 1.0 : 0.0;
+        for (int e = 0; e < kPwStride; ++e) {
+            Pw[r * kPwStride + e] = p;
+            p *= x;
+        }
+    }
+    __syncthreads();
+    if (wv == 0) shared_complement_basis<NB, RM>(Pw, n, M, Ush);
+
+    for (int64_t cb = 0; cb < C; cb += CW) {              // class tiles
+        if (cb == 0) {
+#pragma unroll
+            for (int u = 0; u < kPrefetch; ++u) {
+                const int slot = tid + u * blockDim.x;
+                if (slot < slots) Ysh[slot] = pf[u];
+            }
+            for (int slot = tid + kPrefetch * blockDim.x; slot < slots; slot += blockDim.x) {
+                const int r = slot >> cw_log2, c = slot & (CW - 1);
+                Ysh[slot] = (r < n && c < C) ? pg[static_cast<size_t>(avail[r]) * C + c] : 0.0f;
+            }
+        } else {
+            __syncthreads();                              // every wave is done with the previous tile
+            for (int slot = tid; slot < slots; slot += blockDim.x) {
+                const int r = slot >> cw_log2, c = slot & (CW - 1);
+                Ysh[slot] = (r < n && cb + c < C) ? pg[static_cast<size_t>(avail[r]) * C + cb + c] : 0.0f;
+            }
+        }
+        __syncthreads();
+        const int tile_classes = (C - cb < CW) ? static_cast<int>(C - cb) : CW;
+        for (int c_rel = wv * kClsPerWave; c_rel < tile_classes; c_rel += nw * kClsPerWave)
+            locate_classes_proj<NB, RM>(Ysh, CW, c_rel, c_rel + lane_id() / kClsLanes < tile_classes, avail, xs, Pw, Ush,
+                                        n, M, A, votes);
+    }
+    __syncthreads();
+
+    float *og = out + static_cast<size_t>(g) * K * C;
+    const bool staged = C <= CW;                          // the one tile holds every prediction of the group
+    select_adversaries(adv + g * A, avail, n, N, A, votes, sel, F, Fpos);
+    const int nF = n - A;
+    decoder_weights(alpha_s, beta_s, F, nF, K, KP, sign_mode, WdT);
+    __syncthreads();
+    if (staged) {
+        // out[j][c] = sum_r WdT[r][j] * Y[F_r][c] straight from the staged tile
+        const int Ci = static_cast<int>(C);
+        for (int o = tid; o < K * Ci; o += blockDim.x) {
+            const int jq = o / Ci, c = o - jq * Ci;
+            double acc = 0.0;
+#pragma unroll 6
+            for (int r = 0; r < nF; ++r)
+                acc = fma(WdT[r * KP + jq], static_cast<double>(Ysh[(Fpos[r] << cw_log2) + c]), acc);
+            og[o] = static_cast<float>(acc);
+        }
+    } else if (vec4) {
+        contract_group<4>(pg, og, F, nF, K, KP, C, Cv, WdT);
+    } else {
+        contract_group<1>(pg, og, F, nF, K, KP, C, Cv, WdT);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// general kernel: the full system per class, in LDS
+// ------------------------------------------------------------------------------------------------
+// Algorithm 2, steps 1-5, for the classes c0 .. c0+cpw-1 of one group, by one wave.
+//   n        available workers (rows), M = K + A, W2 = 2M columns including the right-hand side
+//   xs[n]    worker nodes of the available workers (LDS, shared by the workgroup)
+//   scratch  this wave's LDS: per class  mat[n][W2] | coef[M] | key[n]
+// Lane (cl, j) = (lane / W2, lane % W2) works on class c0 + cl; lanes beyond cpw classes idle.
+__device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg, int64_t C, int64_t c0, int cpw,
+                                                    const int *avail, const double *xs, int n, int M, int A,
+                                                    double *scratch, int *votes) {
+    const int lane = lane_id();
+    const int W2 = 2 * M;
+    const int cols = W2 - 1;                 // unknowns P_0..P_{M-1}, Q_1..Q_{M-1}; column `cols` is the rhs
+    const int cl = lane / W2;
+    const int j = lane - cl * W2;
+    const int64_t c = c0 + cl;
+    const bool live = cl < cpw && c < C;     // this lane's class exists
+    const int per_class = n * W2 + M + n;
+    double *mat = scratch + (live ? cl : 0) * per_class;
+    double *coef = mat + n * W2;
+    double *key = coef + M;
+
+    // ---- steps 1-2: the system, one lane per row (rows j, j+W2, ..) -------------------
+    if (live) {
+        for (int r = j; r < n; r += W2) {
+            const double x = xs[r];
+            const double y = static_cast<double>(pg[static_cast<size_t>(avail[r]) * C + c]);
+            double *row = mat + r * W2;
+            double p = 1.0;
+            for (int k = 0; k < M; ++k) {
+                row[k] = p;                               // x^k
+                if (k >= 1) row[M - 1 + k] = -y * p;      // -y x^k
+                p *= x;
+            }
+            row[cols] = y;
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+
+    // ---- Householder QR in least-squares form, one lane per column ---------------------
+    // Step k reflects column k onto e_k over rows k..n-1 and applies the reflector to the
+    // columns right of it (and to the right-hand side).
+    for (int k = 0; k < cols; ++k) {
+        double sigma = 0.0, d = 0.0;
+#pragma unroll 4
+        for (int r = k; r < n; ++r) {
+            const double vr = mat[r * W2 + k];            // broadcast inside the class
+            const double arj = mat[r * W2 + j];
+            sigma = fma(vr, vr, sigma);
+            d = fma(vr, arj, d);
+        }
+        const double xkk = mat[k * W2 + k];
+        const double akj = mat[k * W2 + j];
+        const Reflector h = reflector(sigma, d, xkk, akj);
+        __builtin_amdgcn_wave_barrier();
+        if (live && !h.degenerate) {
+            if (j > k) {
+#pragma unroll 4
+                for (int r = k; r < n; ++r) {
+                    const double vr = (r == k) ? xkk - h.alpha : mat[r * W2 + k];
+                    mat[r * W2 + j] = fma(-h.f, vr, mat[r * W2 + j]);
+                }
+            } else if (j == k) {
+                mat[k * W2 + k] = h.alpha;                // R[k][k]
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // ---- back substitution for Q_{M-1} .. Q_1 (unknowns cols-1 .. M); P is not needed ----
+    // lane j holds the transformed right-hand side entry of row j.
+    double s = (live && j < cols) ? mat[j * W2 + cols] : 0.0;
+    const double diag = (live && j < cols) ? mat[j * W2 + j] : 1.0;
+    for (int t = cols - 1; t >= M; --t) {
+        if (live && j == t) coef[t - M] = s / diag;       // Q_{t-M+1}
+        __builtin_amdgcn_wave_barrier();
+        const double sol = coef[t - M];
+        if (live && j < t) s = fma(-mat[j * W2 + t], sol, s);
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // ---- step 3: a_r = Q(x_r), Horner, one lane per row; steps 4-5: the A smallest |a_r| ----
+    if (live) {
+        for (int r = j; r < n; r += W2) {
+            const double x = xs[r];
+            double a = 0.0;
+            for (int t = cols - 1; t >= M; --t) a = fma(a, x, coef[t - M]);
+            a = fma(a, x, 1.0);                           // Q_0 = 1
+            key[r] = (a != a) ? __builtin_inf() : fabs(a);
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    if (live) pick_and_vote(key, avail, n, A, j, W2, votes);
+    __builtin_amdgcn_wave_barrier();
+}
+
+// dynamic LDS: double scratch[nw][cpw * (n*2M + M + n)] | double WdT[(n-A) * KP] | double xs[n]
+//              | double alpha_s[K] | double beta_s[N]
+//              | int avail[N] | int F[N] | int Fpos[N] | int votes[N] | int sel[N] | int n
+__global__ void decode_byzantine_general_kernel(const float *__restrict__ preds, const uint8_t *__restrict__ mask,
+                                                float *__restrict__ out, int32_t *__restrict__ adv,
+                                                int32_t *__restrict__ status, int K, int N, int S, int A, int64_t C,
+                                                int64_t Cv, int vec4, int sign_mode, int cpw, int n_cap,
+                                                const Nodes nodes) {
+    extern __shared__ __align__(16) double lds_d[];
+    const int KP = round_up4(K);
+    const int M = K + A;
+    const int nF_cap = n_cap - A;
+    const int nw = blockDim.x / kWave;
+    const int wave_doubles = cpw * (n_cap * 2 * M + M + n_cap);
+
+    double *scratch = lds_d;
+    double *WdT = scratch + static_cast<size_t>(nw) * wave_doubles;
+    double *xs = WdT + nF_cap * KP;
+    double *alpha_s = xs + n_cap;
+    double *beta_s = alpha_s + K;
+    int *avail = reinterpret_cast<int *>(beta_s + N);
+    int *F = avail + N;
+    int *Fpos = F + N;
+    int *votes = Fpos + N;
+    int *sel = votes + N;
+    int *n_sh = sel + N;
+
+    const int64_t g = blockIdx.x;
+    const int wv = wave_id();
+    const float *pg = preds + static_cast<size_t>(g) * N * C;
+
+    stage_nodes(nodes, K, N, alpha_s, beta_s);
+    for (int e = threadIdx.x; e < nF_cap * KP; e += blockDim.x) WdT[e] = 0.0;
+    for (int e = threadIdx.x; e < N; e += blockDim.x) votes[e] = 0;
+    if (wv == 0) {
+        const int cnt = survivors_from_mask(mask + g * N, N, avail);
+        if (lane_id() == 0) *n_sh = cnt;
+    }
+    __syncthreads();
+    const int n = *n_sh;
+    const bool good = S < 0 ? (n >= 2 * M && n <= n_cap) : n == n_cap;
+    if (threadIdx.x == 0 && status != nullptr) status[g] = good ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
+    if (!good) return;
+
+    for (int r = threadIdx.x; r < n; r += blockDim.x) xs[r] = beta_s[avail[r]];
+    __syncthreads();
+    for (int64_t c0 = static_cast<int64_t>(wv) * cpw; c0 < C; c0 += static_cast<int64_t>(nw) * cpw)
+        locate_classes_wave(pg, C, c0, cpw, avail, xs, n, M, A, scratch + static_cast<size_t>(wv) * wave_doubles, votes);
+    __syncthreads();
+
+    finish_group(pg, out + static_cast<size_t>(g) * K * C, adv + g * A, avail, n, N, A, K, KP, C, Cv, vec4 != 0, sign_mode,
+                 alpha_s, beta_s, votes, sel, F, Fpos, WdT);
+}
+
+template <int NB, int RM>
+int run_proj(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv, int32_t *d_status, int64_t G,
+             int K, int N, int S, int A, int64_t C, int n_cap, bool vec4, const Nodes &nodes, int sign_mode,
+             hipStream_t stream) {
+    const int KP = (K + 3) & ~3;
+    const int64_t Cv = vec4 ? C / 4 : C;
+    const int cw_log2 = C <= 16 ? 4 : (C <= 32 ? 5 : 6);            // classes per staged tile: 16, 32 or 64
+    const int CW = 1 << cw_log2;
+    // waves per workgroup: one per four classes of a tile, at most four -- but no more than it takes to put
+    // about four waves on every SIMD of the chip (1024 SIMDs): beyond that, extra waves of a group only
+    // idle through the shared factorisation (measured at G = 2048, C = 10: 1 wave 44.7 us, 2 waves 42.7, 3 waves 53.0)
+    int nw = static_cast<int>(((C < CW ? C : CW) + kClsPerWave - 1) / kClsPerWave);
+    if (nw > 4) nw = 4;
+    const int64_t fill = (4096 + G - 1) / G;
+    if (nw > fill) nw = static_cast<int>(fill);
+    const size_t lds = sizeof(double) * (static_cast<size_t>(RM) * NB + NB * kPwStride + NB +
+                                         static_cast<size_t>(n_cap - A) * KP + K + N) +
+                       sizeof(float) * (static_cast<size_t>(NB) * CW) + sizeof(int) * (5 * static_cast<size_t>(N) + 2);
+    if (lds > 64 * 1024) return APPROXIFER_ERR_LIMIT;      // cannot happen inside the projected kernel's domain
+    const dim3 grid(static_cast<unsigned>(G)), block(nw * kWave);
+    hipLaunchKernelGGL((decode_byzantine_proj_kernel<NB, RM>), grid, block, lds, stream, d_preds, d_mask, d_out, d_adv,
+                       d_status, K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, n_cap, cw_log2, nodes);
+    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+}
+
+}  // namespace
+
+int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
+                            int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C, const Nodes &nodes,
+                            int sign_mode, hipStream_t stream) {
+    const int KP = (K + 3) & ~3;
+    // capacity: the most available workers a group can bring (S < 0: read off each mask)
+    const int n = S < 0 ? (N < APPROXIFER_MAX_AVAIL_BYZ ? N : APPROXIFER_MAX_AVAIL_BYZ) : N - S;
+    const int M = K + A;
+    const bool vec4 = (C % 4 == 0) && aligned16(d_preds) && aligned16(d_out);
+    const int64_t Cv = vec4 ? C / 4 : C;
+    if (G > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+
+    if (M <= kProjMaxM && n <= 48 && n - M <= 32) {
+        // register tiles <rows of [V | I], rows of the projected system>: the smallest that holds (n, n - M)
+#define APPROXIFER_PROJ(NB, RM)                                                                                        \
+    if (n <= NB && n - M <= RM)                                                                                        \
+        return run_proj<NB, RM>(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, S, A, C, n, vec4, nodes, sign_mode, stream);
+        APPROXIFER_PROJ(20, 12)
+        APPROXIFER_PROJ(24, 16)
+        APPROXIFER_PROJ(32, 16)
+        APPROXIFER_PROJ(32, 32)
+        APPROXIFER_PROJ(48, 16)
+        APPROXIFER_PROJ(48, 32)
+#undef APPROXIFER_PROJ
+    }
+
+    // classes per wave: a class takes 2M lanes; waves per workgroup: enough for all classes, at most 4
+    int cpw = kWave / (2 * M);
+    if (cpw < 1) cpw = 1;
+    if (cpw > C) cpw = static_cast<int>(C);
+    const size_t fixed = sizeof(double) * (static_cast<size_t>(n - A) * KP + n + K + N) + sizeof(int) * (5 * static_cast<size_t>(N) + 2);
+    const size_t per_class = sizeof(double) * (static_cast<size_t>(n) * 2 * M + M + n);
+    const size_t budget = 64 * 1024;
+    while (cpw > 1 && fixed + cpw * per_class > budget) --cpw;
+    const size_t per_wave = cpw * per_class;
+    if (fixed + per_wave > budget) return APPROXIFER_ERR_LIMIT;
+    int nw = static_cast<int>((C + cpw - 1) / cpw);
+    if (nw > 4) nw = 4;
+    if (nw > static_cast<int>((budget - fixed) / per_wave)) nw = static_cast<int>((budget - fixed) / per_wave);
+    if (nw < 1) nw = 1;
+    const size_t lds = fixed + nw * per_wave;
+    const dim3 grid(static_cast<unsigned>(G)), block(nw * kWave);
+    hipLaunchKernelGGL(decode_byzantine_general_kernel, grid, block, lds, stream, d_preds, d_mask, d_out, d_adv, d_status,
+                       K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, cpw, n, nodes);
+    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+}
+
+}  // namespace approxifer

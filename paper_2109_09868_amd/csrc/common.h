@@ -29,8 +29,10 @@ constexpr int kDppRowMirror = 0x140;     // lane i <-> 15-i inside each row
 
 template <int CTRL>
 __device__ __forceinline__ double dpp_exchange(double v) {
-    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, false);
+    // every pattern used here reads an existing lane of the same row, all rows and banks are enabled:
+    // the 'old' operand is dead, and bound_ctrl tells the compiler so (no extra move per exchange)
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, true);
     return __hiloint2double(hi, lo);
 }
 

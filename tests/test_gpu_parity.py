@@ -426,6 +426,11 @@ def test_byzantine_workload_full_size(gpu):
 @pytest.mark.parametrize("K,A,S,N,C,G", [
     (2, 1, 0, 6, 3, 16), (3, 2, 2, 12, 10, 16), (12, 1, 0, 26, 10, 8), (12, 2, 0, 28, 10, 8), (12, 3, 0, 30, 10, 8),
     (8, 2, 6, 26, 10, 8), (8, 2, 4, 24, 1000, 3), (8, 2, 0, 64, 6, 3), (16, 4, 0, 40, 4, 4), (4, 1, 3, 13, 17, 8),
+    # every register-tile size of the projected kernel, odd numbers of available workers, K + A = 16, one class
+    (2, 1, 0, 22, 5, 8), (8, 2, 0, 40, 7, 6), (13, 3, 1, 33, 3, 4), (3, 1, 0, 9, 6, 8), (5, 2, 2, 23, 4, 8),
+    (1, 1, 0, 48, 2, 4), (6, 1, 0, 14, 1, 16), (14, 2, 0, 48, 9, 3), (9, 1, 5, 54, 12, 3), (15, 2, 0, 36, 4, 3),
+    # class tiles of 32 and 64, several tiles with a ragged last one, many groups (one wave per group)
+    (8, 2, 4, 24, 20, 6), (8, 2, 4, 24, 40, 6), (5, 1, 0, 12, 150, 4), (3, 1, 1, 9, 6, 4200),
 ])
 def test_byzantine_exactly_rational_predictions(gpu, K, A, S, N, C, G):
     # a linear hosted model makes the coded predictions exactly rational in beta (Theorem 1): the
