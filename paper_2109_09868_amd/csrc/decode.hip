@@ -180,10 +180,155 @@ __global__ void decode_top1_kernel(const float *__restrict__ preds, const uint8_
     }
 }
 
+// ------------------------------------------------------------------------------------
+// packed kernel for the small shapes of the image-classification operating points
+// ------------------------------------------------------------------------------------
+// K <= 16 queries, at most 16 surviving workers, C <= 16 classes (e.g. K = 8..12, one to three stragglers,
+// ten classes).  A group is then a few hundred bytes, and a workgroup per group spends its time on launch
+// and barrier latency.  Here ONE WAVE decodes a group on its own -- four groups per workgroup, the only
+// workgroup barrier is the one after the nodes are staged -- with everything in 16 x 16 tiles in the wave's
+// own LDS: survivors from one ballot, predictions Y[r][c], weights W[j][r] (16 lanes per query node, four
+// nodes per pass), then one lane per output (j, c).  TOP1 adds the argmax over classes.
+constexpr int kPk = 16;                 // tile edge: K, |F| and C are all at most 16
+constexpr int kPkGroups = 4;            // groups (= waves) per workgroup
+
+template <bool TOP1>
+__global__ __launch_bounds__(kPkGroups *kWave) void decode_packed_kernel(
+    const float *__restrict__ preds, const uint8_t *__restrict__ mask, float *__restrict__ out,
+    int32_t *__restrict__ top1, float *__restrict__ score, int32_t *__restrict__ status, int64_t G, int K, int N,
+    int S, int C, int sign_mode, const Nodes nodes) {
+    __shared__ double alpha_s[kPk];
+    __shared__ double beta_s[kWave];
+    __shared__ double W_s[kPkGroups][kPk * kPk];       // W[j][r]
+    __shared__ double O_s[TOP1 ? kPkGroups : 1][kPk * kPk];
+    __shared__ float Y_s[kPkGroups][kPk * kPk];        // Y[r][c]
+    __shared__ int F_s[kPkGroups][kPk];
+
+    const int lane = lane_id();
+    const int wv = wave_id();
+    for (int t = threadIdx.x; t < K + N; t += blockDim.x) {
+        if (t < K) alpha_s[t] = nodes.alpha[t];
+        else beta_s[t - K] = nodes.beta[t - K];
+    }
+    __syncthreads();
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * kPkGroups + wv;
+    if (g >= G) return;
+
+    double *W = W_s[wv];
+    float *Y = Y_s[wv];
+    int *F = F_s[wv];
+
+    // survivors: N <= 64, one ballot
+    const bool mine = lane < N && mask[g * N + lane] != 0;
+    const unsigned long long m = __ballot(mine);
+    const int nF = __popcll(m);
+    const bool good = S < 0 ? (nF >= 1 && nF <= kPk) : nF == N - S;
+    if (lane == 0 && status != nullptr) status[g] = good ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
+    if (!good) return;
+    if (mine) F[__popcll(m & ((1ull << lane) - 1ull))] = lane;
+    __builtin_amdgcn_wave_barrier();
+
+    // predictions of the survivors: slot (r, c) = (slot / 16, slot % 16), four slots per lane
+    const float *pg = preds + static_cast<size_t>(g) * N * C;
+    float yv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int slot = lane + u * kWave;
+        const int r = slot / kPk, c = slot % kPk;
+        yv[u] = (r < nF && c < C) ? pg[static_cast<size_t>(F[r]) * C + c] : 0.0f;
+    }
+
+    // weights, Section 3 "ApproxIFER Decoding" step 2: lanes (jsub, r) = (lane / 16, lane % 16)
+    {
+        const int r = lane % kPk, jsub = lane / kPk;
+        const bool valid = r < nF;
+        const int i = valid ? F[r] : 0;
+        const double xb = beta_s[i];
+        const int parity = (sign_mode == APPROXIFER_SIGN_WORKER_INDEX) ? (i & 1) : (r & 1);
+        const double sign = parity ? -1.0 : 1.0;
+        const unsigned long long group_mask = 0xFFFFull << (jsub * kPk);
+#pragma unroll
+        for (int p = 0; p < kPk / 4; ++p) {
+            if (4 * p < K) {
+                const int j = 4 * p + jsub;
+                const bool row = j < K;
+                const BerrutTerm bt = berrut_term(alpha_s[row ? j : 0], xb, sign, valid && row);
+                const double rden = 1.0 / row16_sum(bt.t);
+                const bool any_hit = (__ballot(bt.hit) & group_mask) != 0ull;
+                W[j * kPk + r] = (valid && row) ? (any_hit ? (bt.hit ? 1.0 : 0.0) : bt.t * rden) : 0.0;
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) Y[lane + u * kWave] = yv[u];
+    __builtin_amdgcn_wave_barrier();
+
+    // one lane per output (j, c) = (slot / 16, slot % 16); float64 accumulation, one rounding
+    const int nF4 = (nF + 3) & ~3;                       // rows nF.. of W and Y are zero
+    float *og = out + static_cast<size_t>(g) * K * C;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        if (u * 4 < K) {
+            const int slot = lane + u * kWave;
+            const int j = slot / kPk, c = slot % kPk;
+            double acc = 0.0;
+#pragma unroll
+            for (int r0 = 0; r0 < kPk; r0 += 4) {
+                if (r0 < nF4) {
+#pragma unroll
+                    for (int r = r0; r < r0 + 4; ++r)
+                        acc = fma(W[j * kPk + r], static_cast<double>(Y[r * kPk + c]), acc);
+                }
+            }
+            if (TOP1) O_s[TOP1 ? wv : 0][slot] = acc;
+            else if (j < K && c < C) og[j * C + c] = static_cast<float>(acc);
+        }
+    }
+    if (TOP1) {
+        __builtin_amdgcn_wave_barrier();
+        if (lane < K) {                                   // largest value, smallest class on equal values
+            const double *o = O_s[TOP1 ? wv : 0] + lane * kPk;
+            double bv = o[0];
+            int bi = 0;
+            for (int c = 1; c < C; ++c) {
+                const double v = o[c];
+                if (v > bv) {
+                    bv = v;
+                    bi = c;
+                }
+            }
+            top1[g * K + lane] = bi;
+            if (score != nullptr) score[g * K + lane] = static_cast<float>(bv);
+        }
+    }
+}
+
+bool packed_shape(int K, int N, int S, int64_t C) {
+    const int most_survivors = S < 0 ? N : N - S;
+    return K <= kPk && most_survivors <= kPk && N <= kWave && C <= kPk;
+}
+
+int run_packed(bool top1_variant, const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_top1,
+               float *d_score, int32_t *d_status, int64_t G, int K, int N, int S, int64_t C, const Nodes &nodes,
+               int sign_mode, hipStream_t stream) {
+    const int64_t blocks = (G + kPkGroups - 1) / kPkGroups;
+    if (blocks > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    const dim3 grid(static_cast<unsigned>(blocks)), block(kPkGroups * kWave);
+    if (top1_variant)
+        hipLaunchKernelGGL(decode_packed_kernel<true>, grid, block, 0, stream, d_preds, d_mask, d_out, d_top1, d_score,
+                           d_status, G, K, N, S, static_cast<int>(C), sign_mode, nodes);
+    else
+        hipLaunchKernelGGL(decode_packed_kernel<false>, grid, block, 0, stream, d_preds, d_mask, d_out, d_top1, d_score,
+                           d_status, G, K, N, S, static_cast<int>(C), sign_mode, nodes);
+    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+}
+
 }  // namespace
 
 int launch_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_status, int64_t G, int K,
                   int N, int S, int64_t C, const Nodes &nodes, int sign_mode, hipStream_t stream) {
+    if (packed_shape(K, N, S, C))
+        return run_packed(false, d_preds, d_mask, d_out, nullptr, nullptr, d_status, G, K, N, S, C, nodes, sign_mode, stream);
     const int KP = (K + 3) & ~3;
     const bool vec4 = (C % 4 == 0) && aligned16(d_preds) && aligned16(d_out);
     const int64_t Cv = vec4 ? C / 4 : C;
@@ -212,6 +357,8 @@ int launch_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int
 int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_top1, float *d_score,
                        int32_t *d_status, int64_t G, int K, int N, int S, int64_t C, const Nodes &nodes,
                        int sign_mode, hipStream_t stream) {
+    if (packed_shape(K, N, S, C))
+        return run_packed(true, d_preds, d_mask, nullptr, d_top1, d_score, d_status, G, K, N, S, C, nodes, sign_mode, stream);
     const int KP = (K + 3) & ~3;
     const bool vec4 = (C % 4 == 0) && aligned16(d_preds);
     const int64_t Cv = vec4 ? C / 4 : C;

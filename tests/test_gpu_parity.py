@@ -181,6 +181,9 @@ def test_decode_tiny_workload(gpu, mode):
 @pytest.mark.parametrize("K,N,S,C,G", [
     (1, 2, 1, 1, 3), (2, 3, 1, 7, 4), (4, 9, 0, 260, 3), (5, 100, 10, 33, 2), (12, 20, 8, 1003, 2),
     (16, 24, 6, 2, 9), (32, 48, 12, 2, 5), (64, 128, 0, 12, 2), (64, 128, 60, 5, 2), (9, 70, 3, 516, 2),
+    # the packed small-shape kernel at and just past its limits (K, survivors, classes <= 16, N <= 64)
+    (16, 20, 4, 16, 9), (16, 64, 48, 16, 5), (16, 20, 3, 16, 5), (16, 20, 4, 17, 5), (13, 15, 2, 11, 131), (3, 64, 61, 1, 7),
+    (1, 5, 4, 16, 6), (12, 13, 1, 10, 4099),
 ])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_decode_shapes(gpu, K, N, S, C, G, mode):
@@ -348,6 +351,7 @@ def test_decode_top1_workloads(gpu, name, mode):
 
 
 @pytest.mark.parametrize("K,N,S,C,G", [(1, 2, 1, 1, 3), (2, 3, 1, 7, 4), (5, 100, 10, 33, 2), (12, 20, 8, 1003, 2),
+                                       (16, 20, 4, 16, 9), (16, 64, 48, 16, 5), (13, 15, 2, 11, 131), (8, 9, 1, 10, 1030),
                                        (32, 48, 12, 2, 5), (64, 128, 0, 12, 2), (9, 70, 3, 516, 2), (8, 9, 1, 10, 300)])
 def test_decode_top1_shapes_and_bad_masks(gpu, K, N, S, C, G):
     torch, binding, dev = gpu
