@@ -3,7 +3,8 @@
 //   coded[g][i][d] = sum_j l_j(beta_i) * queries[g][j][d]
 //
 // One workgroup per (group, tile of vector columns): a single wave (64 columns) for K <= 16,
-// four waves (256 columns) above.  Each lane first issues the loads of its vector column of
+// four waves (256 columns) above; short ragged rows are tiled over the flattened (group, column)
+// index instead, so that no lane idles at a row end.  Each lane first issues the loads of its vector column of
 // all K queries (they stay in registers), and while those are in flight the workgroup
 // evaluates the N x K matrix l_j(beta_i) -- it depends on the nodes only -- in float64 (one
 // 16/32/64-lane group per worker row, the row's denominator by a DPP reduction) and keeps it
@@ -60,7 +61,12 @@ __device__ __forceinline__ void store_stream(float *p, typename VecOf<VEC>::type
 
 // K: queries per group (compile time so that the K input columns stay in registers).
 // VEC: floats per lane per access.  THREADS: workgroup size.
-template <int K, int VEC, int THREADS>
+// FLAT: false -- a workgroup covers THREADS consecutive vector columns of ONE group (`chunks` workgroups per
+//       group; the last one of a group may be partly idle);  true -- the (group, vector column) pairs of the
+//       whole batch are numbered consecutively and a workgroup takes THREADS of them, so lanes never idle at a
+//       row end.  Used when rows are short and ragged (28 x 28 queries: 196 vector columns, 23 % idle lanes
+//       otherwise); `chunks` then carries the total number of pairs.
+template <int K, int VEC, int THREADS, bool FLAT>
 __global__ __launch_bounds__(THREADS) void encode_kernel(
     const float *__restrict__ queries, float *__restrict__ coded, int N, int64_t D, int64_t Dv,
     int64_t chunks, const Nodes nodes) {
@@ -71,12 +77,27 @@ __global__ __launch_bounds__(THREADS) void encode_kernel(
     extern __shared__ float wl[];          // [N][KP]
 
     const int tid = threadIdx.x;
-    const int64_t g = blockIdx.x / chunks;
-    const int64_t ch = blockIdx.x - g * chunks;
-    const int64_t col = ch * THREADS + tid;
-    const bool ok = col < Dv;
-    // lanes past the ragged end read column 0 of the group (always in bounds) and store nothing
-    const float *xg = queries + static_cast<size_t>(g) * K * D + (ok ? col : 0) * VEC;
+    int64_t g, col;
+    bool ok;
+    if (FLAT) {
+        const int64_t q = static_cast<int64_t>(blockIdx.x) * THREADS + tid;
+        ok = q < chunks;
+        const int64_t qq = ok ? q : 0;
+        if (chunks <= 0xffffffffLL) {      // the usual case: one 32-bit division per lane
+            const uint32_t g32 = static_cast<uint32_t>(qq) / static_cast<uint32_t>(Dv);
+            g = g32;
+            col = static_cast<uint32_t>(qq) - g32 * static_cast<uint32_t>(Dv);
+        } else {
+            g = qq / Dv;
+            col = qq - g * Dv;
+        }
+    } else {
+        g = blockIdx.x / chunks;
+        col = (blockIdx.x - g * chunks) * THREADS + tid;
+        ok = col < Dv;
+        if (!ok) col = 0;                  // lanes past the ragged end read column 0 of the group and store nothing
+    }
+    const float *xg = queries + static_cast<size_t>(g) * K * D + col * VEC;
     float *og = coded + static_cast<size_t>(g) * N * D + col * VEC;
 
     // ---- this lane's column of the K queries: issue every load before anything else ----
@@ -258,27 +279,41 @@ int run_encode_mfma(const float *d_queries, float *d_coded, int64_t G, int K, in
     return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
 }
 
-template <int K, int VEC>
-int run_encode(const float *d_queries, float *d_coded, int64_t G, int N, int64_t D, const Nodes &nodes,
-               hipStream_t stream) {
+template <int K, int VEC, bool FLAT>
+int run_encode_shape(const float *d_queries, float *d_coded, int64_t tiles, int64_t chunks, int N, int64_t D,
+                     int64_t Dv, const Nodes &nodes, hipStream_t stream) {
     constexpr int KP = (K + 3) & ~3;
     constexpr int THREADS = K <= 16 ? 64 : 256;
     constexpr int PER_CU = K <= 16 ? APPROXIFER_ENCODE_WAVES_PER_CU_SMALL_K : APPROXIFER_ENCODE_BLOCKS_PER_CU_LARGE_K;
-    const int64_t Dv = D / VEC;
-    const int64_t chunks = (Dv + THREADS - 1) / THREADS;
-    const int64_t tiles = G * chunks;
     if (tiles > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
     const size_t lds_used = static_cast<size_t>(N) * KP * sizeof(float);
     // reserve 1/PER_CU of the CU's LDS so that at most PER_CU workgroups are resident
     size_t lds = (static_cast<size_t>(kLdsPerCu / PER_CU) / 512) * 512;
     if (lds < lds_used) lds = lds_used;
     if (lds > 64 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_kernel<K, VEC, THREADS>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_kernel<K, VEC, THREADS, FLAT>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
         return APPROXIFER_ERR_LAUNCH;
-    hipLaunchKernelGGL((encode_kernel<K, VEC, THREADS>), dim3(static_cast<unsigned>(tiles)), dim3(THREADS), lds,
+    hipLaunchKernelGGL((encode_kernel<K, VEC, THREADS, FLAT>), dim3(static_cast<unsigned>(tiles)), dim3(THREADS), lds,
                        stream, d_queries, d_coded, N, D, Dv, chunks, nodes);
     return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+}
+
+template <int K, int VEC>
+int run_encode(const float *d_queries, float *d_coded, int64_t G, int N, int64_t D, const Nodes &nodes,
+               hipStream_t stream) {
+    constexpr int THREADS = K <= 16 ? 64 : 256;
+    const int64_t Dv = D / VEC;
+    const int64_t chunks = (Dv + THREADS - 1) / THREADS;
+    // lanes left idle at the row ends by the per-group tiling; above 3 % the flattened numbering pays for its
+    // per-lane division and addresses
+    const int64_t idle = chunks * THREADS - Dv;
+    if (idle * 100 > 3 * chunks * THREADS) {
+        const int64_t pairs = G * Dv;
+        return run_encode_shape<K, VEC, true>(d_queries, d_coded, (pairs + THREADS - 1) / THREADS, pairs, N, D, Dv, nodes,
+                                              stream);
+    }
+    return run_encode_shape<K, VEC, false>(d_queries, d_coded, G * chunks, chunks, N, D, Dv, nodes, stream);
 }
 
 template <int K>
