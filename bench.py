@@ -221,6 +221,32 @@ def other_workloads(torch, binding, syn, orc_nodes, dev, sign_mode):
                                    planted_adversaries_located=located, note=COLD)
     del q, coded
 
+    # -- the paper's Byzantine operating point: K = 12, S = 0, E = 2, 28 workers, MNIST-sized queries ---
+    w = syn.WORKLOADS["mnist_byz_k12"]
+    alpha, beta = orc_nodes(w.K, w.W)
+    q = torch.from_numpy(syn.queries(w, threads=16)).to(dev)
+    coded = torch.empty((w.G, w.W, w.D), dtype=torch.float32, device=dev)
+    t = time_launches(torch, lambda: binding.approxifer_encode(q, alpha, beta, coded=coded), 20, flush=flush)
+    res["mnist_byz_k12_encode"] = dict(t, coded_queries_per_s=w.G * w.W / (t["avg_ms"] * 1e-3),
+                                       hbm_gbs=encode_bytes(w) / (t["avg_ms"] * 1e6), note=COLD)
+    M = torch.from_numpy(syn.model_params(w)["M"]).to(dev)
+    clean = (coded.double().reshape(-1, w.D) @ M).float().reshape(w.G, w.W, w.C).cpu().numpy()
+    mask_h = syn.masks(w)
+    adv_true = syn.adversaries(w, mask_h)
+    preds = torch.from_numpy(syn.corrupt(w, clean, adv_true)).to(dev)
+    mask = torch.from_numpy(mask_h).to(dev)
+    out = torch.empty((w.G, w.K, w.C), dtype=torch.float32, device=dev)
+    adv = torch.empty((w.G, w.A), dtype=torch.int32, device=dev)
+    st = torch.empty((w.G,), dtype=torch.int32, device=dev)
+    t = time_launches(torch, lambda: binding.approxifer_decode_byzantine(preds, mask, alpha, beta, w.S, w.A, sign_mode,
+                                                                         out=out, adv=adv, status=st), 20, flush=flush)
+    located = float(np.mean(np.all(adv.cpu().numpy() == adv_true, axis=1)))
+    res["mnist_byz_k12_decode"] = dict(t, predictions_per_s=w.G * w.K / (t["avg_ms"] * 1e-3),
+                                       locator_solves_per_s=w.G * w.C / (t["avg_ms"] * 1e-3),
+                                       hbm_gbs=decode_bytes(w, True) / (t["avg_ms"] * 1e6),
+                                       groups_with_planted_adversaries_located=located, note=COLD)
+    del q, coded
+
     # -- text shapes: encode only (decode there moves < 1 MB) -----------------------------------
     for name in ("text", "text_k32"):
         w = syn.WORKLOADS[name]

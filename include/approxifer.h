@@ -159,6 +159,24 @@ int approxifer_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t 
                            int32_t *d_status, int64_t G, int K, int N, int S, int64_t C,
                            const double *h_alpha, const double *h_beta, int sign_mode, void *stream);
 
+/*
+ * Wait rule (Section 3, "ApproxIFER Decoding", step 1: the decoder waits for the results of the
+ * fastest workers -- K of them without adversaries, 2 (K + E) with E of them).  Turns arrival times
+ * into the survivor mask the decoders take: for every group g the `wait_for` workers with the
+ * smallest arrival time get mask 1, all others 0.  Equal times: the smaller worker index first.
+ * A time that is not finite (NaN, +-inf) means the worker never answers; a group in which fewer
+ * than `wait_for` workers answer has all of those marked, and its count says so.
+ *
+ *   d_arrival  [G][N] float32, device, read only: arrival time of every worker's result, any unit
+ *   d_mask     [G][N] uint8, device, written (0 or 1)
+ *   d_count    [G] int32, device, written, or NULL: number of ones in the group's mask
+ *   wait_for   1 <= wait_for <= N
+ * Returns OK, ERR_NULL_POINTER, ERR_BAD_SHAPE (G < 0, N < 1, wait_for out of range) or ERR_LIMIT
+ * (N > APPROXIFER_MAX_N).
+ */
+int approxifer_wait_mask(const float *d_arrival, uint8_t *d_mask, int32_t *d_count,
+                         int64_t G, int N, int wait_for, void *stream);
+
 /* Text for a return code; never NULL.  The string is static. */
 const char *approxifer_strerror(int code);
 

@@ -171,6 +171,28 @@ def decode_top1(Y, mask, alpha, beta, S, sign_mode=SIGN_WORKER_INDEX):
 
 
 # --------------------------------------------------------------------------
+# wait rule
+# --------------------------------------------------------------------------
+def wait_mask(arrival, wait_for):
+    """Survivor mask from arrival times: per group the wait_for workers that answer first get 1.
+    Section 3, "ApproxIFER Decoding", step 1 (the decoder waits for the fastest K workers, or
+    2(K+E) of them when E may be adversarial).  A non-finite time means the worker never answers.
+    Equal times: smaller worker index first (this build's reading; the paper is silent).
+    Returns (mask [G, W] uint8, count [G] int32)."""
+    arrival = np.asarray(arrival, dtype=np.float64)
+    G, W = arrival.shape
+    mask = np.zeros((G, W), dtype=np.uint8)
+    count = np.zeros(G, dtype=np.int32)
+    for g in range(G):
+        answered = [i for i in range(W) if np.isfinite(arrival[g, i])]
+        answered.sort(key=lambda i: (arrival[g, i], i))
+        first = answered[:wait_for]
+        mask[g, first] = 1
+        count[g] = len(first)
+    return mask, count
+
+
+# --------------------------------------------------------------------------
 # adversary location (Algorithm 2)
 # --------------------------------------------------------------------------
 def locator_system(x, y, K, A):

@@ -23,6 +23,7 @@ S_FROM_MASK = -1
 
 EXPORTS = (
     "approxifer_version",
+    "approxifer_wait_mask",
     "approxifer_strerror",
     "approxifer_chebyshev_nodes",
     "approxifer_encode",
@@ -70,6 +71,8 @@ def load() -> ctypes.CDLL:
     lib.approxifer_decode_byzantine.restype = ctypes.c_int
     lib.approxifer_decode_byzantine.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                                 ctypes.c_int, ctypes.c_int, ctypes.c_int64, c_dp, c_dp, ctypes.c_int, vp]
+    lib.approxifer_wait_mask.restype = ctypes.c_int
+    lib.approxifer_wait_mask.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, vp]
     _lib = lib
     return lib
 
@@ -198,3 +201,17 @@ def approxifer_decode_byzantine(preds, mask, alpha, beta, S, A, sign_mode=SIGN_W
                                               _dev(status, torch.int32, (G,)), G, K, N, int(S), int(A), C, ap, bp,
                                               int(sign_mode), ctypes.c_void_p(_stream_handle(stream))))
     return out, adv, status
+
+
+def approxifer_wait_mask(arrival, wait_for, mask=None, count=None, stream=None):
+    """arrival [G, N] float32 device tensor -> (mask [G, N] uint8, count [G] int32): the wait_for fastest workers."""
+    import torch
+    G, N = arrival.shape
+    if mask is None:
+        mask = torch.zeros((G, N), dtype=torch.uint8, device=arrival.device)
+    if count is None:
+        count = torch.full((G,), -1, dtype=torch.int32, device=arrival.device)
+    _check(load().approxifer_wait_mask(_dev(arrival, torch.float32), _dev(mask, torch.uint8, (G, N)),
+                                       _dev(count, torch.int32, (G,)), G, N, int(wait_for),
+                                       ctypes.c_void_p(_stream_handle(stream))))
+    return mask, count

@@ -124,4 +124,13 @@ int approxifer_decode_byzantine(const float *d_preds, const uint8_t *d_mask, flo
                                                sign_mode, static_cast<hipStream_t>(stream));
 }
 
+int approxifer_wait_mask(const float *d_arrival, uint8_t *d_mask, int32_t *d_count, int64_t G, int N, int wait_for,
+                         void *stream) {
+    if (G < 0 || N < 1 || wait_for < 1 || wait_for > N) return APPROXIFER_ERR_BAD_SHAPE;
+    if (N > APPROXIFER_MAX_N) return APPROXIFER_ERR_LIMIT;
+    if (G == 0) return APPROXIFER_OK;
+    if (d_arrival == nullptr || d_mask == nullptr) return APPROXIFER_ERR_NULL_POINTER;
+    return approxifer::launch_wait_mask(d_arrival, d_mask, d_count, G, N, wait_for, static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

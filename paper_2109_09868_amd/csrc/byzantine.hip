@@ -279,17 +279,22 @@ __device__ __forceinline__ void locate_classes_proj(const float *Ysh, int CW, in
 #pragma unroll
     for (int i = 0; i < RM; ++i) a[i] = 0.0;
     const v2d *U2 = reinterpret_cast<const v2d *>(Ush);   // NB is even: row stride NB/2 pairs
-    // rows past n contribute exact zeros (Ysh, Pw and the columns of Ush are zero there): no bound on r,
-    // so every load of this block is independent of every other and can be issued ahead of the arithmetic
+    // rows past n contribute exact zeros (Ysh, Pw and the columns of Ush are zero there): no bound on r, so
+    // inside a block of rows every load is independent of every other and is issued ahead of the arithmetic.
+    // Small tiles are one block; larger ones run in blocks of eight rows to bound the registers in flight.
+    constexpr int kRowBlock = NB <= 24 ? NB : 8;
+#pragma unroll 1
+    for (int rb = 0; rb < NB; rb += kRowBlock) {
 #pragma unroll
-    for (int r = 0; r < NB; r += 2) {
-        const double c0v = sgn * static_cast<double>(ysc[r * CW]) * Pw[r * kPwStride + e];
-        const double c1v = sgn * static_cast<double>(ysc[(r + 1) * CW]) * Pw[(r + 1) * kPwStride + e];
+        for (int r = rb; r < rb + kRowBlock; r += 2) {
+            const double c0v = sgn * static_cast<double>(ysc[r * CW]) * Pw[r * kPwStride + e];
+            const double c1v = sgn * static_cast<double>(ysc[(r + 1) * CW]) * Pw[(r + 1) * kPwStride + e];
 #pragma unroll
-        for (int i = 0; i < RM; ++i) {
-            const v2d u = U2[(i * NB + r) >> 1];
-            a[i] = fma(u.x, c0v, a[i]);
-            a[i] = fma(u.y, c1v, a[i]);
+            for (int i = 0; i < RM; ++i) {
+                const v2d u = U2[(i * NB + r) >> 1];
+                a[i] = fma(u.x, c0v, a[i]);
+                a[i] = fma(u.y, c1v, a[i]);
+            }
         }
     }
 

@@ -303,6 +303,55 @@ __global__ __launch_bounds__(kPkGroups *kWave) void decode_packed_kernel(
     }
 }
 
+// ------------------------------------------------------------------------------------
+// wait rule: arrival times -> survivor mask
+// ------------------------------------------------------------------------------------
+// One wave per group, four groups per workgroup; a lane owns workers lane and lane + 64.  The rank of a
+// worker is the number of workers that answer before it (equal times: smaller index first), counted
+// against the group's times broadcast from the wave's LDS; the wait_for lowest ranks are the survivors.
+constexpr int kWaitGroups = 4;
+
+__global__ __launch_bounds__(kWaitGroups *kWave) void wait_mask_kernel(const float *__restrict__ arrival,
+                                                                         uint8_t *__restrict__ mask,
+                                                                         int32_t *__restrict__ count, int64_t G, int N,
+                                                                         int wait_for) {
+    __shared__ float t_s[kWaitGroups][APPROXIFER_MAX_N];
+    const int lane = lane_id();
+    const int wv = wave_id();
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * kWaitGroups + wv;
+    if (g >= G) return;
+    float *t = t_s[wv];
+    const float never = __builtin_inff();
+    float mine[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int i = lane + p * kWave;
+        float v = never;
+        if (i < N) {
+            v = arrival[g * N + i];
+            if (!(fabsf(v) < never)) v = never;           // NaN and both infinities: never answers
+            t[i] = v;
+        }
+        mine[p] = v;
+    }
+    __builtin_amdgcn_wave_barrier();
+    int total = 0;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int i = lane + p * kWave;
+        int rank = 0;
+#pragma unroll 8
+        for (int o = 0; o < N; ++o) {
+            const float other = t[o];
+            rank += (other < mine[p] || (other == mine[p] && o < i)) ? 1 : 0;
+        }
+        const bool in = i < N && mine[p] < never && rank < wait_for;
+        if (i < N) mask[g * N + i] = in ? 1 : 0;
+        total += __popcll(__ballot(in));
+    }
+    if (lane == 0 && count != nullptr) count[g] = total;
+}
+
 bool packed_shape(int K, int N, int S, int64_t C) {
     const int most_survivors = S < 0 ? N : N - S;
     return K <= kPk && most_survivors <= kPk && N <= kWave && C <= kPk;
@@ -385,6 +434,15 @@ int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_t
     else
         hipLaunchKernelGGL(decode_top1_kernel<1>, grid, block, lds, stream, d_preds, d_mask, d_top1, d_score, d_status,
                            K, N, S, C, Cv, sign_mode, nodes);
+    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+}
+
+int launch_wait_mask(const float *d_arrival, uint8_t *d_mask, int32_t *d_count, int64_t G, int N, int wait_for,
+                     hipStream_t stream) {
+    const int64_t blocks = (G + kWaitGroups - 1) / kWaitGroups;
+    if (blocks > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    hipLaunchKernelGGL(wait_mask_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kWaitGroups * kWave), 0, stream,
+                       d_arrival, d_mask, d_count, G, N, wait_for);
     return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
 }
 

@@ -54,6 +54,9 @@ WORKLOADS = {
     # the paper's own operating point (Section 4.2): MNIST-sized queries, K = 8, one straggler, 10 classes
     "mnist_k8": Workload("mnist_k8", 6, 16384, 8, 9, 1, 0, (1, 28, 28), 10, "uniform01", "linear_softmax"),
     "text_k32": Workload("text_k32", 5, 1024, 32, 48, 12, 0, (128, 768), 2, "normal", "meanpool_linear"),
+    # the paper's Byzantine operating point (Section 4.2, "Byzantine-Robustness"): K = 12, no stragglers,
+    # E = 2 adversaries, N = 2 (K + E) = 28 workers, MNIST-sized queries, 10 classes
+    "mnist_byz_k12": Workload("mnist_byz_k12", 7, 8192, 12, 28, 0, 2, (1, 28, 28), 10, "uniform01", "linear"),
 }
 
 

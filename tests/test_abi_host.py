@@ -121,3 +121,17 @@ def test_binding_raises_typed_error(lib):
     with pytest.raises(binding.ApproxiferError) as e:
         binding.approxifer_chebyshev_nodes(0, 5)
     assert e.value.code == -2
+
+
+def test_wait_mask_validation_codes(lib):
+    fake = ctypes.c_void_p(16)
+    wm = lib.approxifer_wait_mask
+    assert wm(fake, fake, None, -1, 4, 2, None) == -2
+    assert wm(fake, fake, None, 1, 0, 1, None) == -2
+    assert wm(fake, fake, None, 1, 4, 0, None) == -2
+    assert wm(fake, fake, None, 1, 4, 5, None) == -2
+    assert wm(fake, fake, None, 1, 129, 5, None) == -3
+    assert wm(None, fake, None, 1, 4, 2, None) == -1
+    assert wm(fake, None, None, 1, 4, 2, None) == -1
+    assert wm(None, None, None, 0, 4, 2, None) == 0
+

@@ -512,6 +512,47 @@ def test_byzantine_nonlinear_model_votes(gpu):
     assert group_err(out[same], ref[same]).max() <= TOL
 
 
+@pytest.mark.parametrize("real", [0, 1])
+def test_byzantine_fewer_real_adversaries_than_A(gpu, real):
+    # the decoder is configured for A = 2 adversaries but fewer workers actually lie ("at most E", Section 2).
+    # Every fitted Q still vanishes at the real ones, so they must be among the located; the remaining picks
+    # are innocent workers, whose removal costs nothing.  The sets must equal the oracle's wherever its own vote
+    # is decisive, and the decoded values must equal the oracle's decode over the same survivors.
+    torch, binding, dev = gpu
+    K, A, S, N, C, G = 8, 2, 4, 24, 10, 96
+    rng = np.random.default_rng(50 + real)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    X = rng.uniform(0, 1, (G, K, 96))
+    Mf = rng.standard_normal((96, C)) / 10
+    clean = (orc.encode(X, alpha, beta) @ Mf).astype(np.float32)
+    mask = np.zeros((G, N), np.uint8)
+    Y = clean.copy()
+    truth = []
+    for g in range(G):
+        avail = np.sort(rng.permutation(N)[: N - S])
+        mask[g, avail] = 1
+        bad = np.sort(rng.permutation(avail)[:real])
+        truth.append(set(int(b) for b in bad))
+        Y[g, bad] += (10 * clean.std() * rng.standard_normal((real, C))).astype(np.float32)
+    out, adv, st, ref, adv_ref, st_ref = _byz_both(gpu, Y, mask, alpha, beta, S, A, 1)
+    assert np.all(st == 0) and np.array_equal(st, st_ref)
+    decisive = np.zeros(G, bool)
+    for g in range(G):
+        assert truth[g] <= set(adv[g].tolist()) and truth[g] <= set(adv_ref[g].tolist())
+        assert len(set(adv[g].tolist())) == A and np.all(mask[g, adv[g]] == 1) and np.all(np.diff(adv[g]) > 0)
+        _, _, counts = orc.locate(Y[g], np.nonzero(mask[g])[0], beta, K, A)
+        top = np.sort(counts)[::-1]
+        decisive[g] = top[A - 1] - top[A] >= 2
+    same = np.all(adv == adv_ref, axis=1)
+    assert np.all(same[decisive]) and same.mean() >= 0.9
+    assert group_err(out[same], ref[same]).max() <= TOL
+    for g in np.nonzero(~same)[0]:                          # decode parity given the kernel's own survivor set
+        m2 = mask[g:g + 1].copy()
+        m2[0, adv[g]] = 0
+        ref_g, _ = orc.decode(Y[g:g + 1], m2, alpha, beta, S + A, 1)
+        assert group_err(out[g:g + 1], ref_g).max() <= TOL
+
+
 # --------------------------------------------------------------------------------------
 # the paper's own operating points (Section 4.2; Appendix B), on synthetic stand-in data
 # --------------------------------------------------------------------------------------
@@ -637,6 +678,46 @@ def test_byzantine_ragged_masks(gpu):
     good = st == 0
     assert np.array_equal(adv[good], adv_ref[good]) and np.array_equal(adv[good], adv_true[good])
     assert group_err(out[good], ref[good]).max() <= TOL
+
+
+# --------------------------------------------------------------------------------------
+# wait rule: arrival times -> survivor mask
+# --------------------------------------------------------------------------------------
+@pytest.mark.parametrize("N,wait_for,G", [(1, 1, 3), (6, 4, 64), (12, 8, 1000), (24, 20, 257), (64, 1, 9), (65, 33, 9),
+                                          (128, 128, 5), (128, 77, 130), (20, 12, 5000)])
+def test_wait_mask(gpu, N, wait_for, G):
+    torch, binding, dev = gpu
+    rng = np.random.default_rng(N * 1000 + wait_for)
+    arrival = rng.exponential(1.0, (G, N)).astype(np.float32)
+    arrival[rng.random((G, N)) < 0.15] = np.float32(0.5)              # plenty of exact ties
+    arrival[rng.random((G, N)) < 0.10] = np.inf                       # workers that never answer
+    arrival[rng.random((G, N)) < 0.02] = np.nan
+    arrival[rng.random((G, N)) < 0.02] = -np.inf
+    arrival[0] = np.inf                                                # nobody answers
+    if G > 1:
+        arrival[1] = 1.0                                               # everybody at once
+    mask = torch.full((G, N), 77, dtype=torch.uint8, device=dev)
+    mask, count = binding.approxifer_wait_mask(torch.from_numpy(arrival).to(dev), wait_for, mask=mask)
+    ref_mask, ref_count = orc.wait_mask(arrival, wait_for)
+    assert np.array_equal(mask.cpu().numpy(), ref_mask)                # bit-exact
+    assert np.array_equal(count.cpu().numpy(), ref_count)
+    assert ref_count[0] == 0 and (G == 1 or ref_mask[1, :wait_for].all())
+
+
+def test_wait_mask_feeds_the_decoder(gpu):
+    # arrival times -> mask -> decode, all on the device, against the oracle's chain
+    torch, binding, dev = gpu
+    K, N, C, G = 8, 12, 10, 300
+    rng = np.random.default_rng(99)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    arrival = rng.exponential(1.0, (G, N)).astype(np.float32)
+    Y = rng.standard_normal((G, N, C)).astype(np.float32)
+    mask, count = binding.approxifer_wait_mask(torch.from_numpy(arrival).to(dev), K)
+    out, st = binding.approxifer_decode(torch.from_numpy(Y).to(dev), mask, alpha, beta, N - K, 1)
+    ref_mask, _ = orc.wait_mask(arrival, K)
+    ref, st_ref = orc.decode(Y, ref_mask, alpha, beta, N - K, 1)
+    assert np.all(st.cpu().numpy() == 0) and np.all(st_ref == 0)
+    assert group_err(out.cpu().numpy(), ref).max() <= TOL
 
 
 # --------------------------------------------------------------------------------------

@@ -302,3 +302,38 @@ def test_decode_with_per_group_straggler_counts():
     out_neg, st_neg = orc.decode(Y, mask, alpha, beta, -1, 0)
     ref, _ = orc.decode(Y, mask, alpha, beta, None, 0)
     assert np.array_equal(out_neg, ref)
+
+
+def test_wait_mask_hand_built_cases():
+    # Section 3, "ApproxIFER Decoding", step 1: the fastest wait_for workers are the survivors
+    inf, nan = np.inf, np.nan
+    arrival = np.array([
+        [5.0, 1.0, 3.0, 2.0, 4.0],        # plain: the three fastest are workers 1, 3, 2
+        [2.0, 2.0, 1.0, 2.0, 2.0],        # ties at the cut: smaller worker index first (our convention)
+        [inf, 1.0, nan, -inf, 7.0],       # only two workers ever answer
+        [0.0, -1.0, -2.0, 9.0, 8.0],      # negative times are ordinary times
+    ])
+    mask, count = orc.wait_mask(arrival, 3)
+    assert mask.tolist() == [[0, 1, 1, 1, 0], [1, 1, 1, 0, 0], [0, 1, 0, 0, 1], [1, 1, 1, 0, 0]]
+    assert count.tolist() == [3, 3, 2, 3]
+    everyone, c5 = orc.wait_mask(arrival, 5)
+    assert everyone[0].tolist() == [1] * 5 and c5.tolist() == [5, 5, 2, 5]
+
+
+def test_wait_mask_then_decode_uses_the_fastest_workers():
+    # the mask of the wait rule feeds the decoder: decoding with it equals decoding with the set of the
+    # K fastest workers written down by hand, and slower workers' rows are never looked at
+    K, W = 3, 7
+    alpha, beta = orc.chebyshev_nodes(K, W)
+    rng = np.random.default_rng(17)
+    arrival = rng.permutation(W).astype(np.float64)[None, :]
+    Y = rng.standard_normal((1, W, 4))
+    mask, count = orc.wait_mask(arrival, K)
+    fastest = np.sort(np.argsort(arrival[0])[:K])
+    assert count[0] == K and np.array_equal(np.nonzero(mask[0])[0], fastest)
+    Y_dirty = Y.copy()
+    Y_dirty[0, mask[0] == 0] = np.nan
+    out, st = orc.decode(Y_dirty, mask, alpha, beta, W - K, 1)
+    ref = orc.decode_weights(alpha, beta, fastest, 1) @ Y[0, fastest]
+    assert st[0] == 0 and np.allclose(out[0], ref, rtol=1e-14, atol=0)
+

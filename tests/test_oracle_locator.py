@@ -222,3 +222,24 @@ def test_decode_byzantine_with_per_group_straggler_counts():
         assert adv[g, 0] == planted[g]
         one, adv1, st1 = orc.decode_byzantine(Y[g:g + 1], mask[g:g + 1], alpha, beta, W - counts[g], A)
         assert st1[0] == 0 and np.array_equal(out[g], one[0]) and np.array_equal(adv[g], adv1[0])
+
+
+@pytest.mark.parametrize("real", [0, 1])
+def test_fewer_real_adversaries_are_still_located(real):
+    # Appendix A: Q = q * Lambda with Lambda vanishing at the corrupted nodes.  With fewer than A corrupted
+    # workers the fit has a free factor, but every solution still vanishes at the real ones: they are
+    # always among the A located, the other picks are innocent workers.
+    K, A, S, W, C = 4, 2, 1, 13, 6
+    alpha, beta = orc.chebyshev_nodes(K, W)
+    rng = np.random.default_rng(31 + real)
+    for trial in range(20):
+        X = rng.uniform(0, 1, (1, K, 24))
+        Mf = rng.standard_normal((24, C))
+        Y = (orc.encode(X, alpha, beta) @ Mf)[0]
+        avail = np.sort(rng.permutation(W)[: W - S])
+        ok = avail[np.abs(beta[avail]) > 1e-9]
+        bad = np.sort(rng.permutation(ok)[:real])
+        Y[bad] += 3.0 * rng.standard_normal((real, C))
+        adv, I, counts = orc.locate(Y, avail, beta, K, A)
+        assert set(bad.tolist()) <= set(adv.tolist())
+        assert len(set(adv.tolist())) == A and set(adv.tolist()) <= set(avail.tolist())
