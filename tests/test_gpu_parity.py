@@ -721,6 +721,95 @@ def test_wait_mask_feeds_the_decoder(gpu):
 
 
 # --------------------------------------------------------------------------------------
+# HIP graph capture: the calls allocate nothing, keep no state and enqueue kernels only
+# --------------------------------------------------------------------------------------
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed(gpu):
+    torch, binding, dev = gpu
+    K, N, S, D, C, G = 8, 12, 4, 3072, 100, 32
+    Kb, Ab, Sb, Nb, Cb = 8, 2, 4, 24, 10
+    rng = np.random.default_rng(123)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    alphab, betab = orc.chebyshev_nodes(Kb, Nb)
+    q = torch.zeros((G, K, D), dtype=torch.float32, device=dev)
+    coded = torch.zeros((G, N, D), dtype=torch.float32, device=dev)
+    arrival = torch.zeros((G, N), dtype=torch.float32, device=dev)
+    mask = torch.zeros((G, N), dtype=torch.uint8, device=dev)
+    count = torch.zeros((G,), dtype=torch.int32, device=dev)
+    preds = torch.zeros((G, N, C), dtype=torch.float32, device=dev)
+    out = torch.zeros((G, K, C), dtype=torch.float32, device=dev)
+    st = torch.zeros((G,), dtype=torch.int32, device=dev)
+    top1 = torch.zeros((G, K), dtype=torch.int32, device=dev)
+    predsb = torch.zeros((G, Nb, Cb), dtype=torch.float32, device=dev)
+    maskb = torch.zeros((G, Nb), dtype=torch.uint8, device=dev)
+    outb = torch.zeros((G, Kb, Cb), dtype=torch.float32, device=dev)
+    advb = torch.zeros((G, Ab), dtype=torch.int32, device=dev)
+    stb = torch.zeros((G,), dtype=torch.int32, device=dev)
+
+    def calls():
+        binding.approxifer_encode(q, alpha, beta, coded=coded)
+        binding.approxifer_wait_mask(arrival, N - S, mask=mask, count=count)
+        binding.approxifer_decode(preds, mask, alpha, beta, S, 1, out=out, status=st)
+        binding.approxifer_decode_top1(preds, mask, alpha, beta, S, 1, top1=top1, status=st, want_score=False)
+        binding.approxifer_decode_byzantine(predsb, maskb, alphab, betab, Sb, Ab, 1, out=outb, adv=advb, status=stb)
+
+    def fresh_inputs(seed):
+        r = np.random.default_rng(seed)
+        X = r.uniform(0, 1, (G, K, D)).astype(np.float32)
+        arr = r.exponential(1.0, (G, N)).astype(np.float32)
+        Y = r.standard_normal((G, N, C)).astype(np.float32)
+        Xb = r.uniform(0, 1, (G, Kb, 64))
+        clean = (orc.encode(Xb, alphab, betab) @ (r.standard_normal((64, Cb)) / 8)).astype(np.float32)
+        mb = np.zeros((G, Nb), np.uint8)
+        Yb = clean.copy()
+        for g in range(G):
+            avail = np.sort(r.permutation(Nb)[: Nb - Sb])
+            mb[g, avail] = 1
+            bad = np.sort(r.permutation(avail)[:Ab])
+            Yb[g, bad] += (10 * clean.std() * r.standard_normal((Ab, Cb))).astype(np.float32)
+        return X, arr, Y, Yb, mb
+
+    def upload(inp):
+        X, arr, Y, Yb, mb = inp
+        q.copy_(torch.from_numpy(X)); arrival.copy_(torch.from_numpy(arr)); preds.copy_(torch.from_numpy(Y))
+        predsb.copy_(torch.from_numpy(Yb)); maskb.copy_(torch.from_numpy(mb))
+
+    def check(inp):
+        X, arr, Y, Yb, mb = inp
+        assert group_err(coded.cpu().numpy(), orc.encode(X, alpha, beta)).max() <= TOL
+        m_ref, c_ref = orc.wait_mask(arr, N - S)
+        assert np.array_equal(mask.cpu().numpy(), m_ref) and np.array_equal(count.cpu().numpy(), c_ref)
+        ref, _ = orc.decode(Y, m_ref, alpha, beta, S, 1)
+        assert group_err(out.cpu().numpy(), ref).max() <= TOL
+        srt = np.sort(ref, axis=-1)
+        clear = (srt[..., -1] - srt[..., -2]) > 1e-9 * np.abs(ref).max(axis=-1)
+        assert np.array_equal(top1.cpu().numpy()[clear], ref.argmax(-1)[clear])
+        refb, adv_ref, _ = orc.decode_byzantine(Yb, mb, alphab, betab, Sb, Ab, 1)
+        assert np.array_equal(advb.cpu().numpy(), adv_ref)
+        assert group_err(outb.cpu().numpy(), refb).max() <= TOL
+
+    first = fresh_inputs(1)
+    upload(first)
+    calls()                                                 # eager, also loads every kernel before the capture
+    torch.cuda.synchronize()
+    check(first)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            calls()                                         # the binding passes torch's current stream: the capturing one
+    torch.cuda.synchronize()
+    for seed in (2, 3, 4):                                  # replays with new contents, eager work in between
+        inp = fresh_inputs(seed)
+        upload(inp)
+        for t in (coded, out, outb):
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        check(inp)
+
+
+# --------------------------------------------------------------------------------------
 # seeded random shapes: every entry point, every limit in play
 # --------------------------------------------------------------------------------------
 def test_random_shapes_all_entry_points(gpu):
