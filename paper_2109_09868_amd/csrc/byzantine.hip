@@ -234,18 +234,21 @@ struct ClassQrSteps<KEND, KEND, RM> {
 // transformed right-hand side in lane 15.  Every lane of the class ends with the whole solution.
 template <int T, int NS, int RM>
 struct BackSubst {
-    static __device__ __forceinline__ void run(const double (&a)[RM], double (&s)[NS], double (&q)[NS], int cols) {
+    // s enters as the transformed right-hand side and leaves as the solution: entry T is final once solved
+    static __device__ __forceinline__ void run(const double (&a)[RM], double (&s)[NS], int cols) {
         if (T < cols) {
-            q[T] = s[T] / row_bcast<T>(a[T]);
+            s[T] = s[T] / row_bcast<T>(a[T]);
 #pragma unroll
-            for (int i = 0; i < T; ++i) s[i] = fma(-row_bcast<T>(a[i]), q[T], s[i]);
+            for (int i = 0; i < T; ++i) s[i] = fma(-row_bcast<T>(a[i]), s[T], s[i]);
+        } else {
+            s[T] = 0.0;                                   // no such unknown
         }
-        BackSubst<T - 1, NS, RM>::run(a, s, q, cols);
+        BackSubst<T - 1, NS, RM>::run(a, s, cols);
     }
 };
 template <int NS, int RM>
 struct BackSubst<-1, NS, RM> {
-    static __device__ __forceinline__ void run(const double (&)[RM], double (&)[NS], double (&)[NS], int) {}
+    static __device__ __forceinline__ void run(const double (&)[RM], double (&)[NS], int) {}
 };
 
 // (value, row) minimum over the 16 lanes of a class: smaller value first, equal values: smaller row.
@@ -301,13 +304,10 @@ __device__ __forceinline__ void locate_classes_proj(const float *Ysh, int CW, in
     constexpr int kSteps = RM - 1 < kProjMaxM - 1 ? RM - 1 : kProjMaxM - 1;   // most unknowns this tile can hold
     ClassQrSteps<0, kSteps, RM>::run(a, j, cols);
 
-    double s[kSteps], q[kSteps];
+    double q[kSteps];                                     // right-hand side in, Q_1 .. Q_{M-1} out
 #pragma unroll
-    for (int i = 0; i < kSteps; ++i) {
-        s[i] = row_bcast<kClsLanes - 1>(a[i]);
-        q[i] = 0.0;
-    }
-    BackSubst<kSteps - 1, kSteps, RM>::run(a, s, q, cols);
+    for (int i = 0; i < kSteps; ++i) q[i] = row_bcast<kClsLanes - 1>(a[i]);
+    BackSubst<kSteps - 1, kSteps, RM>::run(a, q, cols);
 
     // a_r = Q(x_r) = 1 + sum_t q[t] x^(t+1) (q[t] = 0 for t >= cols), rows j, j+16, .. of this lane
     constexpr int PR = (NB + kClsLanes - 1) / kClsLanes;
@@ -352,7 +352,7 @@ __device__ __forceinline__ void locate_classes_proj(const float *Ysh, int CW, in
 // dynamic LDS (doubles): Ush[RM*NB] | Pw[NB*16] | xs[NB] | WdT[(n_cap-A)*KP] | alpha_s[K] | beta_s[N]
 //               then float Ysh[NB*CW], then ints: avail[N] | F[N] | Fpos[N] | votes[N] | sel[N] | n
 template <int NB, int RM>
-__global__ __launch_bounds__(256) void decode_byzantine_proj_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 ? 3 : 2))) void decode_byzantine_proj_kernel(
     const float *__restrict__ preds, const uint8_t *__restrict__ mask, float *__restrict__ out,
     int32_t *__restrict__ adv, int32_t *__restrict__ status, int K, int N, int S, int A, int64_t C, int64_t Cv,
     int vec4, int sign_mode, int n_cap, int cw_log2, const Nodes nodes) {
