@@ -22,24 +22,33 @@
 //    reaches 6.6 TB/s walked sequentially, 5.2 TB/s walked as 12+12 interleaved rows), i.e.
 //    with the number of tiles in flight.  The kernel therefore caps residency at a few waves
 //    per CU by reserving LDS it does not use: each wave has all K of its 128-bit loads in flight,
-//    which is enough to cover latency (1.76 ms uncapped, 1.62 ms at 7 waves per CU).
+//    which is enough to cover latency (1.76 ms uncapped, 1.60 ms at 6 waves per CU).
 #include "common.h"
 
 namespace approxifer {
 namespace {
 
-// Residency caps (workgroups per CU), found by sweeping 4..32 on the five benchmark shapes.
-#ifndef APPROXIFER_ENCODE_WAVES_PER_CU_SMALL_K
-#define APPROXIFER_ENCODE_WAVES_PER_CU_SMALL_K 7     // K <= 16: one-wave workgroups
+// Residency caps (workgroups per CU), from sweeps on the benchmark shapes and on a K x N x D grid.
+// K <= 16, one-wave workgroups: enough waves to keep about 48 KB of query loads in flight per CU (a wave
+// has K loads of 1 KB each), never fewer than six and never more than 24: measured optima are 20+ at K = 1,
+// 12..16 at K = 2, 8..12 at K = 4..6, 6 at K = 8..16 (7 and up lose 1..4 % there: more row streams open).
+#ifndef APPROXIFER_ENCODE_WAVES_PER_CU_MIN
+#define APPROXIFER_ENCODE_WAVES_PER_CU_MIN 6
+#endif
+#ifndef APPROXIFER_ENCODE_LOAD_KB_PER_CU
+#define APPROXIFER_ENCODE_LOAD_KB_PER_CU 48
 #endif
 #ifndef APPROXIFER_ENCODE_BLOCKS_PER_CU_LARGE_K
 #define APPROXIFER_ENCODE_BLOCKS_PER_CU_LARGE_K 2    // K > 16: four-wave workgroups
 #endif
 #ifndef APPROXIFER_ENCODE_MFMA_MIN_K
-#define APPROXIFER_ENCODE_MFMA_MIN_K 17            // smallest K served by the matrix-core variant
+#define APPROXIFER_ENCODE_MFMA_MIN_K 17            // from this K on the matrix-core variant serves every shape
+#endif
+#ifndef APPROXIFER_ENCODE_MFMA_WIDE_MIN_K
+#define APPROXIFER_ENCODE_MFMA_WIDE_MIN_K 8        // .. and from this K on the shapes with N >= 2K + 4
 #endif
 #ifndef APPROXIFER_ENCODE_MFMA_BLOCKS_PER_CU
-#define APPROXIFER_ENCODE_MFMA_BLOCKS_PER_CU 4       // K > 16, matrix-core variant (four waves of 64 columns)
+#define APPROXIFER_ENCODE_MFMA_BLOCKS_PER_CU 4       // matrix-core variant (four waves of 64 columns)
 #endif
 constexpr int kLdsPerCu = 160 * 1024;                // gfx950
 
@@ -284,11 +293,17 @@ int run_encode_shape(const float *d_queries, float *d_coded, int64_t tiles, int6
                      int64_t Dv, const Nodes &nodes, hipStream_t stream) {
     constexpr int KP = (K + 3) & ~3;
     constexpr int THREADS = K <= 16 ? 64 : 256;
-    constexpr int PER_CU = K <= 16 ? APPROXIFER_ENCODE_WAVES_PER_CU_SMALL_K : APPROXIFER_ENCODE_BLOCKS_PER_CU_LARGE_K;
+    int per_cu = APPROXIFER_ENCODE_BLOCKS_PER_CU_LARGE_K;
+    if (K <= 16) {
+        per_cu = (APPROXIFER_ENCODE_LOAD_KB_PER_CU + K - 1) / K;     // K loads of 1 KB per wave
+        if (per_cu < APPROXIFER_ENCODE_WAVES_PER_CU_MIN) per_cu = APPROXIFER_ENCODE_WAVES_PER_CU_MIN;
+        if (per_cu > 24) per_cu = 24;
+        if (VEC == 1) per_cu = 7;       // rows not 16-byte aligned, 4-byte accesses: 2.5..3.3 TB/s whatever the cap
+    }
     if (tiles > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
     const size_t lds_used = static_cast<size_t>(N) * KP * sizeof(float);
-    // reserve 1/PER_CU of the CU's LDS so that at most PER_CU workgroups are resident
-    size_t lds = (static_cast<size_t>(kLdsPerCu / PER_CU) / 512) * 512;
+    // reserve 1/per_cu of the CU's LDS so that at most per_cu workgroups are resident
+    size_t lds = (static_cast<size_t>(kLdsPerCu / per_cu) / 512) * 512;
     if (lds < lds_used) lds = lds_used;
     if (lds > 64 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(encode_kernel<K, VEC, THREADS, FLAT>),
@@ -324,6 +339,15 @@ int run_encode_k(const float *d_queries, float *d_coded, int64_t G, int N, int64
     if constexpr (K >= APPROXIFER_ENCODE_MFMA_MIN_K) {
         if (aligned16) return run_encode_mfma<(K + 3) / 4>(d_queries, d_coded, G, K, N, D, nodes, stream);
     } else {
+        if constexpr (K >= APPROXIFER_ENCODE_MFMA_WIDE_MIN_K) {
+            // Many more coded than plain queries (the Byzantine worker counts, N = 2 (K + A) + S): a one-wave
+            // tile would keep K + N >= 3K + 4 row streams open, and the matrix-core variant, whose waves work on
+            // 256-byte row segments, measures 4..14 % faster (K=8, N=24: 5.7 -> 6.2 TB/s; K=12, N=36: 5.5 -> 6.0).
+            // It has no flattened tiling, so rows must fill its 64-column workgroups to within 3 %.
+            const int64_t cols = D / 4, blocks = (cols + 63) / 64;
+            if (aligned16 && N >= 2 * K + 4 && (blocks * 64 - cols) * 100 <= 3 * blocks * 64)
+                return run_encode_mfma<(K + 3) / 4>(d_queries, d_coded, G, K, N, D, nodes, stream);
+        }
         if (aligned16) return run_encode<K, 4>(d_queries, d_coded, G, N, D, nodes, stream);
     }
     return run_encode<K, 1>(d_queries, d_coded, G, N, D, nodes, stream);

@@ -52,6 +52,11 @@ def test_encode_tiny_workload(gpu):
     # K > 16 with 16-byte rows: the matrix-core kernel; K % 4 != 0, N % 16 != 0, ragged column tiles
     (17, 21, 4 * 100, 3), (20, 33, 4 * 65, 2), (22, 16, 4 * 64, 2), (24, 36, 4 * 700 + 4, 2), (31, 47, 4 * 3, 3),
     (32, 48, 4 * 1024, 2), (47, 100, 4 * 129, 1), (63, 127, 4 * 77, 2), (64, 65, 4 * 64, 1), (18, 2, 4 * 50, 2),
+    # 8 <= K <= 16 with N >= 2K + 4 and full 64-column blocks: the matrix-core kernel; neighbours stay on the vector kernel
+    (8, 24, 4 * 64 * 3, 2), (12, 28, 4 * 128, 2), (16, 36, 4 * 64, 2), (9, 24, 4 * 64 * 2, 2), (8, 20, 4 * 64, 3),
+    (8, 19, 4 * 64, 3), (8, 24, 4 * 70, 2), (7, 24, 4 * 64, 2), (13, 128, 4 * 64, 1),
+    # residency caps: K = 1, 2, 4 run with many more waves per CU
+    (1, 2, 4 * 64 * 40, 3), (2, 3, 4 * 64 * 33, 3), (4, 6, 4 * 64 * 21, 2),
 ])
 def test_encode_shapes_with_ragged_tails(gpu, K, N, D, G):
     torch, binding, dev = gpu
