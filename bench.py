@@ -29,9 +29,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # (profiles/encode_imagenet_hbm_counters.md).  Valid only for the kernel sources hashed here.
 ENCODE_KERNEL_SOURCES = ("paper_2109_09868_amd/csrc/encode.hip", "paper_2109_09868_amd/csrc/common.h")
 ENCODE_TRAFFIC = {
-    "sources_sha256": "256d50dbebe67d99105a4f08d2364588adabb77de120545bb16168543a1d4bd1",
-    "fetch_size_kib": 1806384.6, "fetch_factor": 2.0000,     # counter reads half the bytes of a known copy
-    "write_size_kib": 6021165.1, "write_factor": 1.0000,
+    "sources_sha256": "8cda2bb6343c793baab7fd7acf3b9f0980fbccc75eec096fb4c8856f47786a09",
+    "fetch_size_kib": 1806384.3, "fetch_factor": 2.0000,     # counter reads half the bytes of a known copy
+    "write_size_kib": 6021141.8, "write_factor": 1.0000,
 }
 
 
@@ -57,6 +57,24 @@ def decode_bytes(w, byzantine=False):
     if byzantine:
         return (4 * w.C * n + w.W + 4 * w.C * w.K + 4 * w.A) * w.G
     return (4 * w.C * n + w.W + 4 * w.C * w.K) * w.G
+
+
+FP64_VECTOR_PEAK_TFLOPS = 78.6   # MI355X, published: 256 CUs x 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz
+
+
+def locator_flops(w):
+    """Flops of Algorithm 2's least-squares fits as the method defines them: per class one Householder solve of the
+    n x (2M - 1) system, 2 n c^2 - (2/3) c^3 with c = 2M - 1 columns (the kernel's projected form needs fewer)."""
+    n, c = w.W - w.S, 2 * (w.K + w.A) - 1
+    return (2.0 * n * c * c - 2.0 * c ** 3 / 3.0) * w.C * w.G
+
+
+def alu_roofline(w, avg_ms):
+    achieved = locator_flops(w) / (avg_ms * 1e9)            # TFLOP/s
+    return {"bound": "alu", "achieved": achieved, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": achieved / FP64_VECTOR_PEAK_TFLOPS,
+            "note": "float64 vector ALU; flops of the full-system Householder solves the method defines, "
+                    "chains of dependent operations on 20x19 .. 28x27 systems"}
 
 
 def event_ms(pairs):
@@ -218,7 +236,7 @@ def other_workloads(torch, binding, syn, orc_nodes, dev, sign_mode):
     res["byzantine_decode"] = dict(t, predictions_per_s=w.G * w.K / (t["avg_ms"] * 1e-3),
                                    locator_solves_per_s=w.G * w.C / (t["avg_ms"] * 1e-3),
                                    hbm_gbs=decode_bytes(w, True) / (t["avg_ms"] * 1e6),
-                                   planted_adversaries_located=located, note=COLD)
+                                   planted_adversaries_located=located, roofline=alu_roofline(w, t["avg_ms"]), note=COLD)
     del q, coded
 
     # -- the paper's Byzantine operating point: K = 12, S = 0, E = 2, 28 workers, MNIST-sized queries ---
@@ -244,7 +262,8 @@ def other_workloads(torch, binding, syn, orc_nodes, dev, sign_mode):
     res["mnist_byz_k12_decode"] = dict(t, predictions_per_s=w.G * w.K / (t["avg_ms"] * 1e-3),
                                        locator_solves_per_s=w.G * w.C / (t["avg_ms"] * 1e-3),
                                        hbm_gbs=decode_bytes(w, True) / (t["avg_ms"] * 1e6),
-                                       groups_with_planted_adversaries_located=located, note=COLD)
+                                       groups_with_planted_adversaries_located=located,
+                                       roofline=alu_roofline(w, t["avg_ms"]), note=COLD)
     del q, coded
 
     # -- text shapes: encode only (decode there moves < 1 MB) -----------------------------------
@@ -348,7 +367,7 @@ def main():
                    "hbm_gbs": achieved, "fp32_tflops": 2.0 * w.K * w.W * w.D * w.G / (enc_avg * 1e9)},
         "decode": {"avg_ms": dec_avg, "min_ms": min(dec_ms), "predictions_per_s": w.G * w.K / (dec_avg * 1e-3),
                    "hbm_gbs": decode_bytes(w) / (dec_avg * 1e6)},
-        "roofline": {"bound": "hbm", "kernel": "encode_kernel<12, 4, 64, false>", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "encode_kernel<12, 4, 64, false, false>", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic_bytes(),
                      "algorithmic_bytes_per_launch": encode_bytes(w)},
     }

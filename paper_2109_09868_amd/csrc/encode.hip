@@ -52,20 +52,28 @@ namespace {
 #endif
 constexpr int kLdsPerCu = 160 * 1024;                // gfx950
 
+// Register type of VEC floats, and the type a lane loads and stores it through.  Rows that are only
+// 4-byte aligned (a row length that is not a multiple of 4 floats, or an offset base pointer) are still
+// moved 128 bits at a time: gfx950 serves dword-aligned 128-bit global accesses, and the compiler emits them
+// for a vector type declared with 4-byte alignment.
 template <int VEC> struct VecOf;
 template <> struct VecOf<4> { typedef v4f type; };
 template <> struct VecOf<2> { typedef v2f type; };
 template <> struct VecOf<1> { typedef float type; };
+typedef v4f v4f_align4 __attribute__((aligned(4)));
+template <int VEC, bool UNAL> struct MemOf { typedef typename VecOf<VEC>::type type; };
+template <> struct MemOf<4, true> { typedef v4f_align4 type; };
 
-template <int VEC>
+template <int VEC, bool UNAL = false>
 __device__ __forceinline__ typename VecOf<VEC>::type load_stream(const float *p) {
-    typedef typename VecOf<VEC>::type V;
-    return __builtin_nontemporal_load(reinterpret_cast<const V *>(p));
+    typedef typename MemOf<VEC, UNAL>::type M;
+    const M v = __builtin_nontemporal_load(reinterpret_cast<const M *>(p));
+    return v;
 }
-template <int VEC>
+template <int VEC, bool UNAL = false>
 __device__ __forceinline__ void store_stream(float *p, typename VecOf<VEC>::type v) {
-    typedef typename VecOf<VEC>::type V;
-    __builtin_nontemporal_store(v, reinterpret_cast<V *>(p));
+    typedef typename MemOf<VEC, UNAL>::type M;
+    __builtin_nontemporal_store(static_cast<M>(v), reinterpret_cast<M *>(p));
 }
 
 // K: queries per group (compile time so that the K input columns stay in registers).
@@ -75,10 +83,12 @@ __device__ __forceinline__ void store_stream(float *p, typename VecOf<VEC>::type
 //       whole batch are numbered consecutively and a workgroup takes THREADS of them, so lanes never idle at a
 //       row end.  Used when rows are short and ragged (28 x 28 queries: 196 vector columns, 23 % idle lanes
 //       otherwise); `chunks` then carries the total number of pairs.
-template <int K, int VEC, int THREADS, bool FLAT>
+// UNAL: rows are only 4-byte aligned (VEC == 4 accesses then go through the 4-byte-aligned vector type).
+// col0: first float column served; columns col0 + VEC * [0, Dv) are produced.
+template <int K, int VEC, int THREADS, bool FLAT, bool UNAL>
 __global__ __launch_bounds__(THREADS) void encode_kernel(
     const float *__restrict__ queries, float *__restrict__ coded, int N, int64_t D, int64_t Dv,
-    int64_t chunks, const Nodes nodes) {
+    int64_t chunks, int64_t col0, const Nodes nodes) {
     typedef typename VecOf<VEC>::type V;
     constexpr int KP = (K + 3) & ~3;       // weight row padded to whole float4s
     constexpr int LPR = K <= 16 ? 16 : (K <= 32 ? 32 : 64);   // lanes per weight row
@@ -106,13 +116,13 @@ __global__ __launch_bounds__(THREADS) void encode_kernel(
         ok = col < Dv;
         if (!ok) col = 0;                  // lanes past the ragged end read column 0 of the group and store nothing
     }
-    const float *xg = queries + static_cast<size_t>(g) * K * D + col * VEC;
-    float *og = coded + static_cast<size_t>(g) * N * D + col * VEC;
+    const float *xg = queries + static_cast<size_t>(g) * K * D + col0 + col * VEC;
+    float *og = coded + static_cast<size_t>(g) * N * D + col0 + col * VEC;
 
     // ---- this lane's column of the K queries: issue every load before anything else ----
     V x[K];
 #pragma unroll
-    for (int j = 0; j < K; ++j) x[j] = load_stream<VEC>(xg + static_cast<size_t>(j) * D);
+    for (int j = 0; j < K; ++j) x[j] = load_stream<VEC, UNAL>(xg + static_cast<size_t>(j) * D);
 
     // ---- l_j(beta_i) in float64, one group of LPR lanes per worker row ---------------------
     // The nodes are read with compile-time or wave-uniform indices only, i.e. through scalar
@@ -159,7 +169,7 @@ __global__ __launch_bounds__(THREADS) void encode_kernel(
             for (int jj = 0; jj < 4; ++jj)
                 if (4 * j4 + jj < K) acc = w[jj] * x[4 * j4 + jj] + acc;
         }
-        if (ok) store_stream<VEC>(og + static_cast<size_t>(i) * D, acc);
+        if (ok) store_stream<VEC, UNAL>(og + static_cast<size_t>(i) * D, acc);
     }
 }
 
@@ -179,7 +189,7 @@ __global__ __launch_bounds__(THREADS) void encode_kernel(
 // The weights sit in LDS already in A-operand order, wA[(mt*KS + s)*64 + l].
 constexpr int kMfmaThreads = 256;
 
-template <int KS>   // KS = ceil(K / 4) k-steps
+template <int KS, bool UNAL>   // KS = ceil(K / 4) k-steps; UNAL: rows only 4-byte aligned
 __global__ __launch_bounds__(kMfmaThreads) void encode_mfma_kernel(
     const float *__restrict__ queries, float *__restrict__ coded, int K, int N, int64_t D, int64_t Dv,
     int64_t chunks, const Nodes nodes) {
@@ -203,7 +213,7 @@ __global__ __launch_bounds__(kMfmaThreads) void encode_mfma_kernel(
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
         const int row = (4 * s + krow < K) ? 4 * s + krow : K - 1;
-        x[s] = load_stream<4>(xg + static_cast<size_t>(row) * D);
+        x[s] = load_stream<4, UNAL>(xg + static_cast<size_t>(row) * D);
     }
 
     // ---- l_j(beta_i) in float64 (scalar node loads only, see encode_kernel), stored in A order ----
@@ -262,13 +272,13 @@ __global__ __launch_bounds__(kMfmaThreads) void encode_mfma_kernel(
                 v[1] = acc[1][r];
                 v[2] = acc[2][r];
                 v[3] = acc[3][r];
-                store_stream<4>(og + static_cast<size_t>(i) * D, v);
+                store_stream<4, UNAL>(og + static_cast<size_t>(i) * D, v);
             }
         }
     }
 }
 
-template <int KS>
+template <int KS, bool UNAL>
 int run_encode_mfma(const float *d_queries, float *d_coded, int64_t G, int K, int N, int64_t D, const Nodes &nodes,
                     hipStream_t stream) {
     const int64_t Dv = D / 4;
@@ -280,17 +290,17 @@ int run_encode_mfma(const float *d_queries, float *d_coded, int64_t G, int K, in
     size_t lds = (static_cast<size_t>(kLdsPerCu / APPROXIFER_ENCODE_MFMA_BLOCKS_PER_CU) / 512) * 512;
     if (lds < lds_used) lds = lds_used;
     if (lds > 64 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_mfma_kernel<KS>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_mfma_kernel<KS, UNAL>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
         return APPROXIFER_ERR_LAUNCH;
-    hipLaunchKernelGGL((encode_mfma_kernel<KS>), dim3(static_cast<unsigned>(tiles)), dim3(kMfmaThreads), lds, stream,
+    hipLaunchKernelGGL((encode_mfma_kernel<KS, UNAL>), dim3(static_cast<unsigned>(tiles)), dim3(kMfmaThreads), lds, stream,
                        d_queries, d_coded, K, N, D, Dv, chunks, nodes);
     return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
 }
 
-template <int K, int VEC, bool FLAT>
+template <int K, int VEC, bool FLAT, bool UNAL>
 int run_encode_shape(const float *d_queries, float *d_coded, int64_t tiles, int64_t chunks, int N, int64_t D,
-                     int64_t Dv, const Nodes &nodes, hipStream_t stream) {
+                     int64_t Dv, int64_t col0, const Nodes &nodes, hipStream_t stream) {
     constexpr int KP = (K + 3) & ~3;
     constexpr int THREADS = K <= 16 ? 64 : 256;
     int per_cu = APPROXIFER_ENCODE_BLOCKS_PER_CU_LARGE_K;
@@ -298,7 +308,7 @@ int run_encode_shape(const float *d_queries, float *d_coded, int64_t tiles, int6
         per_cu = (APPROXIFER_ENCODE_LOAD_KB_PER_CU + K - 1) / K;     // K loads of 1 KB per wave
         if (per_cu < APPROXIFER_ENCODE_WAVES_PER_CU_MIN) per_cu = APPROXIFER_ENCODE_WAVES_PER_CU_MIN;
         if (per_cu > 24) per_cu = 24;
-        if (VEC == 1) per_cu = 7;       // rows not 16-byte aligned, 4-byte accesses: 2.5..3.3 TB/s whatever the cap
+        if (VEC == 1) per_cu = 7;       // 4-byte accesses (the last D % 4 columns, or D < 4): a sliver of the work
     }
     if (tiles > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
     const size_t lds_used = static_cast<size_t>(N) * KP * sizeof(float);
@@ -306,38 +316,37 @@ int run_encode_shape(const float *d_queries, float *d_coded, int64_t tiles, int6
     size_t lds = (static_cast<size_t>(kLdsPerCu / per_cu) / 512) * 512;
     if (lds < lds_used) lds = lds_used;
     if (lds > 64 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_kernel<K, VEC, THREADS, FLAT>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_kernel<K, VEC, THREADS, FLAT, UNAL>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
         return APPROXIFER_ERR_LAUNCH;
-    hipLaunchKernelGGL((encode_kernel<K, VEC, THREADS, FLAT>), dim3(static_cast<unsigned>(tiles)), dim3(THREADS), lds,
-                       stream, d_queries, d_coded, N, D, Dv, chunks, nodes);
+    hipLaunchKernelGGL((encode_kernel<K, VEC, THREADS, FLAT, UNAL>), dim3(static_cast<unsigned>(tiles)), dim3(THREADS),
+                       lds, stream, d_queries, d_coded, N, D, Dv, chunks, col0, nodes);
     return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
 }
 
-template <int K, int VEC>
-int run_encode(const float *d_queries, float *d_coded, int64_t G, int N, int64_t D, const Nodes &nodes,
-               hipStream_t stream) {
+// Vector columns [0, Dv) of width VEC floats, starting at float column col0.
+template <int K, int VEC, bool UNAL>
+int run_encode(const float *d_queries, float *d_coded, int64_t G, int N, int64_t D, int64_t Dv, int64_t col0,
+               const Nodes &nodes, hipStream_t stream) {
     constexpr int THREADS = K <= 16 ? 64 : 256;
-    const int64_t Dv = D / VEC;
     const int64_t chunks = (Dv + THREADS - 1) / THREADS;
     // lanes left idle at the row ends by the per-group tiling; above 3 % the flattened numbering pays for its
     // per-lane division and addresses
     const int64_t idle = chunks * THREADS - Dv;
     if (idle * 100 > 3 * chunks * THREADS) {
         const int64_t pairs = G * Dv;
-        return run_encode_shape<K, VEC, true>(d_queries, d_coded, (pairs + THREADS - 1) / THREADS, pairs, N, D, Dv, nodes,
-                                              stream);
+        return run_encode_shape<K, VEC, true, UNAL>(d_queries, d_coded, (pairs + THREADS - 1) / THREADS, pairs, N, D, Dv,
+                                                    col0, nodes, stream);
     }
-    return run_encode_shape<K, VEC, false>(d_queries, d_coded, G * chunks, chunks, N, D, Dv, nodes, stream);
+    return run_encode_shape<K, VEC, false, UNAL>(d_queries, d_coded, G * chunks, chunks, N, D, Dv, col0, nodes, stream);
 }
 
-template <int K>
-int run_encode_k(const float *d_queries, float *d_coded, int64_t G, int N, int64_t D, const Nodes &nodes,
-                 hipStream_t stream) {
-    const bool aligned16 = (reinterpret_cast<uintptr_t>(d_queries) % 16 == 0) &&
-                           (reinterpret_cast<uintptr_t>(d_coded) % 16 == 0) && (D % 4 == 0);
+// 128-bit columns: the matrix-core kernel or the vector kernel, by shape.
+template <int K, bool UNAL>
+int run_encode_wide(const float *d_queries, float *d_coded, int64_t G, int N, int64_t D, const Nodes &nodes,
+                    hipStream_t stream) {
     if constexpr (K >= APPROXIFER_ENCODE_MFMA_MIN_K) {
-        if (aligned16) return run_encode_mfma<(K + 3) / 4>(d_queries, d_coded, G, K, N, D, nodes, stream);
+        return run_encode_mfma<(K + 3) / 4, UNAL>(d_queries, d_coded, G, K, N, D, nodes, stream);
     } else {
         if constexpr (K >= APPROXIFER_ENCODE_MFMA_WIDE_MIN_K) {
             // Many more coded than plain queries (the Byzantine worker counts, N = 2 (K + A) + S): a one-wave
@@ -345,12 +354,27 @@ int run_encode_k(const float *d_queries, float *d_coded, int64_t G, int N, int64
             // 256-byte row segments, measures 4..14 % faster (K=8, N=24: 5.7 -> 6.2 TB/s; K=12, N=36: 5.5 -> 6.0).
             // It has no flattened tiling, so rows must fill its 64-column workgroups to within 3 %.
             const int64_t cols = D / 4, blocks = (cols + 63) / 64;
-            if (aligned16 && N >= 2 * K + 4 && (blocks * 64 - cols) * 100 <= 3 * blocks * 64)
-                return run_encode_mfma<(K + 3) / 4>(d_queries, d_coded, G, K, N, D, nodes, stream);
+            if (N >= 2 * K + 4 && (blocks * 64 - cols) * 100 <= 3 * blocks * 64)
+                return run_encode_mfma<(K + 3) / 4, UNAL>(d_queries, d_coded, G, K, N, D, nodes, stream);
         }
-        if (aligned16) return run_encode<K, 4>(d_queries, d_coded, G, N, D, nodes, stream);
+        return run_encode<K, 4, UNAL>(d_queries, d_coded, G, N, D, D / 4, 0, nodes, stream);
     }
-    return run_encode<K, 1>(d_queries, d_coded, G, N, D, nodes, stream);
+}
+
+template <int K>
+int run_encode_k(const float *d_queries, float *d_coded, int64_t G, int N, int64_t D, const Nodes &nodes,
+                 hipStream_t stream) {
+    const bool aligned16 = (reinterpret_cast<uintptr_t>(d_queries) % 16 == 0) &&
+                           (reinterpret_cast<uintptr_t>(d_coded) % 16 == 0) && (D % 4 == 0);
+    if (aligned16) return run_encode_wide<K, false>(d_queries, d_coded, G, N, D, nodes, stream);
+    // rows only 4-byte aligned: 128-bit accesses on the first 4 * (D / 4) columns, 4-byte accesses on the rest
+    if (D >= 4) {
+        const int rc = run_encode_wide<K, true>(d_queries, d_coded, G, N, D, nodes, stream);
+        if (rc != APPROXIFER_OK) return rc;
+    }
+    const int64_t tail = D % 4;
+    if (tail == 0) return APPROXIFER_OK;
+    return run_encode<K, 1, false>(d_queries, d_coded, G, N, D, tail, D - tail, nodes, stream);
 }
 
 }  // namespace

@@ -68,20 +68,25 @@ def test_encode_shapes_with_ragged_tails(gpu, K, N, D, G):
     assert err.max() <= TOL, err.max()
 
 
-def test_encode_unaligned_pointers_and_canaries(gpu):
+@pytest.mark.parametrize("K,N,D,G,off_in,off_out", [
+    (6, 10, 1000, 2, 1, 3), (6, 10, 1003, 3, 0, 0), (6, 10, 1001, 2, 1, 2), (12, 20, 4 * 64 * 3 + 2, 2, 3, 1),
+    (8, 24, 4 * 64 * 2 + 1, 2, 2, 2), (20, 30, 4 * 64 + 3, 2, 1, 1), (33, 40, 4 * 64 * 2, 1, 3, 3), (3, 5, 2, 4, 1, 1),
+])
+def test_encode_unaligned_pointers_and_canaries(gpu, K, N, D, G, off_in, off_out):
+    # rows that are only 4-byte aligned (odd row length and/or offset base pointers): 128-bit accesses through the
+    # 4-byte-aligned vector type plus a 4-byte tail; nothing outside the output tensor may be touched
     torch, binding, dev = gpu
-    K, N, D, G = 6, 10, 1000, 2
     alpha, beta = orc.chebyshev_nodes(K, N)
-    X = np.random.default_rng(5).uniform(0, 1, (G, K, D)).astype(np.float32)
-    flat_in = torch.zeros(G * K * D + 3, dtype=torch.float32, device=dev)
-    flat_in[1:1 + G * K * D] = torch.from_numpy(X).to(dev).reshape(-1)
-    q = flat_in[1:1 + G * K * D].view(G, K, D)            # 4-byte aligned only
-    flat_out = torch.full((G * N * D + 9,), 7.5, dtype=torch.float32, device=dev)
-    c = flat_out[3:3 + G * N * D].view(G, N, D)
+    X = np.random.default_rng(5 + D).uniform(0, 1, (G, K, D)).astype(np.float32)
+    flat_in = torch.zeros(G * K * D + off_in + 5, dtype=torch.float32, device=dev)
+    flat_in[off_in:off_in + G * K * D] = torch.from_numpy(X).to(dev).reshape(-1)
+    q = flat_in[off_in:off_in + G * K * D].view(G, K, D)
+    flat_out = torch.full((G * N * D + off_out + 9,), 7.5, dtype=torch.float32, device=dev)
+    c = flat_out[off_out:off_out + G * N * D].view(G, N, D)
     binding.approxifer_encode(q, alpha, beta, coded=c)
     err = group_err(c.cpu().numpy(), orc.encode(X, alpha, beta))
     assert err.max() <= TOL
-    assert torch.all(flat_out[:3] == 7.5) and torch.all(flat_out[3 + G * N * D:] == 7.5)
+    assert torch.all(flat_out[:off_out] == 7.5) and torch.all(flat_out[off_out + G * N * D:] == 7.5)
 
 
 def test_encode_node_coincidence_passes_query_through(gpu):
