@@ -189,7 +189,9 @@ __global__ __launch_bounds__(THREADS) void encode_kernel(
 // The weights sit in LDS already in A-operand order, wA[(mt*KS + s)*64 + l].
 constexpr int kMfmaThreads = 256;
 
-template <int KS, bool UNAL>   // KS = ceil(K / 4) k-steps; UNAL: rows only 4-byte aligned
+// KS = ceil(K / 4) k-steps; UNAL: rows only 4-byte aligned; FLAT: the 16-column wave tiles run over the flattened
+// (group, vector column) numbering of the batch (`chunks` = number of pairs), as in encode_kernel.
+template <int KS, bool UNAL, bool FLAT>
 __global__ __launch_bounds__(kMfmaThreads) void encode_mfma_kernel(
     const float *__restrict__ queries, float *__restrict__ coded, int K, int N, int64_t D, int64_t Dv,
     int64_t chunks, const Nodes nodes) {
@@ -200,12 +202,28 @@ __global__ __launch_bounds__(kMfmaThreads) void encode_mfma_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wv = tid >> 6;
-    const int64_t g = blockIdx.x / chunks;
-    const int64_t ch = blockIdx.x - g * chunks;
-    const int64_t col = (ch * (kMfmaThreads / 64) + wv) * 16 + (lane & 15);   // this lane's vector column
-    const bool ok = col < Dv;
+    int64_t g, col;                                           // this lane's group and vector column
+    bool ok;
+    if (FLAT) {
+        const int64_t q = (static_cast<int64_t>(blockIdx.x) * (kMfmaThreads / 64) + wv) * 16 + (lane & 15);
+        ok = q < chunks;
+        const int64_t qq = ok ? q : 0;
+        if (chunks <= 0xffffffffLL) {
+            const uint32_t g32 = static_cast<uint32_t>(qq) / static_cast<uint32_t>(Dv);
+            g = g32;
+            col = static_cast<uint32_t>(qq) - g32 * static_cast<uint32_t>(Dv);
+        } else {
+            g = qq / Dv;
+            col = qq - g * Dv;
+        }
+    } else {
+        g = blockIdx.x / chunks;
+        col = ((blockIdx.x - g * chunks) * (kMfmaThreads / 64) + wv) * 16 + (lane & 15);
+        ok = col < Dv;
+        if (!ok) col = 0;
+    }
     const int krow = lane >> 4;                               // row offset inside a k-step
-    const float *xg = queries + static_cast<size_t>(g) * K * D + (ok ? col : 0) * 4;
+    const float *xg = queries + static_cast<size_t>(g) * K * D + col * 4;
     float *og = coded + static_cast<size_t>(g) * N * D + col * 4;
 
     // ---- query rows 4s + krow, columns 4*col..+3; rows past K are clamped (their weights are 0) ----
@@ -278,24 +296,35 @@ __global__ __launch_bounds__(kMfmaThreads) void encode_mfma_kernel(
     }
 }
 
+template <int KS, bool UNAL, bool FLAT>
+int run_encode_mfma_shape(const float *d_queries, float *d_coded, int64_t tiles, int64_t chunks, int K, int N, int64_t D,
+                          int64_t Dv, const Nodes &nodes, hipStream_t stream) {
+    if (tiles > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    const size_t lds_used = static_cast<size_t>((N + 15) / 16) * KS * 64 * sizeof(float);
+    size_t lds = (static_cast<size_t>(kLdsPerCu / APPROXIFER_ENCODE_MFMA_BLOCKS_PER_CU) / 512) * 512;
+    if (lds < lds_used) lds = lds_used;
+    if (lds > 64 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_mfma_kernel<KS, UNAL, FLAT>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
+        return APPROXIFER_ERR_LAUNCH;
+    hipLaunchKernelGGL((encode_mfma_kernel<KS, UNAL, FLAT>), dim3(static_cast<unsigned>(tiles)), dim3(kMfmaThreads), lds,
+                       stream, d_queries, d_coded, K, N, D, Dv, chunks, nodes);
+    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+}
+
 template <int KS, bool UNAL>
 int run_encode_mfma(const float *d_queries, float *d_coded, int64_t G, int K, int N, int64_t D, const Nodes &nodes,
                     hipStream_t stream) {
     const int64_t Dv = D / 4;
     const int64_t cols_per_block = (kMfmaThreads / 64) * 16;           // vector columns per workgroup
     const int64_t chunks = (Dv + cols_per_block - 1) / cols_per_block;
-    const int64_t tiles = G * chunks;
-    if (tiles > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
-    const size_t lds_used = static_cast<size_t>((N + 15) / 16) * KS * 64 * sizeof(float);
-    size_t lds = (static_cast<size_t>(kLdsPerCu / APPROXIFER_ENCODE_MFMA_BLOCKS_PER_CU) / 512) * 512;
-    if (lds < lds_used) lds = lds_used;
-    if (lds > 64 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_mfma_kernel<KS, UNAL>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
-        return APPROXIFER_ERR_LAUNCH;
-    hipLaunchKernelGGL((encode_mfma_kernel<KS, UNAL>), dim3(static_cast<unsigned>(tiles)), dim3(kMfmaThreads), lds, stream,
-                       d_queries, d_coded, K, N, D, Dv, chunks, nodes);
-    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+    const int64_t idle = chunks * cols_per_block - Dv;                  // columns without data at the row ends
+    if (idle * 100 > 3 * chunks * cols_per_block) {
+        const int64_t pairs = G * Dv;
+        return run_encode_mfma_shape<KS, UNAL, true>(d_queries, d_coded, (pairs + cols_per_block - 1) / cols_per_block,
+                                                     pairs, K, N, D, Dv, nodes, stream);
+    }
+    return run_encode_mfma_shape<KS, UNAL, false>(d_queries, d_coded, G * chunks, chunks, K, N, D, Dv, nodes, stream);
 }
 
 template <int K, int VEC, bool FLAT, bool UNAL>
@@ -352,9 +381,7 @@ int run_encode_wide(const float *d_queries, float *d_coded, int64_t G, int N, in
             // Many more coded than plain queries (the Byzantine worker counts, N = 2 (K + A) + S): a one-wave
             // tile would keep K + N >= 3K + 4 row streams open, and the matrix-core variant, whose waves work on
             // 256-byte row segments, measures 4..14 % faster (K=8, N=24: 5.7 -> 6.2 TB/s; K=12, N=36: 5.5 -> 6.0).
-            // It has no flattened tiling, so rows must fill its 64-column workgroups to within 3 %.
-            const int64_t cols = D / 4, blocks = (cols + 63) / 64;
-            if (N >= 2 * K + 4 && (blocks * 64 - cols) * 100 <= 3 * blocks * 64)
+            if (N >= 2 * K + 4)
                 return run_encode_mfma<(K + 3) / 4, UNAL>(d_queries, d_coded, G, K, N, D, nodes, stream);
         }
         return run_encode<K, 4, UNAL>(d_queries, d_coded, G, N, D, D / 4, 0, nodes, stream);

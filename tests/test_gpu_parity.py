@@ -55,6 +55,8 @@ def test_encode_tiny_workload(gpu):
     # 8 <= K <= 16 with N >= 2K + 4 and full 64-column blocks: the matrix-core kernel; neighbours stay on the vector kernel
     (8, 24, 4 * 64 * 3, 2), (12, 28, 4 * 128, 2), (16, 36, 4 * 64, 2), (9, 24, 4 * 64 * 2, 2), (8, 20, 4 * 64, 3),
     (8, 19, 4 * 64, 3), (8, 24, 4 * 70, 2), (7, 24, 4 * 64, 2), (13, 128, 4 * 64, 1),
+    # matrix-core kernel over the flattened (group, column) numbering: short ragged rows
+    (12, 28, 784, 5), (8, 24, 4 * 50, 3), (20, 30, 4 * 70, 3), (32, 48, 4 * 10, 7), (17, 20, 4 * 1, 9),
     # residency caps: K = 1, 2, 4 run with many more waves per CU
     (1, 2, 4 * 64 * 40, 3), (2, 3, 4 * 64 * 33, 3), (4, 6, 4 * 64 * 21, 2),
 ])
