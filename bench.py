@@ -172,6 +172,25 @@ def other_workloads(torch, binding, syn, orc_nodes, dev, sign_mode):
                                        hbm_gbs=top1_bytes / (t["avg_ms"] * 1e6), note=COLD)
     del preds, out
 
+    # -- tiny workload: 64 groups, latency only ----------------------------------------------------
+    w = syn.WORKLOADS["tiny"]
+    alpha, beta = orc_nodes(w.K, w.W)
+    q = torch.from_numpy(syn.queries(w)).to(dev)
+    coded = torch.empty((w.G, w.W, w.D), dtype=torch.float32, device=dev)
+    t = time_launches(torch, lambda: binding.approxifer_encode(q, alpha, beta, coded=coded), 20, flush=flush)
+    res["tiny_encode"] = dict(t, coded_queries_per_s=w.G * w.W / (t["avg_ms"] * 1e-3),
+                              hbm_gbs=encode_bytes(w) / (t["avg_ms"] * 1e6), note=COLD)
+    Mt = torch.from_numpy(syn.model_params(w)["M"]).to(dev)
+    preds = torch.softmax(coded.double().reshape(-1, w.D) @ Mt, dim=1).float().reshape(w.G, w.W, w.C).contiguous()
+    mask = torch.from_numpy(syn.masks(w)).to(dev)
+    out = torch.empty((w.G, w.K, w.C), dtype=torch.float32, device=dev)
+    st = torch.empty((w.G,), dtype=torch.int32, device=dev)
+    t = time_launches(torch, lambda: binding.approxifer_decode(preds, mask, alpha, beta, w.S, sign_mode, out=out, status=st), 20,
+                      flush=flush)
+    res["tiny_decode"] = dict(t, predictions_per_s=w.G * w.K / (t["avg_ms"] * 1e-3),
+                              hbm_gbs=decode_bytes(w) / (t["avg_ms"] * 1e6), note=COLD)
+    del q, coded, preds, out
+
     # -- the paper's operating point: MNIST-sized queries, K = 8, S = 1, 10 classes -----------------
     w = syn.WORKLOADS["mnist_k8"]
     alpha, beta = orc_nodes(w.K, w.W)
@@ -220,7 +239,10 @@ def other_workloads(torch, binding, syn, orc_nodes, dev, sign_mode):
     w = syn.WORKLOADS["byzantine"]
     alpha, beta = orc_nodes(w.K, w.W)
     q = torch.from_numpy(syn.queries(w, threads=16)).to(dev)
-    coded = binding.approxifer_encode(q, alpha, beta)
+    coded = torch.empty((w.G, w.W, w.D), dtype=torch.float32, device=dev)
+    t = time_launches(torch, lambda: binding.approxifer_encode(q, alpha, beta, coded=coded), 20, flush=flush)
+    res["byzantine_encode"] = dict(t, coded_queries_per_s=w.G * w.W / (t["avg_ms"] * 1e-3),
+                                   hbm_gbs=encode_bytes(w) / (t["avg_ms"] * 1e6), note=COLD)
     M = torch.from_numpy(syn.model_params(w)["M"]).to(dev)
     clean = (coded.double().reshape(-1, w.D) @ M).float().reshape(w.G, w.W, w.C).cpu().numpy()
     mask_h = syn.masks(w)
