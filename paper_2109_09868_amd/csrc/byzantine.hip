@@ -24,10 +24,11 @@
 //    2M neighbouring lanes, lane j owns COLUMN j of the full n x (2M-1) system, which sits in LDS
 //    row-major; a Householder step walks down the pivot column (an LDS broadcast).
 //
-// Both finish the same way: Q by back substitution, a_r = Q(x_r) by Horner's rule, rank of |a_r| by
-// counting (equal magnitudes: smaller worker index first), votes in an LDS histogram, the A most
-// voted workers (equal counts: smaller index first) leave the available list, and the workgroup
-// decodes the group over the rest.
+// Both finish the same way: Q by back substitution, a_r = Q(x_r) by Horner's rule, the A smallest
+// |a_r| (equal magnitudes: smaller worker index first; by counting ranks in the general kernel, by A
+// rounds of a DPP arg-min in the projected one) vote in an LDS histogram, the A most voted workers
+// (equal counts: smaller index first) leave the available list, and the workgroup decodes the group
+// over the rest.
 #include "decode_common.h"
 
 namespace approxifer {
@@ -36,8 +37,7 @@ namespace {
 // ------------------------------------------------------------------------------------------------
 // shared tail: vote -> located adversaries -> F -> decode
 // ------------------------------------------------------------------------------------------------
-// Called by the whole workgroup after every vote has been added (and a barrier).  sel/F are LDS
-// scratch of N ints each; n <= 64.
+// Decoder contraction of one group over every column tile, predictions read from global memory.
 template <int VEC>
 __device__ __forceinline__ void contract_group(const float *__restrict__ pg, float *__restrict__ og, const int *F, int nF,
                                                int K, int KP, int64_t C, int64_t Cv, const double *WdT) {
