@@ -296,3 +296,27 @@ def locator_values_homogeneous(x, y, K, A):
     _, _, Vt = np.linalg.svd(H, full_matrices=True)
     coef = Vt[-1]
     return V @ coef[M:]
+
+
+# --------------------------------------------------------------------------
+# Algorithm 3 (P / Q reconstruction) -- not on the serving path, kept to show why
+# --------------------------------------------------------------------------
+def rational_reconstruction(x, y, K, A, z):
+    """Appendix A, Algorithm 3: with (P, Q) the least-squares solution of P(x_i) = y_i Q(x_i)
+    (degrees K+A-1, Q_0 = 1, the system of Algorithm 2), return r(z) = P(z) / Q(z).
+    Theorem 2 makes this exact for exactly rational data with at most A errors; the paper
+    sets it aside because the division is fragile under round-off (P and Q share the
+    error-locator factor, which nearly vanishes close to a corrupted node)."""
+    M = K + A
+    Amat, rhs = locator_system(x, y, K, A)
+    sol = np.linalg.lstsq(Amat, rhs, rcond=None)[0]
+    P = sol[:M]
+    Q = np.concatenate([[1.0], sol[M:]])
+    z = np.asarray(z, dtype=np.float64)
+    num = np.zeros_like(z)
+    den = np.zeros_like(z)
+    for k in range(M - 1, -1, -1):
+        num = num * z + P[k]
+        den = den * z + Q[k]
+    return num / den
+

@@ -243,3 +243,45 @@ def test_fewer_real_adversaries_are_still_located(real):
         adv, I, counts = orc.locate(Y, avail, beta, K, A)
         assert set(bad.tolist()) <= set(adv.tolist())
         assert len(set(adv.tolist())) == A and set(adv.tolist()) <= set(avail.tolist())
+
+
+def test_algorithm3_is_exact_in_float64_and_fragile_on_float32_data():
+    # Appendix A: r = P / Q reconstructs the rational function exactly (Theorem 2), and the paper's closing
+    # remark: the division is prone to round-off.  With a linear model the coded predictions are exactly
+    # rational in beta: from float64 data P/Q returns f(X_j) itself to ~1e-8; once the same data are rounded
+    # to float32 (1e-7 relative), single groups are off by more than 1e-2 while the typical one is at 1e-5.
+    # Locating and dropping the adversaries first, then Berrut, has no such tail: its error is the method's
+    # own approximation error, the same for both precisions.
+    K, A, S, N, C, G = 8, 2, 4, 24, 4, 50
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    results = {}
+    for single in (False, True):
+        rng = np.random.default_rng(82)
+        X = rng.uniform(0, 1, (G, K, 32))
+        Mf = rng.standard_normal((32, C)) / 4
+        truth = X @ Mf
+        clean = orc.encode(X, alpha, beta) @ Mf
+        e_div, e_ber = [], []
+        for g in range(G):
+            avail = np.sort(rng.permutation(N)[: N - S])
+            bad = np.sort(rng.permutation(avail)[:A])
+            Y = clean[g].copy()
+            Y[bad] += 10 * clean.std() * rng.standard_normal((A, C))
+            if single:
+                Y = Y.astype(np.float32).astype(np.float64)
+            r = np.stack([orc.rational_reconstruction(beta[avail], Y[avail, c], K, A, alpha) for c in range(C)], axis=1)
+            mask = np.zeros((1, N), np.uint8)
+            mask[0, avail] = 1
+            out, located, _ = orc.decode_byzantine(Y[None], mask, alpha, beta, S, A, 1)
+            assert np.array_equal(located[0], bad)
+            scale = np.abs(truth[g]).max()
+            e_div.append(np.abs(r - truth[g]).max() / scale)
+            e_ber.append(np.abs(out[0] - truth[g]).max() / scale)
+        results[single] = (np.array(e_div), np.array(e_ber))
+    exact, _ = results[False]
+    fragile, berrut32 = results[True]
+    _, berrut64 = results[False]
+    assert exact.max() < 1e-6
+    assert np.median(fragile) < 1e-4 and fragile.max() > 1e-2 and fragile.max() > 1e3 * np.median(fragile)
+    assert np.allclose(berrut32, berrut64, rtol=1e-3, atol=1e-6) and berrut32.max() < 1.0
+
