@@ -624,6 +624,42 @@ def test_byzantine_operating_points(gpu, E, sigma):
     assert group_err(out, ref).max() <= TOL
 
 
+@pytest.mark.timeout(900)
+def test_paper_operating_point_workloads_full_size(gpu):
+    # the two MNIST-shaped workloads the benchmark times, at full size and in its launch configuration:
+    # K = 8, one straggler (packed decoder, fused top-1) and K = 12, E = 2, 28 workers (projected Byzantine kernel)
+    torch, binding, dev = gpu
+    w = syn.WORKLOADS["mnist_k8"]
+    alpha, beta = orc.chebyshev_nodes(w.K, w.W)
+    X = syn.queries(w, threads=16)
+    coded = binding.approxifer_encode(torch.from_numpy(X).to(dev), alpha, beta).cpu().numpy()
+    worst = 0.0
+    for g0 in range(0, w.G, 2048):
+        worst = max(worst, group_err(coded[g0:g0 + 2048], orc.encode(X[g0:g0 + 2048], alpha, beta)).max())
+    assert worst <= TOL, worst
+    Y = syn.model_apply(w, syn.model_params(w), coded.astype(np.float64))
+    mask = syn.masks(w)
+    out, st, ref, st_ref = _decode_both(gpu, Y, mask, alpha, beta, w.S, 0)
+    assert np.all(st == 0) and np.array_equal(st, st_ref)
+    assert group_err(out, ref).max() <= TOL
+    top1, score, st1 = binding.approxifer_decode_top1(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev),
+                                                      alpha, beta, w.S, 0)
+    srt = np.sort(ref, axis=-1)
+    clear = (srt[..., -1] - srt[..., -2]) > 1e-9 * np.abs(ref).max(axis=-1)
+    assert clear.mean() > 0.99 and np.array_equal(top1.cpu().numpy()[clear], ref.argmax(-1)[clear])
+
+    wb = syn.WORKLOADS["mnist_byz_k12"]
+    alpha, beta, Yb, maskb, adv_true = _byzantine_inputs(wb)
+    outb, advb, stb = binding.approxifer_decode_byzantine(torch.from_numpy(Yb).to(dev), torch.from_numpy(maskb).to(dev),
+                                                          alpha, beta, wb.S, wb.A)
+    outb, advb, stb = outb.cpu().numpy(), advb.cpu().numpy(), stb.cpu().numpy()
+    assert np.all(stb == 0) and np.array_equal(advb, adv_true)          # every planted set, bit for bit
+    sample = np.arange(0, wb.G, 16)                                      # the oracle on every 16th group
+    refb, adv_ref, _ = orc.decode_byzantine(Yb[sample], maskb[sample], alpha, beta, wb.S, wb.A)
+    assert np.array_equal(advb[sample], adv_ref)
+    assert group_err(outb[sample], refb).max() <= TOL
+
+
 # --------------------------------------------------------------------------------------
 # per-group straggler counts (S = APPROXIFER_S_FROM_MASK): ragged masks
 # --------------------------------------------------------------------------------------
