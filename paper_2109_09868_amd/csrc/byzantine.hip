@@ -130,6 +130,29 @@ __device__ __forceinline__ double row_bcast(double v) {   // lane LANE of every 
     return __hiloint2double(hi, lo);
 }
 
+// Reciprocal and square root of a normal, positive-or-negative (rcp) / positive (sqrt) double to full
+// double precision: the hardware estimate refined by two Newton (Goldschmidt) steps and, for the root, one
+// residual correction.  No scaling for denormals or infinities and no final correctly-rounded fix-up, which
+// the factorisations here do not need: their operands are column norms and pivots, and a zero norm is
+// handled by the caller.
+__device__ __forceinline__ double rcp_normal(double x) {
+    double r = __builtin_amdgcn_rcp(x);
+    r = fma(fma(-x, r, 1.0), r, r);
+    r = fma(fma(-x, r, 1.0), r, r);
+    return r;
+}
+__device__ __forceinline__ double sqrt_normal(double s) {
+    const double y = __builtin_amdgcn_rsq(s);
+    double g = s * y, h = 0.5 * y;
+    double r = fma(-h, g, 0.5);
+    g = fma(g, r, g);
+    h = fma(h, r, h);
+    r = fma(-h, g, 0.5);
+    g = fma(g, r, g);
+    h = fma(h, r, h);
+    return fma(fma(-g, g, s), h, g);
+}
+
 // Householder reflector of a pivot column x (rows k..): returns alpha = -sign(x_k) ||x|| and the factor
 // f = 2 v^T a / (v^T v) for a column a, v = x - alpha e_k, given sigma = x^T x, d = x^T a.
 struct Reflector {
@@ -139,10 +162,10 @@ struct Reflector {
 __device__ __forceinline__ Reflector reflector(double sigma, double d, double xkk, double akj) {
     Reflector h;
     h.degenerate = !(sigma > 0.0);
-    const double nrm = sqrt(sigma);
+    const double nrm = sqrt_normal(sigma);
     h.alpha = (xkk >= 0.0) ? -nrm : nrm;
-    const double scale = 1.0 / (sigma - h.alpha * xkk);   // 2 / (v^T v)
-    h.f = scale * (d - h.alpha * akj);
+    const double scale = rcp_normal(fma(-h.alpha, xkk, sigma));   // 2 / (v^T v) = 1 / (sigma + |x_k| ||x||)
+    h.f = scale * fma(-h.alpha, akj, d);
     return h;
 }
 
@@ -237,7 +260,7 @@ struct BackSubst {
     // s enters as the transformed right-hand side and leaves as the solution: entry T is final once solved
     static __device__ __forceinline__ void run(const double (&a)[RM], double (&s)[NS], int cols) {
         if (T < cols) {
-            s[T] = s[T] / row_bcast<T>(a[T]);
+            s[T] = s[T] * rcp_normal(row_bcast<T>(a[T]));
 #pragma unroll
             for (int i = 0; i < T; ++i) s[i] = fma(-row_bcast<T>(a[i]), s[T], s[i]);
         } else {
@@ -284,8 +307,9 @@ __device__ __forceinline__ void locate_classes_proj(const float *Ysh, int CW, in
     const v2d *U2 = reinterpret_cast<const v2d *>(Ush);   // NB is even: row stride NB/2 pairs
     // rows past n contribute exact zeros (Ysh, Pw and the columns of Ush are zero there): no bound on r, so
     // inside a block of rows every load is independent of every other and is issued ahead of the arithmetic.
-    // Small tiles are one block; larger ones run in blocks of eight rows to bound the registers in flight.
-    constexpr int kRowBlock = NB <= 24 ? NB : 8;
+    // Tiles of up to 28 rows are one block; larger ones run in blocks of eight rows to bound the registers in flight.
+    constexpr int kRowBlock = NB <= 28 ? NB : 8;
+    static_assert(NB % 2 == 0 && NB % kRowBlock == 0, "row blocks must tile the rows");
 #pragma unroll 1
     for (int rb = 0; rb < NB; rb += kRowBlock) {
 #pragma unroll
@@ -352,7 +376,7 @@ __device__ __forceinline__ void locate_classes_proj(const float *Ysh, int CW, in
 // dynamic LDS (doubles): Ush[RM*NB] | Pw[NB*16] | xs[NB] | WdT[(n_cap-A)*KP] | alpha_s[K] | beta_s[N]
 //               then float Ysh[NB*CW], then ints: avail[N] | F[N] | Fpos[N] | votes[N] | sel[N] | n
 template <int NB, int RM>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 ? 3 : 2))) void decode_byzantine_proj_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 14 ? 4 : (RM <= 16 ? 3 : 2)))) void decode_byzantine_proj_kernel(
     const float *__restrict__ preds, const uint8_t *__restrict__ mask, float *__restrict__ out,
     int32_t *__restrict__ adv, int32_t *__restrict__ status, int K, int N, int S, int A, int64_t C, int64_t Cv,
     int vec4, int sign_mode, int n_cap, int cw_log2, const Nodes nodes) {
@@ -662,8 +686,11 @@ int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *
 #define APPROXIFER_PROJ(NB, RM)                                                                                        \
     if (n <= NB && n - M <= RM)                                                                                        \
         return run_proj<NB, RM>(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, S, A, C, n, vec4, nodes, sign_mode, stream);
+        APPROXIFER_PROJ(20, 10)       // n = 2M, the minimum of eq. (3), up to K + A = 10
         APPROXIFER_PROJ(20, 12)
+        APPROXIFER_PROJ(24, 12)       // n = 2M up to K + A = 12
         APPROXIFER_PROJ(24, 16)
+        APPROXIFER_PROJ(28, 14)       // n = 2M up to K + A = 14
         APPROXIFER_PROJ(32, 16)
         APPROXIFER_PROJ(32, 32)
         APPROXIFER_PROJ(48, 16)
