@@ -120,6 +120,10 @@ constexpr int kClsLanes = 16;      // lanes per class (one DPP row)
 constexpr int kClsPerWave = 4;
 constexpr int kPwStride = 16;      // powers table row: x^0 .. x^15
 constexpr int kProjMaxM = 16;      // M - 1 <= 15 unknown columns in lanes 0..14, right-hand side in lane 15
+// U in LDS: rows padded to a multiple of four (the matrix-core tiles below take four rows of U at a time), row
+// stride chosen so that the sixteen (row, column) pairs one operand load touches fall in distinct banks.
+constexpr int ush_rows(int RM) { return (RM + 3) & ~3; }
+constexpr int ush_stride(int NB) { return NB % 16 == 0 ? NB + 4 : NB; }
 
 template <int LANE>
 __device__ __forceinline__ double row_bcast(double v) {   // lane LANE of every 16-lane row, to the whole row
@@ -197,7 +201,7 @@ struct SharedQrSteps<kProjMaxM, NB> {
     static __device__ __forceinline__ void run(double (&)[NB], int, int) {}
 };
 
-// Pw[r][e] = x_r^e (LDS), n rows, M <= 16 columns.  Writes Ush[i][r] = U[i][r], i < RM, row stride NB.
+// Pw[r][e] = x_r^e (LDS), n rows, M <= 16 columns.  Writes Ush[i][r] = U[i][r], i < RM, row stride ush_stride(NB).
 template <int NB, int RM>
 __device__ __forceinline__ void shared_complement_basis(const double *Pw, int n, int M, double *Ush) {
     const int lane = lane_id();
@@ -215,7 +219,7 @@ __device__ __forceinline__ void shared_complement_basis(const double *Pw, int n,
 #pragma unroll
         for (int row = 2; row < NB; ++row) {        // M >= 2 always
             const int i = row - M;
-            if (i >= 0 && i < RM) Ush[i * NB + r_out] = col[row];
+            if (i >= 0 && i < RM) Ush[i * ush_stride(NB) + r_out] = col[row];
         }
     }
 }
@@ -286,43 +290,59 @@ __device__ __forceinline__ void row_min_step(double &v, int &i) {
 
 // Algorithm 2, steps 1-5, for the four classes c_rel..c_rel+3 of the staged class tile, by one wave.
 //   Ysh[NB][CW] float: predictions of the available workers, row r = r-th available worker, zero past n and
-//   past the last class;  Ush[RM][NB], Pw[NB][16] (rows past n zero), xs[n]: the group's LDS.
+//   past the last class;  Ush[ush_rows(RM)][ush_stride(NB)] (zero past row n-M and column n), Pw[NB][16] (rows past n
+//   zero), xs[n]: the group's LDS.
 template <int NB, int RM>
 __device__ __forceinline__ void locate_classes_proj(const float *Ysh, int CW, int c_rel, bool live, const int *avail,
                                                     const double *xs, const double *Pw, const double *Ush, int n,
                                                     int M, int A, int *votes) {
-    typedef double v2d __attribute__((ext_vector_type(2)));
+    typedef double v4d __attribute__((ext_vector_type(4)));
     const int lane = lane_id();
     const int cl = lane / kClsLanes;
     const int j = lane % kClsLanes;
     const int cols = M - 1;                               // unknowns Q_1 .. Q_{M-1}
-    const float *ysc = Ysh + c_rel + cl;                  // this class's column of the tile
 
     // column of this lane: -y x^(j+1) for the unknown Q_(j+1), y for the right-hand side, 0 on idle lanes
     const int e = j < cols ? j + 1 : 0;
     const double sgn = j < cols ? -1.0 : (j == kClsLanes - 1 ? 1.0 : 0.0);
-    double a[RM];
+
+    // ---- the projected systems of the four classes, B_c = U diag(y_c) [x^e], on the float64 matrix cores -------
+    // v_mfma_f64_16x16x4_f64 computes D[16x16] += A[16x4] * B[4x16]; lane l holds A[l%16][l/16], B[l/16][l%16] and, in
+    // register t of D, D[4t + l/16][l%16].  With
+    //     A[4t + c][k] = U[4b + t][r] * y_{r, class c}      B[k][j] = sgn_j * x_r^{e_j}      (r = 4s + k)
+    // summed over the k-steps s, register t of lane (c, j) receives B_c[4b + t][j]: exactly the layout the
+    // factorisation below wants (lane = class and column, rows in registers), with no lane exchange at all.
+    // Rows past n of Ysh and Pw and columns past n of Ush are zero, so the k-steps need no bound.
+    constexpr int kKSteps = NB / 4;
+    constexpr int kRowBlocks = ush_rows(RM) / 4;
+    static_assert(NB % 4 == 0, "k-steps take four available workers at a time");
+    double bop[kKSteps], yop[kKSteps];
+    {
+        const int k = lane / kClsLanes, cm = (lane % kClsLanes) & 3;
 #pragma unroll
-    for (int i = 0; i < RM; ++i) a[i] = 0.0;
-    const v2d *U2 = reinterpret_cast<const v2d *>(Ush);   // NB is even: row stride NB/2 pairs
-    // rows past n contribute exact zeros (Ysh, Pw and the columns of Ush are zero there): no bound on r, so
-    // inside a block of rows every load is independent of every other and is issued ahead of the arithmetic.
-    // Tiles of up to 28 rows are one block; larger ones run in blocks of eight rows to bound the registers in flight.
-    constexpr int kRowBlock = NB <= 28 ? NB : 8;
-    static_assert(NB % 2 == 0 && NB % kRowBlock == 0, "row blocks must tile the rows");
-#pragma unroll 1
-    for (int rb = 0; rb < NB; rb += kRowBlock) {
-#pragma unroll
-        for (int r = rb; r < rb + kRowBlock; r += 2) {
-            const double c0v = sgn * static_cast<double>(ysc[r * CW]) * Pw[r * kPwStride + e];
-            const double c1v = sgn * static_cast<double>(ysc[(r + 1) * CW]) * Pw[(r + 1) * kPwStride + e];
-#pragma unroll
-            for (int i = 0; i < RM; ++i) {
-                const v2d u = U2[(i * NB + r) >> 1];
-                a[i] = fma(u.x, c0v, a[i]);
-                a[i] = fma(u.y, c1v, a[i]);
-            }
+        for (int s = 0; s < kKSteps; ++s) {
+            const int r = 4 * s + k;
+            bop[s] = sgn * Pw[r * kPwStride + e];
+            yop[s] = static_cast<double>(Ysh[r * CW + c_rel + cm]);
         }
+    }
+    double a[RM];
+    {
+        const double *urow = Ush + ((lane % kClsLanes) >> 2) * ush_stride(NB) + lane / kClsLanes;
+        v4d acc[kRowBlocks];
+#pragma unroll
+        for (int b = 0; b < kRowBlocks; ++b) acc[b] = v4d{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int s = 0; s < kKSteps; ++s)                 // the row blocks are independent accumulation chains
+#pragma unroll
+            for (int b = 0; b < kRowBlocks; ++b)
+                acc[b] = __builtin_amdgcn_mfma_f64_16x16x4f64(urow[4 * b * ush_stride(NB) + 4 * s] * yop[s], bop[s], acc[b],
+                                                              0, 0, 0);
+#pragma unroll
+        for (int b = 0; b < kRowBlocks; ++b)
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (4 * b + t < RM) a[4 * b + t] = acc[b][t];
     }
 
     constexpr int kSteps = RM - 1 < kProjMaxM - 1 ? RM - 1 : kProjMaxM - 1;   // most unknowns this tile can hold
@@ -373,10 +393,10 @@ __device__ __forceinline__ void locate_classes_proj(const float *Ysh, int CW, in
     }
 }
 
-// dynamic LDS (doubles): Ush[RM*NB] | Pw[NB*16] | xs[NB] | WdT[(n_cap-A)*KP] | alpha_s[K] | beta_s[N]
+// dynamic LDS (doubles): Ush[ush_rows(RM)*ush_stride(NB)] | Pw[NB*16] | xs[NB] | WdT[(n_cap-A)*KP] | alpha_s[K] | beta_s[N]
 //               then float Ysh[NB*CW], then ints: avail[N] | F[N] | Fpos[N] | votes[N] | sel[N] | n
 template <int NB, int RM>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 14 ? 4 : (RM <= 16 ? 3 : 2)))) void decode_byzantine_proj_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 && NB <= 32 ? 3 : 2))) void decode_byzantine_proj_kernel(
     const float *__restrict__ preds, const uint8_t *__restrict__ mask, float *__restrict__ out,
     int32_t *__restrict__ adv, int32_t *__restrict__ status, int K, int N, int S, int A, int64_t C, int64_t Cv,
     int vec4, int sign_mode, int n_cap, int cw_log2, const Nodes nodes) {
@@ -386,7 +406,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 14 ? 
     const int nw = blockDim.x / kWave;
     const int CW = 1 << cw_log2;                          // classes per staged tile (16, 32 or 64)
     double *Ush = lds_d;
-    double *Pw = Ush + RM * NB;
+    constexpr int kUshDoubles = ush_rows(RM) * ush_stride(NB);
+    double *Pw = Ush + kUshDoubles;
     double *xs = Pw + NB * kPwStride;
     double *WdT = xs + NB;
     double *alpha_s = WdT + (n_cap - A) * KP;
@@ -406,7 +427,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 14 ? 
 
     stage_nodes(nodes, K, N, alpha_s, beta_s);
     for (int e = tid; e < (n_cap - A) * KP; e += blockDim.x) WdT[e] = 0.0;
-    for (int e = tid; e < RM * NB; e += blockDim.x) Ush[e] = 0.0;
+    for (int e = tid; e < kUshDoubles; e += blockDim.x) Ush[e] = 0.0;
     for (int e = tid; e < N; e += blockDim.x) votes[e] = 0;
     if (wv == 0) {
         const int cnt = survivors_from_mask(mask + g * N, N, avail);
@@ -658,7 +679,7 @@ int run_proj(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t 
     if (nw > 4) nw = 4;
     const int64_t fill = (4096 + G - 1) / G;
     if (nw > fill) nw = static_cast<int>(fill);
-    const size_t lds = sizeof(double) * (static_cast<size_t>(RM) * NB + NB * kPwStride + NB +
+    const size_t lds = sizeof(double) * (static_cast<size_t>(ush_rows(RM)) * ush_stride(NB) + NB * kPwStride + NB +
                                          static_cast<size_t>(n_cap - A) * KP + K + N) +
                        sizeof(float) * (static_cast<size_t>(NB) * CW) + sizeof(int) * (5 * static_cast<size_t>(N) + 2);
     if (lds > 64 * 1024) return APPROXIFER_ERR_LIMIT;      // cannot happen inside the projected kernel's domain
