@@ -16,7 +16,8 @@
 //    LDS.  Eliminating p exactly, class c only has to solve the (n-M) x (M-1) problem
 //        min_q || U C_c q - U y_c ||,
 //    so a class needs 16 lanes (lane = column, 15 = right-hand side), four classes share a wave, the
-//    projected system is formed with U broadcast from LDS, and its Householder QR runs entirely in
+//    four projected systems are formed by the float64 matrix cores (operands read from LDS, result
+//    directly in the lane layout of the factorisation), and the Householder QR runs entirely in
 //    registers: the pivot column reaches the other lanes of the class through DPP row broadcasts.
 //    No LDS traffic and no barrier inside either factorisation.
 //
