@@ -188,11 +188,12 @@ struct SharedQrSteps {
             }
             const double xkk = read_lane(col[K0], K0);
             const Reflector h = reflector(sg[0] + sg[1], dt[0] + dt[1], xkk, col[K0]);
-            if (!h.degenerate && lane > K0) {
-                col[K0] = fma(-h.f, xkk - h.alpha, col[K0]);
+            // no branch: columns up to the pivot (and every column of a degenerate step) take the factor 0, so the
+            // pivot values read for the dot products serve the update as well
+            const double nf = (!h.degenerate && lane > K0) ? -h.f : 0.0;
+            col[K0] = fma(nf, xkk - h.alpha, col[K0]);
 #pragma unroll
-                for (int r = K0 + 1; r < NB; ++r) col[r] = fma(-h.f, read_lane(col[r], K0), col[r]);
-            }
+            for (int r = K0 + 1; r < NB; ++r) col[r] = fma(nf, read_lane(col[r], K0), col[r]);
             SharedQrSteps<K0 + 1, NB>::run(col, lane, M);
         }
     }
@@ -240,15 +241,11 @@ struct ClassQrSteps {
                 dt[(r - K0) & 1] = fma(v[r], a[r], dt[(r - K0) & 1]);
             }
             const Reflector h = reflector(sg[0] + sg[1], dt[0] + dt[1], v[K0], a[K0]);
-            if (!h.degenerate) {
-                if (j > K0) {
-                    a[K0] = fma(-h.f, v[K0] - h.alpha, a[K0]);
+            const double nf = (!h.degenerate && j > K0) ? -h.f : 0.0;       // no branch: other columns take the factor 0
+            const double akk = fma(nf, v[K0] - h.alpha, a[K0]);
+            a[K0] = (!h.degenerate && j == K0) ? h.alpha : akk;           // R[k][k] in the pivot lane
 #pragma unroll
-                    for (int r = K0 + 1; r < RM; ++r) a[r] = fma(-h.f, v[r], a[r]);
-                } else if (j == K0) {
-                    a[K0] = h.alpha;                // R[k][k]
-                }
-            }
+            for (int r = K0 + 1; r < RM; ++r) a[r] = fma(nf, v[r], a[r]);
             ClassQrSteps<K0 + 1, KEND, RM>::run(a, j, cols);
         }
     }
