@@ -179,15 +179,13 @@ template <int K0, int NB>
 struct SharedQrSteps {
     static __device__ __forceinline__ void run(double (&col)[NB], int lane, int M) {
         if (K0 < M) {
-            double sg[2] = {0.0, 0.0}, dt[2] = {0.0, 0.0};   // two partial sums each: shorter dependency chains
+            double dt[2] = {0.0, 0.0};                       // two partial sums: shorter dependency chains
 #pragma unroll
-            for (int r = K0; r < NB; ++r) {
-                const double vr = read_lane(col[r], K0);
-                sg[(r - K0) & 1] = fma(vr, vr, sg[(r - K0) & 1]);
-                dt[(r - K0) & 1] = fma(vr, col[r], dt[(r - K0) & 1]);
-            }
+            for (int r = K0; r < NB; ++r) dt[(r - K0) & 1] = fma(read_lane(col[r], K0), col[r], dt[(r - K0) & 1]);
+            const double d = dt[0] + dt[1];                  // x^T a for this lane's column a ..
+            const double sigma = read_lane(d, K0);           // .. which in the pivot lane is x^T x
             const double xkk = read_lane(col[K0], K0);
-            const Reflector h = reflector(sg[0] + sg[1], dt[0] + dt[1], xkk, col[K0]);
+            const Reflector h = reflector(sigma, d, xkk, col[K0]);
             // no branch: columns up to the pivot (and every column of a degenerate step) take the factor 0, so the
             // pivot values read for the dot products serve the update as well
             const double nf = (!h.degenerate && lane > K0) ? -h.f : 0.0;
@@ -233,14 +231,15 @@ struct ClassQrSteps {
     static __device__ __forceinline__ void run(double (&a)[RM], int j, int cols) {
         if (K0 < cols) {
             double v[RM];
-            double sg[2] = {0.0, 0.0}, dt[2] = {0.0, 0.0};   // two partial sums each: shorter dependency chains
+            double dt[2] = {0.0, 0.0};                       // two partial sums: shorter dependency chains
 #pragma unroll
             for (int r = K0; r < RM; ++r) {
                 v[r] = row_bcast<K0>(a[r]);
-                sg[(r - K0) & 1] = fma(v[r], v[r], sg[(r - K0) & 1]);
                 dt[(r - K0) & 1] = fma(v[r], a[r], dt[(r - K0) & 1]);
             }
-            const Reflector h = reflector(sg[0] + sg[1], dt[0] + dt[1], v[K0], a[K0]);
+            const double d = dt[0] + dt[1];                  // x^T a for this lane's column a ..
+            const double sigma = row_bcast<K0>(d);           // .. which in the pivot lane is x^T x
+            const Reflector h = reflector(sigma, d, v[K0], a[K0]);
             const double nf = (!h.degenerate && j > K0) ? -h.f : 0.0;       // no branch: other columns take the factor 0
             const double akk = fma(nf, v[K0] - h.alpha, a[K0]);
             a[K0] = (!h.degenerate && j == K0) ? h.alpha : akk;           // R[k][k] in the pivot lane
