@@ -946,3 +946,66 @@ def test_random_shapes_all_entry_points(gpu):
         assert np.all(same[decisive])
         if same.any():
             assert group_err(outb.cpu().numpy()[same], refb[same]).max() <= TOL
+
+
+def test_random_byzantine_shapes(gpu):
+    # every register tile of the projected kernel and the general kernel behind it: K + A up to 16, up to 64
+    # available workers, odd and even counts, per-group counts, one to a few hundred classes; exactly rational
+    # data (linear model), so the planted adversaries must come back wherever float32 data still separate them
+    import os
+    torch, binding, dev = gpu
+    rng = np.random.default_rng(int(os.environ.get("APPROXIFER_FUZZ_SEED", "909868")))
+    for trial in range(int(os.environ.get("APPROXIFER_FUZZ_TRIALS", "40"))):
+        K = int(rng.integers(1, 15))
+        A = int(rng.integers(1, 4))
+        if K + A > 16:
+            K = 16 - A
+        M = K + A
+        S = int(rng.integers(0, 5))
+        extra = int(rng.choice([0, 0, 0, 1, 2, 5, 11, 30]))
+        n = min(2 * M + extra, 64)
+        N = n + S
+        if N % 2 == 1:                                       # keep the zero node out (Q(0) = 1)
+            N += 1
+            S += 1
+        C = int(rng.choice([1, 2, 3, 4, 7, 10, 16, 17, 40, 65, 130]))
+        G = int(rng.integers(1, 7))
+        ragged = bool(rng.integers(0, 2)) and N > 2 * M
+        mode = int(rng.integers(0, 2))
+        print("trial", trial, dict(K=K, A=A, S=S, N=N, C=C, G=G, ragged=ragged, mode=mode), flush=True)
+        alpha, beta = orc.chebyshev_nodes(K, N)
+        X = rng.uniform(0, 1, (G, K, 48))
+        Mf = rng.standard_normal((48, C)) / 7
+        clean = (orc.encode(X, alpha, beta) @ Mf).astype(np.float32)
+        mask = np.zeros((G, N), np.uint8)
+        Y = clean.copy()
+        adv_true = np.zeros((G, A), np.int32)
+        for g in range(G):
+            cnt = int(rng.integers(2 * M, min(N, 64) + 1)) if ragged else N - S
+            avail = np.sort(rng.permutation(N)[:cnt])
+            mask[g, avail] = 1
+            adv_true[g] = np.sort(rng.permutation(avail)[:A])
+            Y[g, adv_true[g]] += (10 * (clean.std() + 1e-3) * rng.standard_normal((A, C))).astype(np.float32)
+        S_arg = binding.S_FROM_MASK if ragged else S
+        out, adv, st = binding.approxifer_decode_byzantine(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev),
+                                                           alpha, beta, S_arg, A, mode)
+        ref, adv_ref, st_ref = orc.decode_byzantine(Y, mask, alpha, beta, None if ragged else S, A, mode)
+        out, adv, st = out.cpu().numpy(), adv.cpu().numpy(), st.cpu().numpy()
+        assert np.array_equal(st, st_ref) and np.all(st == 0)
+        same = np.all(adv == adv_ref, axis=1)
+        decisive = np.zeros(G, bool)
+        for g in range(G):
+            _, _, counts = orc.locate(Y[g], np.nonzero(mask[g])[0], beta, K, A)
+            top = np.sort(counts)[::-1]
+            decisive[g] = top[A - 1] - top[A] >= 2
+        assert np.all(same[decisive]), (adv, adv_ref)
+        if M <= 12 and C >= 7:
+            assert np.array_equal(adv[decisive], adv_true[decisive])
+        for g in range(G):                                   # decode parity over the kernel's own survivor set
+            m2 = mask[g:g + 1].copy()
+            m2[0, adv[g]] = 0
+            if not well_posed(alpha, beta, m2, mode)[0]:
+                continue
+            ref_g, _ = orc.decode(Y[g:g + 1], m2, alpha, beta, None, mode)
+            assert group_err(out[g:g + 1], ref_g).max() <= TOL
+
