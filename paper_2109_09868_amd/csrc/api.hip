@@ -36,7 +36,7 @@ int check_common(int K, int N, const double *h_alpha, const double *h_beta, Node
 
 extern "C" {
 
-int approxifer_version(void) { return 100; }
+int approxifer_version(void) { return 200; }   // 0.2.0: approxifer_wait_mask, APPROXIFER_S_FROM_MASK
 
 const char *approxifer_strerror(int code) {
     switch (code) {
