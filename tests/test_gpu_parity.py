@@ -581,6 +581,42 @@ def test_byzantine_fewer_real_adversaries_than_A(gpu, real):
         assert group_err(out[g:g + 1], ref_g).max() <= TOL
 
 
+@pytest.mark.parametrize("K,A,S,N,C", [(8, 2, 4, 24, 10), (12, 2, 0, 28, 10), (3, 1, 0, 64, 5), (18, 2, 0, 44, 3)])
+def test_byzantine_degenerate_predictions(gpu, K, A, S, N, C):
+    # rank-deficient fits: all-zero predictions, the same constant everywhere, identical classes, one available
+    # worker holding NaN.  No located set is "right" here; what must hold: every group is decoded, the located
+    # workers are distinct available workers in ascending order, and -- the weights sum to one -- constants
+    # decode to themselves whoever was dropped
+    torch, binding, dev = gpu
+    G = 6
+    rng = np.random.default_rng(K + N)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    mask = np.zeros((G, N), np.uint8)
+    for g in range(G):
+        mask[g, rng.permutation(N)[: N - S]] = 1
+    Y = np.zeros((G, N, C), np.float32)
+    Y[1] = 2.5                                                  # constant
+    Y[2] = rng.standard_normal((N, 1)).astype(np.float32)      # every class the same column
+    Y[3] = 1e30                                                 # huge constant
+    Y[4] = rng.standard_normal((N, C)).astype(np.float32)
+    Y[4, np.nonzero(mask[4])[0][3]] = np.nan                    # a worker that returns NaN
+    Y[5] = rng.standard_normal((N, C)).astype(np.float32) * 1e-30
+    out, adv, st = binding.approxifer_decode_byzantine(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev),
+                                                       alpha, beta, S, A, 1)
+    out, adv, st = out.cpu().numpy(), adv.cpu().numpy(), st.cpu().numpy()
+    assert np.all(st == 0)
+    for g in range(G):
+        assert np.all(np.diff(adv[g]) > 0) and np.all(mask[g, adv[g]] == 1)
+    assert np.all(out[0] == 0.0)
+    assert np.max(np.abs(out[1] - 2.5)) <= 2.5e-5
+    assert np.max(np.abs(out[3] / 1e30 - 1.0)) <= 1e-5
+    for g in (2, 5):                                            # finite inputs: decode parity over the kernel's survivors
+        m2 = mask[g:g + 1].copy()
+        m2[0, adv[g]] = 0
+        ref_g, _ = orc.decode(Y[g:g + 1], m2, alpha, beta, None, 1)
+        assert group_err(out[g:g + 1], ref_g).max() <= TOL
+
+
 # --------------------------------------------------------------------------------------
 # the paper's own operating points (Section 4.2; Appendix B), on synthetic stand-in data
 # --------------------------------------------------------------------------------------
