@@ -34,6 +34,9 @@ import numpy as np
 SIGN_WORKER_INDEX = 0   # (-1)^i with i the worker index, as the decoder formula is printed
 SIGN_SURVIVOR_RANK = 1  # (-1)^r with r the position of the node among the surviving nodes
 
+LOCATOR_ALGORITHM_2 = 2  # Q_0 = 1, least squares: the locator of Section 4.1
+LOCATOR_ALGORITHM_1 = 1  # Q_0 free, null vector of the homogeneous system (Section 2)
+
 
 # --------------------------------------------------------------------------
 # nodes
@@ -241,9 +244,11 @@ def vote(I, W, A):
     return np.sort(order[:A]).astype(np.int32), counts
 
 
-def locate(Yg, avail, beta, K, A):
-    """Algorithm 2 for one group.  Yg is [W, C]; avail lists the available workers
-    in ascending order.  Returns (adv [A] int32 ascending, I [C, A], counts [W])."""
+def locate(Yg, avail, beta, K, A, locator=LOCATOR_ALGORITHM_2):
+    """Adversary location for one group: Algorithm 2 (or, with locator = LOCATOR_ALGORITHM_1,
+    the homogeneous fit of Algorithm 1 applied class by class, with the same picks and vote).
+    Yg is [W, C]; avail lists the available workers in ascending order.
+    Returns (adv [A] int32 ascending, I [C, A], counts [W])."""
     Yg = np.asarray(Yg)
     avail = np.asarray(avail, dtype=np.int64)
     beta = np.asarray(beta, dtype=np.float64)
@@ -251,15 +256,20 @@ def locate(Yg, avail, beta, K, A):
     x = beta[avail]
     I = np.zeros((C, A), dtype=np.int64)
     for c in range(C):
-        a = locator_values(x, Yg[avail, c].astype(np.float64), K, A)
+        y = Yg[avail, c].astype(np.float64)
+        if locator == LOCATOR_ALGORITHM_1:
+            a = locator_values_homogeneous(x, y, K, A)
+        else:
+            a = locator_values(x, y, K, A)
         I[c, :] = pick_smallest(a, avail, A)
     adv, counts = vote(I, W, A)
     return adv, I, counts
 
 
-def decode_byzantine(Y, mask, alpha, beta, S, A, sign_mode=SIGN_WORKER_INDEX):
-    """Locate the adversaries among the available workers (Algorithm 2), drop them,
-    decode over the rest (Section 4.1, "Encoding and Decoding").
+def decode_byzantine(Y, mask, alpha, beta, S, A, sign_mode=SIGN_WORKER_INDEX, locator=LOCATOR_ALGORITHM_2):
+    """Locate the adversaries among the available workers (Algorithm 2; Algorithm 1's fit
+    per class with locator = LOCATOR_ALGORITHM_1), drop them, decode over the rest
+    (Section 4.1, "Encoding and Decoding").
     Returns (out [G, K, C] float64, adv [G, A] int32, status [G])."""
     Y = np.asarray(Y)
     mask = np.asarray(mask)
@@ -273,7 +283,7 @@ def decode_byzantine(Y, mask, alpha, beta, S, A, sign_mode=SIGN_WORKER_INDEX):
         if (avail.size != W - S) if (S is not None and S >= 0) else (avail.size < 2 * (K + A)):
             status[g] = 1                                 # S None/negative: per-group count, Section 3 eq. (3) must hold
             continue
-        adv[g], _, _ = locate(Y[g], avail, beta, K, A)
+        adv[g], _, _ = locate(Y[g], avail, beta, K, A, locator)
         F = np.setdiff1d(avail, adv[g])
         Wd = decode_weights(alpha, beta, F, sign_mode)
         out[g] = Wd @ Y[g, F, :].astype(np.float64)
@@ -281,7 +291,7 @@ def decode_byzantine(Y, mask, alpha, beta, S, A, sign_mode=SIGN_WORKER_INDEX):
 
 
 # --------------------------------------------------------------------------
-# Algorithm 1 (homogeneous form) -- used only to cross-check Algorithm 2
+# Algorithm 1 (homogeneous form) -- cross-checks Algorithm 2; the alternate locator
 # --------------------------------------------------------------------------
 def locator_values_homogeneous(x, y, K, A):
     """Algorithm 1: P and Q both of degree K+A-1 with Q_0 free; the coefficient

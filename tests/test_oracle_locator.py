@@ -93,6 +93,8 @@ def test_locator_agrees_with_brute_force_subset_search(K, A, W):
         assert smin < 1e-10 and set(sub) == set(bad)
         a = orc.locator_values(x, y, K, A)
         assert set(np.argsort(np.abs(a))[:A]) == set(sub)
+        a1 = orc.locator_values_homogeneous(x, y, K, A)
+        assert set(np.argsort(np.abs(a1))[:A]) == set(sub)
 
 
 def test_zero_node_cannot_be_located_with_q0_fixed():
@@ -184,6 +186,48 @@ def test_locate_and_decode_byzantine_on_linear_model_groups():
     truth = syn.model_apply(w, params, X)
     out_dirty, _ = orc.decode(Y, mask, alpha, beta, w.S)
     assert np.median(np.abs(out - truth)) < 0.25 * np.median(np.abs(out_dirty - truth))
+
+
+def test_algorithm1_as_the_group_locator_on_linear_model_groups():
+    # the same groups through Algorithm 1's homogeneous fit (per class, same picks and vote): on
+    # exactly rational data its null vector is the error locator times q (Appendix A), so it finds
+    # the same workers and the decoded group is the same
+    w = syn.scaled(syn.WORKLOADS["byzantine"], G=24)
+    alpha, beta = orc.chebyshev_nodes(w.K, w.W)
+    clean = syn.model_apply(w, syn.model_params(w), orc.encode(syn.queries(w), alpha, beta))
+    mask = syn.masks(w)
+    adv_true = syn.adversaries(w, mask)
+    Y = syn.corrupt(w, clean, adv_true)
+    out1, adv1, st1 = orc.decode_byzantine(Y, mask, alpha, beta, w.S, w.A, locator=orc.LOCATOR_ALGORITHM_1)
+    out2, adv2, st2 = orc.decode_byzantine(Y, mask, alpha, beta, w.S, w.A)
+    assert np.all(st1 == 0) and np.array_equal(adv1, adv_true) and np.array_equal(adv2, adv_true)
+    assert np.array_equal(out1, out2)
+    # and per class: every class's picks are the planted workers
+    for g in range(4):
+        avail = np.nonzero(mask[g])[0]
+        _, I, counts = orc.locate(Y[g], avail, beta, w.K, w.A, orc.LOCATOR_ALGORITHM_1)
+        assert np.array_equal(np.sort(I, axis=1), np.tile(adv_true[g], (Y.shape[2], 1)))
+        assert counts.sum() == Y.shape[2] * w.A
+
+
+def test_algorithm1_is_invariant_to_scaling_predictions_and_coefficients():
+    # a null vector is defined up to a factor: a_i = Q(x_i) may come back with either sign and any
+    # length, the order of the |a_i| may not change; scaling the predictions rescales P only
+    rng = np.random.default_rng(8)
+    K, A, W = 3, 2, 12
+    _, beta = orc.chebyshev_nodes(K, W)
+    x = beta[np.sort(rng.permutation(W)[: 2 * (K + A)])]
+    y = _rational_samples(rng, K, x)
+    y[[1, 6]] += [3.0, -2.0]
+    a = orc.locator_values_homogeneous(x, y, K, A)
+    b = orc.locator_values_homogeneous(x, 64.0 * y, K, A)
+    assert set(np.argsort(np.abs(a))[:A]) == set(np.argsort(np.abs(b))[:A]) == {1, 6}
+    good = np.setdiff1d(np.arange(x.size), [1, 6])
+    r = a[good] / b[good]
+    assert np.allclose(r, r[0], rtol=1e-6)
+    # the fit itself: P(x_i) - y_i Q(x_i) = 0 off the adversaries means Q(x_i) (y_i - r(x_i)) = 0, so on
+    # the adversaries, where y_i != r(x_i), Q vanishes: |a| there is at rounding level of the rest
+    assert np.max(np.abs(a[[1, 6]])) < 1e-8 * np.min(np.abs(a[good]))
 
 
 def test_decode_byzantine_status():

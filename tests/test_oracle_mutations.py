@@ -159,6 +159,33 @@ def _values_without_q0(x, y, K, A):
     return _ORIG["locator_values"](x, y, K, A) - 1.0
 
 
+def _homogeneous_largest_singular_vector(x, y, K, A):
+    x = np.asarray(x, dtype=np.float64)
+    y = np.asarray(y, dtype=np.float64)
+    M = K + A
+    V = np.vander(x, M, increasing=True)
+    H = np.concatenate([V, -y[:, None] * V], axis=1)
+    return V @ np.linalg.svd(H)[2][0][M:]
+
+
+def _homogeneous_reads_p_half(x, y, K, A):
+    x = np.asarray(x, dtype=np.float64)
+    y = np.asarray(y, dtype=np.float64)
+    M = K + A
+    V = np.vander(x, M, increasing=True)
+    H = np.concatenate([V, -y[:, None] * V], axis=1)
+    return V @ np.linalg.svd(H)[2][-1][:M]
+
+
+def _homogeneous_q_one_degree_short(x, y, K, A):
+    x = np.asarray(x, dtype=np.float64)
+    y = np.asarray(y, dtype=np.float64)
+    M = K + A
+    V = np.vander(x, M, increasing=True)
+    H = np.concatenate([V, -y[:, None] * V[:, : M - 1]], axis=1)
+    return V[:, : M - 1] @ np.linalg.svd(H)[2][-1][M:]
+
+
 def _pick_largest(a, avail, A):
     order = np.argsort(-np.abs(a), kind="stable")
     return np.asarray(avail, dtype=np.int64)[order[:A]]
@@ -216,6 +243,9 @@ MUTATIONS = {
     "locator Q starting at x^0": ("locator_system", _system_q_starts_at_x0),
     "locator P one degree short": ("locator_system", _system_p_one_degree_short),
     "locator values without Q_0 = 1": ("locator_values", _values_without_q0),
+    "Algorithm 1 with the largest singular vector": ("locator_values_homogeneous", _homogeneous_largest_singular_vector),
+    "Algorithm 1 reading Q from the P half": ("locator_values_homogeneous", _homogeneous_reads_p_half),
+    "Algorithm 1 with Q one degree short": ("locator_values_homogeneous", _homogeneous_q_one_degree_short),
     "picks the largest |a|": ("pick_smallest", _pick_largest),
     "picks returned as positions, not worker indices": ("pick_smallest", _pick_positions_not_workers),
     "vote keeps the least frequent": ("vote", _vote_least_frequent),
