@@ -142,6 +142,25 @@ int approxifer_decode_byzantine(const float *d_preds, const uint8_t *d_mask, flo
                                 const double *h_alpha, const double *h_beta, int sign_mode, void *stream);
 
 /*
+ * Byzantine decoder with the locator of Section 2, Algorithm 1, in place of Algorithm 2: the
+ * same call, the same picks, vote and decode, but per class the fit leaves Q_0 free.  With
+ * M = K + A, P and Q both of degree M-1, the coefficient vector (P_0..P_{M-1}, Q_0..Q_{M-1})
+ * is the unit vector minimising sum_i (P(x_i) - y_i Q(x_i))^2 over the available workers: the
+ * right singular vector of the smallest singular value of the n x 2M matrix of the
+ * homogeneous system (float64 Householder QR, then one-sided Jacobi rotations on the
+ * triangular factor until every pair of columns is orthogonal to rounding).  a_i = Q(x_i) is
+ * defined up to one factor, which the order of the |a_i| does not see.  Unlike Algorithm 2
+ * this locator can find a worker whose node is exactly 0.  It costs a singular value
+ * decomposition per class where Algorithm 2 costs a least-squares solve.
+ * Arguments, requirements and error behaviour as approxifer_decode_byzantine().
+ */
+int approxifer_decode_byzantine_homogeneous(const float *d_preds, const uint8_t *d_mask, float *d_out,
+                                            int32_t *d_adv, int32_t *d_status,
+                                            int64_t G, int K, int N, int S, int A, int64_t C,
+                                            const double *h_alpha, const double *h_beta, int sign_mode,
+                                            void *stream);
+
+/*
  * Fused decoder + top-1 (Section 4.1, "Performance metric": the paper scores the class of the
  * largest decoded soft label).  Decodes exactly as approxifer_decode() does, in float64, and for
  * every group g and query j writes only

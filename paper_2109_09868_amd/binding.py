@@ -30,6 +30,7 @@ EXPORTS = (
     "approxifer_decode",
     "approxifer_decode_top1",
     "approxifer_decode_byzantine",
+    "approxifer_decode_byzantine_homogeneous",
 )
 
 _lib = None
@@ -71,6 +72,8 @@ def load() -> ctypes.CDLL:
     lib.approxifer_decode_byzantine.restype = ctypes.c_int
     lib.approxifer_decode_byzantine.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                                 ctypes.c_int, ctypes.c_int, ctypes.c_int64, c_dp, c_dp, ctypes.c_int, vp]
+    lib.approxifer_decode_byzantine_homogeneous.restype = ctypes.c_int
+    lib.approxifer_decode_byzantine_homogeneous.argtypes = lib.approxifer_decode_byzantine.argtypes
     lib.approxifer_wait_mask.restype = ctypes.c_int
     lib.approxifer_wait_mask.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, vp]
     _lib = lib
@@ -179,10 +182,7 @@ def approxifer_decode_top1(preds, mask, alpha, beta, S, sign_mode=SIGN_WORKER_IN
     return top1, score, status
 
 
-def approxifer_decode_byzantine(preds, mask, alpha, beta, S, A, sign_mode=SIGN_WORKER_INDEX, out=None, adv=None,
-                                status=None, stream=None):
-    """As approxifer_decode, after locating and dropping A adversaries per group.
-    Returns (out [G, K, C] float32, adv [G, A] int32 ascending, status [G] int32)."""
+def _decode_byzantine(entry, preds, mask, alpha, beta, S, A, sign_mode, out, adv, status, stream):
     import torch
     a, ap = _nodes(alpha)
     b, bp = _nodes(beta)
@@ -196,11 +196,26 @@ def approxifer_decode_byzantine(preds, mask, alpha, beta, S, A, sign_mode=SIGN_W
         adv = torch.full((G, max(int(A), 0)), -1, dtype=torch.int32, device=preds.device)
     if status is None:
         status = torch.full((G,), -1, dtype=torch.int32, device=preds.device)
-    _check(load().approxifer_decode_byzantine(_dev(preds, torch.float32), _dev(mask, torch.uint8, (G, N)),
-                                              _dev(out, torch.float32, (G, K, C)), _dev(adv, torch.int32),
-                                              _dev(status, torch.int32, (G,)), G, K, N, int(S), int(A), C, ap, bp,
-                                              int(sign_mode), ctypes.c_void_p(_stream_handle(stream))))
+    _check(getattr(load(), entry)(_dev(preds, torch.float32), _dev(mask, torch.uint8, (G, N)),
+                                  _dev(out, torch.float32, (G, K, C)), _dev(adv, torch.int32),
+                                  _dev(status, torch.int32, (G,)), G, K, N, int(S), int(A), C, ap, bp,
+                                  int(sign_mode), ctypes.c_void_p(_stream_handle(stream))))
     return out, adv, status
+
+
+def approxifer_decode_byzantine(preds, mask, alpha, beta, S, A, sign_mode=SIGN_WORKER_INDEX, out=None, adv=None,
+                                status=None, stream=None):
+    """As approxifer_decode, after locating and dropping A adversaries per group.
+    Returns (out [G, K, C] float32, adv [G, A] int32 ascending, status [G] int32)."""
+    return _decode_byzantine("approxifer_decode_byzantine", preds, mask, alpha, beta, S, A, sign_mode, out, adv,
+                             status, stream)
+
+
+def approxifer_decode_byzantine_homogeneous(preds, mask, alpha, beta, S, A, sign_mode=SIGN_WORKER_INDEX, out=None,
+                                            adv=None, status=None, stream=None):
+    """As approxifer_decode_byzantine, with Algorithm 1's homogeneous fit as the per-class locator."""
+    return _decode_byzantine("approxifer_decode_byzantine_homogeneous", preds, mask, alpha, beta, S, A, sign_mode,
+                             out, adv, status, stream)
 
 
 def approxifer_wait_mask(arrival, wait_for, mask=None, count=None, stream=None):

@@ -104,9 +104,10 @@ int approxifer_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t 
                                           sign_mode, static_cast<hipStream_t>(stream));
 }
 
-int approxifer_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
-                                int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C,
-                                const double *h_alpha, const double *h_beta, int sign_mode, void *stream) {
+static int decode_byzantine_checked(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
+                                    int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C,
+                                    const double *h_alpha, const double *h_beta, int sign_mode, bool homogeneous,
+                                    void *stream) {
     if (G < 0 || C < 0) return APPROXIFER_ERR_BAD_SHAPE;
     Nodes nodes;
     const int rc = check_common(K, N, h_alpha, h_beta, &nodes);
@@ -121,7 +122,22 @@ int approxifer_decode_byzantine(const float *d_preds, const uint8_t *d_mask, flo
     if (d_mask == nullptr || d_adv == nullptr || d_preds == nullptr || d_out == nullptr)
         return APPROXIFER_ERR_NULL_POINTER;
     return approxifer::launch_decode_byzantine(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, S, A, C, nodes,
-                                               sign_mode, static_cast<hipStream_t>(stream));
+                                               sign_mode, homogeneous, static_cast<hipStream_t>(stream));
+}
+
+int approxifer_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
+                                int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C,
+                                const double *h_alpha, const double *h_beta, int sign_mode, void *stream) {
+    return decode_byzantine_checked(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, S, A, C, h_alpha, h_beta,
+                                    sign_mode, false, stream);
+}
+
+int approxifer_decode_byzantine_homogeneous(const float *d_preds, const uint8_t *d_mask, float *d_out,
+                                            int32_t *d_adv, int32_t *d_status, int64_t G, int K, int N, int S,
+                                            int A, int64_t C, const double *h_alpha, const double *h_beta,
+                                            int sign_mode, void *stream) {
+    return decode_byzantine_checked(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, S, A, C, h_alpha, h_beta,
+                                    sign_mode, true, stream);
 }
 
 int approxifer_wait_mask(const float *d_arrival, uint8_t *d_mask, int32_t *d_count, int64_t G, int N, int wait_for,

@@ -513,11 +513,84 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
 // ------------------------------------------------------------------------------------------------
 // general kernel: the full system per class, in LDS
 // ------------------------------------------------------------------------------------------------
+// Algorithm 1's fit needs a null vector of the homogeneous system: the right singular vector of the smallest
+// singular value of its triangular factor R (rows 0..W2-1 of mat, row stride W2).  One-sided Jacobi on G = R^T:
+// lane j owns column j of G, which is row j of mat; a step rotates W2/2 disjoint pairs of columns until they are
+// orthogonal (round-robin pairing, W2 - 1 steps per sweep); the columns then are sigma_i v_i, v_i the right
+// singular vectors of R.  Returns the row of mat that holds the shortest one (a null vector needs no length).
+// Both lanes of a pair read both columns and write their own: the new value of element t depends on both reads of
+// element t, and the lanes of a wave run in lock step, so no lane sees a half-rotated pair.
+constexpr int kJacobiSweeps = 30;
+__device__ __forceinline__ int smallest_singular_row(double *mat, double *key, int W2, int j, bool live) {
+    double *own = mat + j * W2;
+    if (live)
+        for (int t = 0; t < j; ++t) own[t] = 0.0;         // left of the diagonal the factorisation leaves old values
+    __builtin_amdgcn_wave_barrier();
+    const int m = W2 - 1;
+    const double tol = W2 * 2.220446049250313e-16;
+    for (int sweep = 0; sweep < kJacobiSweeps; ++sweep) {
+        bool rotated = false;
+        for (int s = 0; s < m; ++s) {
+            int k;                                        // this lane's partner: lane m plays s, the others mirror about s
+            if (j == m) {
+                k = s;
+            } else if (j == s) {
+                k = m;
+            } else {
+                k = 2 * s - j;
+                if (k < 0) k += m;
+                if (k >= m) k -= m;
+            }
+            const double *oth = mat + k * W2;
+            double al = 0.0, be = 0.0, ga = 0.0;
+#pragma unroll 4
+            for (int t = 0; t < W2; ++t) {
+                const double a = own[t], b = oth[t];
+                al = fma(a, a, al);
+                be = fma(b, b, be);
+                ga = fma(a, b, ga);
+            }
+            const bool first = j < k;                     // the pair is (p, q), p < q; both lanes compute the same angle
+            const double ap = first ? al : be, aq = first ? be : al;
+            const bool rot = live && fabs(ga) > tol * sqrt(ap * aq);
+            if (rot) {
+                const double zeta = (aq - ap) / (2.0 * ga);
+                const double tn = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(fma(zeta, zeta, 1.0)));
+                const double cs = 1.0 / sqrt(fma(tn, tn, 1.0));
+                const double so = first ? -cs * tn : cs * tn;      // g_p' = c g_p - s g_q,  g_q' = s g_p + c g_q
+#pragma unroll 4
+                for (int t = 0; t < W2; ++t) own[t] = fma(so, oth[t], cs * own[t]);
+                rotated = true;
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        if (!__any(rotated ? 1 : 0)) break;
+    }
+    double nrm = 0.0;
+    for (int t = 0; t < W2; ++t) nrm = fma(own[t], own[t], nrm);
+    if (live) key[j] = (nrm == nrm) ? nrm : __builtin_inf();
+    __builtin_amdgcn_wave_barrier();
+    int jmin = 0;
+    double best = key[0];
+    for (int t = 1; t < W2; ++t) {
+        const double v = key[t];
+        if (v < best) {
+            best = v;
+            jmin = t;
+        }
+    }
+    __builtin_amdgcn_wave_barrier();                      // key is reused by the caller
+    return jmin;
+}
+
 // Algorithm 2, steps 1-5, for the classes c0 .. c0+cpw-1 of one group, by one wave.
 //   n        available workers (rows), M = K + A, W2 = 2M columns including the right-hand side
 //   xs[n]    worker nodes of the available workers (LDS, shared by the workgroup)
 //   scratch  this wave's LDS: per class  mat[n][W2] | coef[M] | key[n]
 // Lane (cl, j) = (lane / W2, lane % W2) works on class c0 + cl; lanes beyond cpw classes idle.
+// HOMOG: Algorithm 1's fit instead (Q_0 free).  The last column, y, then is one more column of the homogeneous
+// system [V | -y x^1 .. -y x^(M-1) | y] whose coefficient is -Q_0; (P, Q) is its null vector of unit length.
+template <bool HOMOG>
 __device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg, int64_t C, int64_t c0, int cpw,
                                                     const int *avail, const double *xs, int n, int M, int A,
                                                     double *scratch, int *votes) {
@@ -553,7 +626,8 @@ __device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg
     // ---- Householder QR in least-squares form, one lane per column ---------------------
     // Step k reflects column k onto e_k over rows k..n-1 and applies the reflector to the
     // columns right of it (and to the right-hand side).
-    for (int k = 0; k < cols; ++k) {
+    const int qr_steps = HOMOG ? W2 : cols;               // n >= W2: eq. (3)
+    for (int k = 0; k < qr_steps; ++k) {
         double sigma = 0.0, d = 0.0;
 #pragma unroll 4
         for (int r = k; r < n; ++r) {
@@ -580,26 +654,40 @@ __device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg
         __builtin_amdgcn_wave_barrier();
     }
 
-    // ---- back substitution for Q_{M-1} .. Q_1 (unknowns cols-1 .. M); P is not needed ----
-    // lane j holds the transformed right-hand side entry of row j.
-    double s = (live && j < cols) ? mat[j * W2 + cols] : 0.0;
-    const double diag = (live && j < cols) ? mat[j * W2 + j] : 1.0;
-    for (int t = cols - 1; t >= M; --t) {
-        if (live && j == t) coef[t - M] = s / diag;       // Q_{t-M+1}
-        __builtin_amdgcn_wave_barrier();
-        const double sol = coef[t - M];
-        if (live && j < t) s = fma(-mat[j * W2 + t], sol, s);
-        __builtin_amdgcn_wave_barrier();
-    }
+    if (HOMOG) {
+        // ---- the null vector, then a_r = Q(x_r): Q_k = z[M-1+k] for k >= 1, Q_0 = -z[cols] -------------------------
+        const double *z = mat + smallest_singular_row(mat, key, W2, j, live) * W2;
+        if (live) {
+            for (int r = j; r < n; r += W2) {
+                const double x = xs[r];
+                double a = 0.0;
+                for (int t = cols - 1; t >= M; --t) a = fma(a, x, z[t]);
+                a = fma(a, x, -z[cols]);
+                key[r] = (a != a) ? __builtin_inf() : fabs(a);
+            }
+        }
+    } else {
+        // ---- back substitution for Q_{M-1} .. Q_1 (unknowns cols-1 .. M); P is not needed ----
+        // lane j holds the transformed right-hand side entry of row j.
+        double s = (live && j < cols) ? mat[j * W2 + cols] : 0.0;
+        const double diag = (live && j < cols) ? mat[j * W2 + j] : 1.0;
+        for (int t = cols - 1; t >= M; --t) {
+            if (live && j == t) coef[t - M] = s / diag;   // Q_{t-M+1}
+            __builtin_amdgcn_wave_barrier();
+            const double sol = coef[t - M];
+            if (live && j < t) s = fma(-mat[j * W2 + t], sol, s);
+            __builtin_amdgcn_wave_barrier();
+        }
 
-    // ---- step 3: a_r = Q(x_r), Horner, one lane per row; steps 4-5: the A smallest |a_r| ----
-    if (live) {
-        for (int r = j; r < n; r += W2) {
-            const double x = xs[r];
-            double a = 0.0;
-            for (int t = cols - 1; t >= M; --t) a = fma(a, x, coef[t - M]);
-            a = fma(a, x, 1.0);                           // Q_0 = 1
-            key[r] = (a != a) ? __builtin_inf() : fabs(a);
+        // ---- step 3: a_r = Q(x_r), Horner, one lane per row; steps 4-5: the A smallest |a_r| ----
+        if (live) {
+            for (int r = j; r < n; r += W2) {
+                const double x = xs[r];
+                double a = 0.0;
+                for (int t = cols - 1; t >= M; --t) a = fma(a, x, coef[t - M]);
+                a = fma(a, x, 1.0);                       // Q_0 = 1
+                key[r] = (a != a) ? __builtin_inf() : fabs(a);
+            }
         }
     }
     __builtin_amdgcn_wave_barrier();
@@ -610,6 +698,7 @@ __device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg
 // dynamic LDS: double scratch[nw][cpw * (n*2M + M + n)] | double WdT[(n-A) * KP] | double xs[n]
 //              | double alpha_s[K] | double beta_s[N]
 //              | int avail[N] | int F[N] | int Fpos[N] | int votes[N] | int sel[N] | int n
+template <bool HOMOG>
 __global__ void decode_byzantine_general_kernel(const float *__restrict__ preds, const uint8_t *__restrict__ mask,
                                                 float *__restrict__ out, int32_t *__restrict__ adv,
                                                 int32_t *__restrict__ status, int K, int N, int S, int A, int64_t C,
@@ -654,7 +743,8 @@ __global__ void decode_byzantine_general_kernel(const float *__restrict__ preds,
     for (int r = threadIdx.x; r < n; r += blockDim.x) xs[r] = beta_s[avail[r]];
     __syncthreads();
     for (int64_t c0 = static_cast<int64_t>(wv) * cpw; c0 < C; c0 += static_cast<int64_t>(nw) * cpw)
-        locate_classes_wave(pg, C, c0, cpw, avail, xs, n, M, A, scratch + static_cast<size_t>(wv) * wave_doubles, votes);
+        locate_classes_wave<HOMOG>(pg, C, c0, cpw, avail, xs, n, M, A, scratch + static_cast<size_t>(wv) * wave_doubles,
+                                   votes);
     __syncthreads();
 
     finish_group(pg, out + static_cast<size_t>(g) * K * C, adv + g * A, avail, n, N, A, K, KP, C, Cv, vec4 != 0, sign_mode,
@@ -690,7 +780,7 @@ int run_proj(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t 
 
 int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
                             int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C, const Nodes &nodes,
-                            int sign_mode, hipStream_t stream) {
+                            int sign_mode, bool homogeneous, hipStream_t stream) {
     const int KP = (K + 3) & ~3;
     // capacity: the most available workers a group can bring (S < 0: read off each mask)
     const int n = S < 0 ? (N < APPROXIFER_MAX_AVAIL_BYZ ? N : APPROXIFER_MAX_AVAIL_BYZ) : N - S;
@@ -699,7 +789,7 @@ int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *
     const int64_t Cv = vec4 ? C / 4 : C;
     if (G > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
 
-    if (M <= kProjMaxM && n <= 48 && n - M <= 32) {
+    if (!homogeneous && M <= kProjMaxM && n <= 48 && n - M <= 32) {
         // register tiles <rows of [V | I], rows of the projected system>: the smallest that holds (n, n - M)
 #define APPROXIFER_PROJ(NB, RM)                                                                                        \
     if (n <= NB && n - M <= RM)                                                                                        \
@@ -732,8 +822,12 @@ int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *
     if (nw < 1) nw = 1;
     const size_t lds = fixed + nw * per_wave;
     const dim3 grid(static_cast<unsigned>(G)), block(nw * kWave);
-    hipLaunchKernelGGL(decode_byzantine_general_kernel, grid, block, lds, stream, d_preds, d_mask, d_out, d_adv, d_status,
-                       K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, cpw, n, nodes);
+    if (homogeneous)
+        hipLaunchKernelGGL(decode_byzantine_general_kernel<true>, grid, block, lds, stream, d_preds, d_mask, d_out, d_adv,
+                           d_status, K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, cpw, n, nodes);
+    else
+        hipLaunchKernelGGL(decode_byzantine_general_kernel<false>, grid, block, lds, stream, d_preds, d_mask, d_out, d_adv,
+                           d_status, K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, cpw, n, nodes);
     return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
 }
 

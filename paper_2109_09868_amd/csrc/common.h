@@ -104,7 +104,7 @@ int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_t
                        int sign_mode, hipStream_t stream);
 int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
                             int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C,
-                            const Nodes &nodes, int sign_mode, hipStream_t stream);
+                            const Nodes &nodes, int sign_mode, bool homogeneous, hipStream_t stream);
 
 int launch_wait_mask(const float *d_arrival, uint8_t *d_mask, int32_t *d_count, int64_t G, int N, int wait_for,
                      hipStream_t stream);

@@ -581,8 +581,9 @@ def test_byzantine_fewer_real_adversaries_than_A(gpu, real):
         assert group_err(out[g:g + 1], ref_g).max() <= TOL
 
 
+@pytest.mark.parametrize("entry", ["approxifer_decode_byzantine", "approxifer_decode_byzantine_homogeneous"])
 @pytest.mark.parametrize("K,A,S,N,C", [(8, 2, 4, 24, 10), (12, 2, 0, 28, 10), (3, 1, 0, 64, 5), (18, 2, 0, 44, 3)])
-def test_byzantine_degenerate_predictions(gpu, K, A, S, N, C):
+def test_byzantine_degenerate_predictions(gpu, K, A, S, N, C, entry):
     # rank-deficient fits: all-zero predictions, the same constant everywhere, identical classes, one available
     # worker holding NaN.  No located set is "right" here; what must hold: every group is decoded, the located
     # workers are distinct available workers in ascending order, and -- the weights sum to one -- constants
@@ -601,8 +602,8 @@ def test_byzantine_degenerate_predictions(gpu, K, A, S, N, C):
     Y[4] = rng.standard_normal((N, C)).astype(np.float32)
     Y[4, np.nonzero(mask[4])[0][3]] = np.nan                    # a worker that returns NaN
     Y[5] = rng.standard_normal((N, C)).astype(np.float32) * 1e-30
-    out, adv, st = binding.approxifer_decode_byzantine(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev),
-                                                       alpha, beta, S, A, 1)
+    out, adv, st = getattr(binding, entry)(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev), alpha, beta, S,
+                                           A, 1)
     out, adv, st = out.cpu().numpy(), adv.cpu().numpy(), st.cpu().numpy()
     assert np.all(st == 0)
     for g in range(G):
@@ -615,6 +616,138 @@ def test_byzantine_degenerate_predictions(gpu, K, A, S, N, C):
         m2[0, adv[g]] = 0
         ref_g, _ = orc.decode(Y[g:g + 1], m2, alpha, beta, None, 1)
         assert group_err(out[g:g + 1], ref_g).max() <= TOL
+
+
+# --------------------------------------------------------------------------------------
+# Algorithm 1 (Q_0 free, null vector of the homogeneous system) as the per-class locator
+# --------------------------------------------------------------------------------------
+def _hom_both(gpu, Y, mask, alpha, beta, S, A, mode=0):
+    torch, binding, dev = gpu
+    out, adv, st = binding.approxifer_decode_byzantine_homogeneous(torch.from_numpy(Y).to(dev),
+                                                                   torch.from_numpy(mask).to(dev), alpha, beta, S, A, mode)
+    ref, adv_ref, st_ref = orc.decode_byzantine(Y, mask, alpha, beta, S, A, mode, locator=orc.LOCATOR_ALGORITHM_1)
+    return out.cpu().numpy(), adv.cpu().numpy(), st.cpu().numpy(), ref, adv_ref, st_ref
+
+
+def _decisive(Y, mask, beta, K, A, locator):
+    """Groups whose oracle vote separates the A-th from the (A+1)-th most voted worker by two or more."""
+    ok = np.zeros(Y.shape[0], bool)
+    for g in range(Y.shape[0]):
+        _, _, counts = orc.locate(Y[g], np.nonzero(mask[g])[0], beta, K, A, locator)
+        top = np.sort(counts)[::-1]
+        ok[g] = top[A - 1] - top[A] >= 2
+    return ok
+
+
+def test_homogeneous_locator_byzantine_workload(gpu):
+    w = syn.scaled(syn.WORKLOADS["byzantine"], G=256)
+    alpha, beta, Y, mask, adv_true = _byzantine_inputs(w)
+    out, adv, st, ref, adv_ref, st_ref = _hom_both(gpu, Y, mask, alpha, beta, w.S, w.A)
+    assert np.all(st == 0) and np.array_equal(st, st_ref)
+    assert np.array_equal(adv, adv_ref) and np.array_equal(adv, adv_true)
+    assert group_err(out, ref).max() <= TOL
+
+
+@pytest.mark.parametrize("K,A,S,N,C,G", [
+    (2, 1, 0, 6, 3, 16), (3, 2, 2, 12, 10, 16), (12, 2, 0, 28, 10, 4), (8, 2, 4, 24, 40, 4), (8, 2, 0, 64, 6, 2),
+    (4, 1, 3, 13, 17, 8), (1, 1, 0, 48, 2, 4), (3, 1, 1, 9, 6, 600), (13, 3, 1, 33, 3, 3), (5, 2, 2, 23, 4, 8),
+])
+def test_homogeneous_locator_exactly_rational_predictions(gpu, K, A, S, N, C, G):
+    # Theorem 1's setting: the null vector is the error locator times the denominator, the planted workers come back.
+    # Here a worker on the node 0 can be an adversary too: Q_0 is free.
+    rng = np.random.default_rng(K * 100 + A * 10 + S + 5)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    X = rng.uniform(0, 1, (G, K, 96))
+    Mf = rng.standard_normal((96, C)) / 10
+    clean = (orc.encode(X, alpha, beta) @ Mf).astype(np.float32)
+    mask = np.zeros((G, N), np.uint8)
+    adv_true = np.zeros((G, A), np.int32)
+    Y = clean.copy()
+    for g in range(G):
+        avail = np.sort(rng.permutation(N)[: N - S])
+        mask[g, avail] = 1
+        adv_true[g] = np.sort(rng.permutation(avail)[:A])
+        Y[g, adv_true[g]] += (10 * clean.std() * rng.standard_normal((A, C))).astype(np.float32)
+    out, adv, st, ref, adv_ref, st_ref = _hom_both(gpu, Y, mask, alpha, beta, S, A)
+    assert np.all(st == 0)
+    assert np.array_equal(adv, adv_ref) and np.array_equal(adv, adv_true)
+    assert group_err(out, ref).max() <= TOL
+
+
+def test_homogeneous_locator_finds_the_worker_on_node_zero(gpu):
+    # an odd number of workers puts the middle worker on the node 0, where Algorithm 2's Q equals 1 by construction
+    # (it can only be picked there if |Q| happens to exceed 1 on every other node); Algorithm 1's Q vanishes on it
+    torch, binding, dev = gpu
+    K, A, S, N, C, G = 3, 1, 0, 9, 6, 32
+    rng = np.random.default_rng(3)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    assert abs(beta[4]) < 1e-15
+    X = rng.uniform(0, 1, (G, K, 64))
+    Mf = rng.standard_normal((64, C)) / 8
+    Y = (orc.encode(X, alpha, beta) @ Mf).astype(np.float32)
+    mask = np.ones((G, N), np.uint8)
+    Y[:, 4] += (10 * Y.std() * rng.standard_normal((G, C))).astype(np.float32)
+    out, adv, st, ref, adv_ref, _ = _hom_both(gpu, Y, mask, alpha, beta, S, A)
+    assert np.all(st == 0) and np.all(adv == 4) and np.array_equal(adv, adv_ref)
+    assert group_err(out, ref).max() <= TOL
+    for g in range(4):                                      # per class, Algorithm 1 is unanimous
+        _, I, _ = orc.locate(Y[g], np.arange(N), beta, K, A, orc.LOCATOR_ALGORITHM_1)
+        assert np.all(I == 4)
+
+
+def test_homogeneous_locator_on_data_that_is_not_rational(gpu):
+    # softmax outputs and plain noise: no null vector, the smallest singular vector is a genuine fit and its
+    # singular value need not be well separated.  The kernel's Jacobi iteration and the oracle's SVD must still
+    # agree on every group whose vote is not a near tie.
+    K, A, S, N, C, G = 4, 1, 2, 12, 10, 128
+    rng = np.random.default_rng(78)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    X = rng.uniform(0, 1, (G, K, 48))
+    z = orc.encode(X, alpha, beta) @ rng.standard_normal((48, C))
+    Y = (np.exp(z) / np.exp(z).sum(-1, keepdims=True)).astype(np.float32)
+    Y[G // 2:] = rng.standard_normal((G - G // 2, N, C)).astype(np.float32)
+    mask = np.zeros((G, N), np.uint8)
+    for g in range(G):
+        avail = np.sort(rng.permutation(N)[: N - S])
+        mask[g, avail] = 1
+        Y[g, rng.permutation(avail)[:A]] += rng.standard_normal((A, C)).astype(np.float32)
+    out, adv, st, ref, adv_ref, _ = _hom_both(gpu, Y, mask, alpha, beta, S, A)
+    clear = _decisive(Y, mask, beta, K, A, orc.LOCATOR_ALGORITHM_1)
+    assert clear.sum() >= G // 4
+    assert np.array_equal(adv[clear], adv_ref[clear])
+    same = np.all(adv == adv_ref, axis=1)
+    assert same.mean() >= 0.95
+    assert group_err(out[same], ref[same]).max() <= TOL
+
+
+def test_homogeneous_locator_bad_and_ragged_masks(gpu):
+    torch, binding, dev = gpu
+    K, A, N, C, G = 4, 1, 16, 7, 48
+    rng = np.random.default_rng(12)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    X = rng.uniform(0, 1, (G, K, 64))
+    clean = (orc.encode(X, alpha, beta) @ (rng.standard_normal((64, C)) / 8)).astype(np.float32)
+    mask = np.zeros((G, N), np.uint8)
+    Y = clean.copy()
+    adv_true = np.full((G, A), -1, np.int32)
+    for g in range(G):
+        n = int(rng.integers(8, N + 1))                     # 8, 9: fewer than 2(K+A) = 10 available -> bad mask
+        avail = np.sort(rng.permutation(N)[:n])
+        mask[g, avail] = 1
+        adv_true[g] = np.sort(rng.permutation(avail)[:A])
+        Y[g, adv_true[g]] += (10 * clean.std() * rng.standard_normal((A, C))).astype(np.float32)
+    out0 = torch.full((G, K, C), -3.0, dtype=torch.float32, device=dev)
+    adv0 = torch.full((G, A), -7, dtype=torch.int32, device=dev)
+    out, adv, st = binding.approxifer_decode_byzantine_homogeneous(torch.from_numpy(Y).to(dev),
+                                                                   torch.from_numpy(mask).to(dev), alpha, beta,
+                                                                   binding.S_FROM_MASK, A, 1, out=out0, adv=adv0)
+    ref, adv_ref, st_ref = orc.decode_byzantine(Y, mask, alpha, beta, None, A, 1, locator=orc.LOCATOR_ALGORITHM_1)
+    out, adv, st = out.cpu().numpy(), adv.cpu().numpy(), st.cpu().numpy()
+    assert np.array_equal(st, st_ref) and 0 < st.sum() < G
+    bad = st != 0
+    assert np.all(out[bad] == -3.0) and np.all(adv[bad] == -7)
+    assert np.array_equal(adv[~bad], adv_ref[~bad]) and np.array_equal(adv[~bad], adv_true[~bad])
+    assert group_err(out[~bad], ref[~bad]).max() <= TOL
 
 
 # --------------------------------------------------------------------------------------
