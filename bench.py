@@ -29,9 +29,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # (profiles/encode_imagenet_hbm_counters.md).  Valid only for the kernel sources hashed here.
 ENCODE_KERNEL_SOURCES = ("paper_2109_09868_amd/csrc/encode.hip", "paper_2109_09868_amd/csrc/common.h")
 ENCODE_TRAFFIC = {
-    "sources_sha256": "5b79276b1f51d27afa8e2f083a8bf522d3308e2698e7c5ecb88e72cbd08f5a1c",
-    "fetch_size_kib": 1806382.0, "fetch_factor": 2.0000,     # counter reads half the bytes of a known copy
-    "write_size_kib": 6021132.3, "write_factor": 1.0000,
+    "sources_sha256": "e31ff801f124dcb88b4446fe92de3fa6aca3713f8c803cdcc241ebb75700b3f4",
+    "fetch_size_kib": 1806382.8, "fetch_factor": 2.0000,     # counter reads half the bytes of a known copy
+    "write_size_kib": 6021142.2, "write_factor": 1.0000,
 }
 
 
@@ -259,6 +259,13 @@ def other_workloads(torch, binding, syn, orc_nodes, dev, sign_mode):
                                    locator_solves_per_s=w.G * w.C / (t["avg_ms"] * 1e-3),
                                    hbm_gbs=decode_bytes(w, True) / (t["avg_ms"] * 1e6),
                                    planted_adversaries_located=located, roofline=alu_roofline(w, t["avg_ms"]), note=COLD)
+    # the same groups with Algorithm 1's homogeneous fit as the locator: a singular vector per class
+    t = time_launches(torch, lambda: binding.approxifer_decode_byzantine_homogeneous(
+        preds, mask, alpha, beta, w.S, w.A, sign_mode, out=out, adv=adv, status=st), 10, flush=flush)
+    located = bool(np.array_equal(adv.cpu().numpy(), adv_true))
+    res["byzantine_decode_algorithm1"] = dict(t, predictions_per_s=w.G * w.K / (t["avg_ms"] * 1e-3),
+                                              locator_fits_per_s=w.G * w.C / (t["avg_ms"] * 1e-3),
+                                              planted_adversaries_located=located, note=COLD)
     del q, coded
 
     # -- the paper's Byzantine operating point: K = 12, S = 0, E = 2, 28 workers, MNIST-sized queries ---

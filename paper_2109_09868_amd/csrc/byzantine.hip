@@ -514,20 +514,80 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
 // general kernel: the full system per class, in LDS
 // ------------------------------------------------------------------------------------------------
 // Algorithm 1's fit needs a null vector of the homogeneous system: the right singular vector of the smallest
-// singular value of its triangular factor R (rows 0..W2-1 of mat, row stride W2).  One-sided Jacobi on G = R^T:
-// lane j owns column j of G, which is row j of mat; a step rotates W2/2 disjoint pairs of columns until they are
-// orthogonal (round-robin pairing, W2 - 1 steps per sweep); the columns then are sigma_i v_i, v_i the right
-// singular vectors of R.  Returns the row of mat that holds the shortest one (a null vector needs no length).
-// Both lanes of a pair read both columns and write their own: the new value of element t depends on both reads of
-// element t, and the lanes of a wave run in lock step, so no lane sees a half-rotated pair.
+// singular value of its triangular factor R (rows 0..W2-1 of mat, row stride LD, lane j owns row j).  Writes the Q
+// half of that vector to coef[0..M-1] (coefficients of columns M..W2-1); its length and sign are immaterial.
+//
+//  1. Inverse iteration z <- (R^T R)^-1 z, two triangular solves per round.  When the data are rational up to
+//     rounding -- the case the locator is built for -- the smallest singular value is orders of magnitude below the
+//     next and two to four rounds settle z: successive iterates within 1e-11, or no longer approaching each other.
+//  2. Classes that have not settled after kInverseRounds (no gap: data that fit no rational function; or a zero on
+//     the diagonal) get the full answer from one-sided Jacobi on G = R^T: lane j owns column j of G, which is row j
+//     of mat; a step rotates W2/2 disjoint pairs of columns (round-robin pairing, W2 - 1 steps per sweep) until all
+//     are orthogonal to rounding; the columns then are sigma_i v_i, v_i the right singular vectors of R, and the
+//     shortest is the one wanted.  Both lanes of a pair read both columns and write their own: the new value of
+//     element t depends on both reads of element t, and the lanes of a wave run in lock step, so no lane sees a
+//     half-rotated pair.
+constexpr int kInverseRounds = 24;
 constexpr int kJacobiSweeps = 30;
-__device__ __forceinline__ int smallest_singular_row(double *mat, double *key, int W2, int j, bool live) {
-    double *own = mat + j * W2;
+__device__ __forceinline__ void homogeneous_q(double *mat, int LD, double *coef, double *key, int W2, int M, int j,
+                                              bool live) {
+    double *own = mat + j * LD;
+    // ---- 1. inverse iteration; R mirrored into the lower triangle so that both solves read rows ----------------
     if (live)
-        for (int t = 0; t < j; ++t) own[t] = 0.0;         // left of the diagonal the factorisation leaves old values
+        for (int t = 0; t < j; ++t) own[t] = mat[t * LD + j];
+    __builtin_amdgcn_wave_barrier();
+    const double rd = 1.0 / own[j];                     // a zero on the diagonal: nothing settles, Jacobi takes the class
+    double z = 1.0 + 0.25 * (j % 3);
+    double dd_prev = __builtin_inf();
+    bool settled = false;
+    for (int round = 0; round < kInverseRounds; ++round) {
+        double s = z;                                     // R^T w = z, forward
+        for (int t = 0; t < W2; ++t) {
+            const double rtj = mat[t * LD + j];           // issued ahead of the write -> read chain through key
+            if (live && j == t) key[t] = s * rd;
+            __builtin_amdgcn_wave_barrier();
+            const double wt = key[t];
+            if (j > t) s = fma(-rtj, wt, s);
+        }
+        __builtin_amdgcn_wave_barrier();
+        s = key[j];                                       // R z' = w, backward
+        for (int t = W2 - 1; t >= 0; --t) {
+            const double rjt = mat[t * LD + j];           // the mirrored R[j][t]
+            if (live && j == t) key[t] = s * rd;
+            __builtin_amdgcn_wave_barrier();
+            const double zt = key[t];
+            if (j < t) s = fma(-rjt, zt, s);
+        }
+        __builtin_amdgcn_wave_barrier();
+        double nn = 0.0;
+        for (int t = 0; t < W2; ++t) nn = fma(key[t], key[t], nn);
+        const double zn = key[j] * rcp_normal(sqrt_normal(nn));   // nn = 0, inf or NaN: NaN, and the class goes to Jacobi
+        const double dz = zn - z;                         // z' . z > 0 always: no sign to align
+        __builtin_amdgcn_wave_barrier();
+        if (live) key[j] = dz * dz;
+        __builtin_amdgcn_wave_barrier();
+        double dd = 0.0;
+        for (int t = 0; t < W2; ++t) dd += key[t];
+        __builtin_amdgcn_wave_barrier();
+        z = zn;
+        // settled: the step is below 1e-11, or it has stopped shrinking at the level rounding allows (false for NaN)
+        settled = dd <= 1e-22 || (dd_prev <= 1e-16 && dd >= 0.25 * dd_prev);
+        dd_prev = dd;
+        if (__all((settled || !live) ? 1 : 0)) break;
+    }
+    if (live && settled && j >= M) coef[j - M] = z;
+    const bool need = live && !settled;
+    if (!__any(need ? 1 : 0)) {
+        __builtin_amdgcn_wave_barrier();
+        return;
+    }
+
+    // ---- 2. one-sided Jacobi for the classes that did not settle ----------------------------------------------
+    if (need)
+        for (int t = 0; t < j; ++t) own[t] = 0.0;
     __builtin_amdgcn_wave_barrier();
     const int m = W2 - 1;
-    const double tol = W2 * 2.220446049250313e-16;
+    const double tol2 = (W2 * 2.220446049250313e-16) * (W2 * 2.220446049250313e-16);
     for (int sweep = 0; sweep < kJacobiSweeps; ++sweep) {
         bool rotated = false;
         for (int s = 0; s < m; ++s) {
@@ -541,22 +601,27 @@ __device__ __forceinline__ int smallest_singular_row(double *mat, double *key, i
                 if (k < 0) k += m;
                 if (k >= m) k -= m;
             }
-            const double *oth = mat + k * W2;
+            const double *oth = mat + k * LD;
             double al = 0.0, be = 0.0, ga = 0.0;
+            if (need) {
 #pragma unroll 4
-            for (int t = 0; t < W2; ++t) {
-                const double a = own[t], b = oth[t];
-                al = fma(a, a, al);
-                be = fma(b, b, be);
-                ga = fma(a, b, ga);
+                for (int t = 0; t < W2; ++t) {
+                    const double a = own[t], b = oth[t];
+                    al = fma(a, a, al);
+                    be = fma(b, b, be);
+                    ga = fma(a, b, ga);
+                }
             }
             const bool first = j < k;                     // the pair is (p, q), p < q; both lanes compute the same angle
             const double ap = first ? al : be, aq = first ? be : al;
-            const bool rot = live && fabs(ga) > tol * sqrt(ap * aq);
+            // rotate unless |g_p . g_q| <= tol |g_p| |g_q| (also skipped: NaN, and products that underflow to zero)
+            const bool rot = need && ga * ga > tol2 * (ap * aq);
             if (rot) {
-                const double zeta = (aq - ap) / (2.0 * ga);
-                const double tn = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(fma(zeta, zeta, 1.0)));
-                const double cs = 1.0 / sqrt(fma(tn, tn, 1.0));
+                // zeta = cot(2 phi), clamped so that its square stays finite (beyond 1e150 the rotation is the identity
+                // to more digits than a double holds)
+                const double zeta = fmin(fmax((aq - ap) * rcp_normal(2.0 * ga), -1e150), 1e150);
+                const double tn = (zeta >= 0.0 ? 1.0 : -1.0) * rcp_normal(fabs(zeta) + sqrt_normal(fma(zeta, zeta, 1.0)));
+                const double cs = rcp_normal(sqrt_normal(fma(tn, tn, 1.0)));
                 const double so = first ? -cs * tn : cs * tn;      // g_p' = c g_p - s g_q,  g_q' = s g_p + c g_q
 #pragma unroll 4
                 for (int t = 0; t < W2; ++t) own[t] = fma(so, oth[t], cs * own[t]);
@@ -568,7 +633,7 @@ __device__ __forceinline__ int smallest_singular_row(double *mat, double *key, i
     }
     double nrm = 0.0;
     for (int t = 0; t < W2; ++t) nrm = fma(own[t], own[t], nrm);
-    if (live) key[j] = (nrm == nrm) ? nrm : __builtin_inf();
+    if (need) key[j] = (nrm == nrm) ? nrm : __builtin_inf();
     __builtin_amdgcn_wave_barrier();
     int jmin = 0;
     double best = key[0];
@@ -579,8 +644,8 @@ __device__ __forceinline__ int smallest_singular_row(double *mat, double *key, i
             jmin = t;
         }
     }
+    if (need && j >= M) coef[j - M] = mat[jmin * LD + j];
     __builtin_amdgcn_wave_barrier();                      // key is reused by the caller
-    return jmin;
 }
 
 // Algorithm 2, steps 1-5, for the classes c0 .. c0+cpw-1 of one group, by one wave.
@@ -601,9 +666,10 @@ __device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg
     const int j = lane - cl * W2;
     const int64_t c = c0 + cl;
     const bool live = cl < cpw && c < C;     // this lane's class exists
-    const int per_class = n * W2 + M + n;
+    const int LD = HOMOG ? W2 + 1 : W2;     // row stride of mat; odd for the column rotations of Algorithm 1's fit
+    const int per_class = n * LD + M + n;
     double *mat = scratch + (live ? cl : 0) * per_class;
-    double *coef = mat + n * W2;
+    double *coef = mat + n * LD;
     double *key = coef + M;
 
     // ---- steps 1-2: the system, one lane per row (rows j, j+W2, ..) -------------------
@@ -611,7 +677,7 @@ __device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg
         for (int r = j; r < n; r += W2) {
             const double x = xs[r];
             const double y = static_cast<double>(pg[static_cast<size_t>(avail[r]) * C + c]);
-            double *row = mat + r * W2;
+            double *row = mat + r * LD;
             double p = 1.0;
             for (int k = 0; k < M; ++k) {
                 row[k] = p;                               // x^k
@@ -631,51 +697,51 @@ __device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg
         double sigma = 0.0, d = 0.0;
 #pragma unroll 4
         for (int r = k; r < n; ++r) {
-            const double vr = mat[r * W2 + k];            // broadcast inside the class
-            const double arj = mat[r * W2 + j];
+            const double vr = mat[r * LD + k];            // broadcast inside the class
+            const double arj = mat[r * LD + j];
             sigma = fma(vr, vr, sigma);
             d = fma(vr, arj, d);
         }
-        const double xkk = mat[k * W2 + k];
-        const double akj = mat[k * W2 + j];
+        const double xkk = mat[k * LD + k];
+        const double akj = mat[k * LD + j];
         const Reflector h = reflector(sigma, d, xkk, akj);
         __builtin_amdgcn_wave_barrier();
         if (live && !h.degenerate) {
             if (j > k) {
 #pragma unroll 4
                 for (int r = k; r < n; ++r) {
-                    const double vr = (r == k) ? xkk - h.alpha : mat[r * W2 + k];
-                    mat[r * W2 + j] = fma(-h.f, vr, mat[r * W2 + j]);
+                    const double vr = (r == k) ? xkk - h.alpha : mat[r * LD + k];
+                    mat[r * LD + j] = fma(-h.f, vr, mat[r * LD + j]);
                 }
             } else if (j == k) {
-                mat[k * W2 + k] = h.alpha;                // R[k][k]
+                mat[k * LD + k] = h.alpha;                // R[k][k]
             }
         }
         __builtin_amdgcn_wave_barrier();
     }
 
     if (HOMOG) {
-        // ---- the null vector, then a_r = Q(x_r): Q_k = z[M-1+k] for k >= 1, Q_0 = -z[cols] -------------------------
-        const double *z = mat + smallest_singular_row(mat, key, W2, j, live) * W2;
+        // ---- the null vector, then a_r = Q(x_r): Q_k = coef[k-1] for k >= 1, Q_0 = -coef[M-1] ----------------------
+        homogeneous_q(mat, LD, coef, key, W2, M, j, live);
         if (live) {
             for (int r = j; r < n; r += W2) {
                 const double x = xs[r];
                 double a = 0.0;
-                for (int t = cols - 1; t >= M; --t) a = fma(a, x, z[t]);
-                a = fma(a, x, -z[cols]);
+                for (int t = M - 2; t >= 0; --t) a = fma(a, x, coef[t]);
+                a = fma(a, x, -coef[M - 1]);
                 key[r] = (a != a) ? __builtin_inf() : fabs(a);
             }
         }
     } else {
         // ---- back substitution for Q_{M-1} .. Q_1 (unknowns cols-1 .. M); P is not needed ----
         // lane j holds the transformed right-hand side entry of row j.
-        double s = (live && j < cols) ? mat[j * W2 + cols] : 0.0;
-        const double diag = (live && j < cols) ? mat[j * W2 + j] : 1.0;
+        double s = (live && j < cols) ? mat[j * LD + cols] : 0.0;
+        const double diag = (live && j < cols) ? mat[j * LD + j] : 1.0;
         for (int t = cols - 1; t >= M; --t) {
             if (live && j == t) coef[t - M] = s / diag;   // Q_{t-M+1}
             __builtin_amdgcn_wave_barrier();
             const double sol = coef[t - M];
-            if (live && j < t) s = fma(-mat[j * W2 + t], sol, s);
+            if (live && j < t) s = fma(-mat[j * LD + t], sol, s);
             __builtin_amdgcn_wave_barrier();
         }
 
@@ -695,7 +761,7 @@ __device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg
     __builtin_amdgcn_wave_barrier();
 }
 
-// dynamic LDS: double scratch[nw][cpw * (n*2M + M + n)] | double WdT[(n-A) * KP] | double xs[n]
+// dynamic LDS: double scratch[nw][cpw * (n*LD + M + n)] (LD = 2M, 2M+1 for Algorithm 1) | double WdT[(n-A) * KP] | double xs[n]
 //              | double alpha_s[K] | double beta_s[N]
 //              | int avail[N] | int F[N] | int Fpos[N] | int votes[N] | int sel[N] | int n
 template <bool HOMOG>
@@ -709,7 +775,7 @@ __global__ void decode_byzantine_general_kernel(const float *__restrict__ preds,
     const int M = K + A;
     const int nF_cap = n_cap - A;
     const int nw = blockDim.x / kWave;
-    const int wave_doubles = cpw * (n_cap * 2 * M + M + n_cap);
+    const int wave_doubles = cpw * (n_cap * (HOMOG ? 2 * M + 1 : 2 * M) + M + n_cap);
 
     double *scratch = lds_d;
     double *WdT = scratch + static_cast<size_t>(nw) * wave_doubles;
@@ -811,7 +877,7 @@ int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *
     if (cpw < 1) cpw = 1;
     if (cpw > C) cpw = static_cast<int>(C);
     const size_t fixed = sizeof(double) * (static_cast<size_t>(n - A) * KP + n + K + N) + sizeof(int) * (5 * static_cast<size_t>(N) + 2);
-    const size_t per_class = sizeof(double) * (static_cast<size_t>(n) * 2 * M + M + n);
+    const size_t per_class = sizeof(double) * (static_cast<size_t>(n) * (homogeneous ? 2 * M + 1 : 2 * M) + M + n);
     const size_t budget = 64 * 1024;
     while (cpw > 1 && fixed + cpw * per_class > budget) --cpw;
     const size_t per_wave = cpw * per_class;
