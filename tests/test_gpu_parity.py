@@ -1118,9 +1118,10 @@ def test_random_shapes_all_entry_points(gpu):
 
 
 def test_random_byzantine_shapes(gpu):
-    # every register tile of the projected kernel and the general kernel behind it: K + A up to 16, up to 64
-    # available workers, odd and even counts, per-group counts, one to a few hundred classes; exactly rational
-    # data (linear model), so the planted adversaries must come back wherever float32 data still separate them
+    # every register tile of the projected kernel and the general kernel behind it, and Algorithm 1's locator on the
+    # same inputs: K + A up to 16, up to 64 available workers, odd and even counts, per-group counts, one to a few
+    # hundred classes; exactly rational data (linear model), so the planted adversaries must come back wherever
+    # float32 data still separate them
     import os
     torch, binding, dev = gpu
     rng = np.random.default_rng(int(os.environ.get("APPROXIFER_FUZZ_SEED", "909868")))
@@ -1156,25 +1157,25 @@ def test_random_byzantine_shapes(gpu):
             adv_true[g] = np.sort(rng.permutation(avail)[:A])
             Y[g, adv_true[g]] += (10 * (clean.std() + 1e-3) * rng.standard_normal((A, C))).astype(np.float32)
         S_arg = binding.S_FROM_MASK if ragged else S
-        out, adv, st = binding.approxifer_decode_byzantine(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev),
-                                                           alpha, beta, S_arg, A, mode)
-        ref, adv_ref, st_ref = orc.decode_byzantine(Y, mask, alpha, beta, None if ragged else S, A, mode)
-        out, adv, st = out.cpu().numpy(), adv.cpu().numpy(), st.cpu().numpy()
-        assert np.array_equal(st, st_ref) and np.all(st == 0)
-        same = np.all(adv == adv_ref, axis=1)
-        decisive = np.zeros(G, bool)
-        for g in range(G):
-            _, _, counts = orc.locate(Y[g], np.nonzero(mask[g])[0], beta, K, A)
-            top = np.sort(counts)[::-1]
-            decisive[g] = top[A - 1] - top[A] >= 2
-        assert np.all(same[decisive]), (adv, adv_ref)
-        if M <= 12 and C >= 7:
-            assert np.array_equal(adv[decisive], adv_true[decisive])
-        for g in range(G):                                   # decode parity over the kernel's own survivor set
-            m2 = mask[g:g + 1].copy()
-            m2[0, adv[g]] = 0
-            if not well_posed(alpha, beta, m2, mode)[0]:
-                continue
-            ref_g, _ = orc.decode(Y[g:g + 1], m2, alpha, beta, None, mode)
-            assert group_err(out[g:g + 1], ref_g).max() <= TOL
-
+        for locator, entry in ((orc.LOCATOR_ALGORITHM_2, binding.approxifer_decode_byzantine),
+                               (orc.LOCATOR_ALGORITHM_1, binding.approxifer_decode_byzantine_homogeneous)):
+            out, adv, st = entry(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev), alpha, beta, S_arg, A, mode)
+            ref, adv_ref, st_ref = orc.decode_byzantine(Y, mask, alpha, beta, None if ragged else S, A, mode, locator)
+            out, adv, st = out.cpu().numpy(), adv.cpu().numpy(), st.cpu().numpy()
+            assert np.array_equal(st, st_ref) and np.all(st == 0)
+            same = np.all(adv == adv_ref, axis=1)
+            decisive = np.zeros(G, bool)
+            for g in range(G):
+                _, _, counts = orc.locate(Y[g], np.nonzero(mask[g])[0], beta, K, A, locator)
+                top = np.sort(counts)[::-1]
+                decisive[g] = top[A - 1] - top[A] >= 2
+            assert np.all(same[decisive]), (locator, adv, adv_ref)
+            if M <= 12 and C >= 7:
+                assert np.array_equal(adv[decisive], adv_true[decisive]), locator
+            for g in range(G):                               # decode parity over the kernel's own survivor set
+                m2 = mask[g:g + 1].copy()
+                m2[0, adv[g]] = 0
+                if not well_posed(alpha, beta, m2, mode)[0]:
+                    continue
+                ref_g, _ = orc.decode(Y[g:g + 1], m2, alpha, beta, None, mode)
+                assert group_err(out[g:g + 1], ref_g).max() <= TOL
