@@ -977,6 +977,8 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed(gpu):
     outb = torch.zeros((G, Kb, Cb), dtype=torch.float32, device=dev)
     advb = torch.zeros((G, Ab), dtype=torch.int32, device=dev)
     stb = torch.zeros((G,), dtype=torch.int32, device=dev)
+    outh = torch.zeros((G, Kb, Cb), dtype=torch.float32, device=dev)
+    advh = torch.zeros((G, Ab), dtype=torch.int32, device=dev)
 
     def calls():
         binding.approxifer_encode(q, alpha, beta, coded=coded)
@@ -984,6 +986,8 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed(gpu):
         binding.approxifer_decode(preds, mask, alpha, beta, S, 1, out=out, status=st)
         binding.approxifer_decode_top1(preds, mask, alpha, beta, S, 1, top1=top1, status=st, want_score=False)
         binding.approxifer_decode_byzantine(predsb, maskb, alphab, betab, Sb, Ab, 1, out=outb, adv=advb, status=stb)
+        binding.approxifer_decode_byzantine_homogeneous(predsb, maskb, alphab, betab, Sb, Ab, 1, out=outh, adv=advh,
+                                                        status=stb)
 
     def fresh_inputs(seed):
         r = np.random.default_rng(seed)
@@ -1019,6 +1023,9 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed(gpu):
         refb, adv_ref, _ = orc.decode_byzantine(Yb, mb, alphab, betab, Sb, Ab, 1)
         assert np.array_equal(advb.cpu().numpy(), adv_ref)
         assert group_err(outb.cpu().numpy(), refb).max() <= TOL
+        refh, adv_refh, _ = orc.decode_byzantine(Yb, mb, alphab, betab, Sb, Ab, 1, orc.LOCATOR_ALGORITHM_1)
+        assert np.array_equal(advh.cpu().numpy(), adv_refh)
+        assert group_err(outh.cpu().numpy(), refh).max() <= TOL
 
     first = fresh_inputs(1)
     upload(first)
@@ -1034,7 +1041,7 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed(gpu):
     for seed in (2, 3, 4):                                  # replays with new contents, eager work in between
         inp = fresh_inputs(seed)
         upload(inp)
-        for t in (coded, out, outb):
+        for t in (coded, out, outb, outh):
             t.zero_()
         torch.cuda.synchronize()
         graph.replay()
