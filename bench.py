@@ -323,7 +323,7 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="wall-time budget of the CPU-oracle leg")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported"
+        print("bench.py: the library runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported"
               % args.gpus, file=sys.stderr)
         sys.exit(2)
 

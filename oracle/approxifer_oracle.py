@@ -21,8 +21,8 @@ are widened exactly and all arithmetic is float64.
 Pins: the weights, the encoder, the decoder and the locator are pinned in
 tests/test_oracle_*.py by exact-rational evaluation, closed forms, invariants
 and brute force.  The tie-break conventions of `pick_smallest` and `vote`
-(equal magnitudes / equal counts -> smaller worker index first) are this
-build's reading, the paper is silent on them: parity unpinned for those two
+(equal magnitudes / equal counts -> smaller worker index first) are a reading
+of our own, the paper is silent on them: parity unpinned for those two
 conventions.  The behaviour of the least-squares fit on data that is not exactly
 rational (a non-linear hosted model) is fixed only as "ordinary least squares":
 parity unpinned beyond that.
@@ -180,7 +180,7 @@ def wait_mask(arrival, wait_for):
     """Survivor mask from arrival times: per group the wait_for workers that answer first get 1.
     Section 3, "ApproxIFER Decoding", step 1 (the decoder waits for the fastest K workers, or
     2(K+E) of them when E may be adversarial).  A non-finite time means the worker never answers.
-    Equal times: smaller worker index first (this build's reading; the paper is silent).
+    Equal times: smaller worker index first (a reading of our own; the paper is silent).
     Returns (mask [G, W] uint8, count [G] int32)."""
     arrival = np.asarray(arrival, dtype=np.float64)
     G, W = arrival.shape
