@@ -25,7 +25,10 @@ and brute force.  The tie-break conventions of `pick_smallest` and `vote`
 of our own, the paper is silent on them: parity unpinned for those two
 conventions.  The behaviour of the least-squares fit on data that is not exactly
 rational (a non-linear hosted model) is fixed only as "ordinary least squares":
-parity unpinned beyond that.
+parity unpinned beyond that.  Algorithm 1's homogeneous system is read as "the
+unit coefficient vector of least residual" (smallest right singular vector); on
+exactly rational data every reading gives the same null vector and the pins
+hold it there, on other data: parity unpinned beyond that reading.
 """
 from __future__ import annotations
 
