@@ -147,8 +147,9 @@ int approxifer_decode_byzantine(const float *d_preds, const uint8_t *d_mask, flo
  * M = K + A, P and Q both of degree M-1, the coefficient vector (P_0..P_{M-1}, Q_0..Q_{M-1})
  * is the unit vector minimising sum_i (P(x_i) - y_i Q(x_i))^2 over the available workers: the
  * right singular vector of the smallest singular value of the n x 2M matrix of the
- * homogeneous system (float64 Householder QR, then one-sided Jacobi rotations on the
- * triangular factor until every pair of columns is orthogonal to rounding).  a_i = Q(x_i) is
+ * homogeneous system (float64 Householder QR, then inverse iteration on the triangular
+ * factor and, for a class whose iteration does not settle, one-sided Jacobi rotations
+ * until every pair of its columns is orthogonal to rounding).  a_i = Q(x_i) is
  * defined up to one factor, which the order of the |a_i| does not see.  Unlike Algorithm 2
  * this locator can find a worker whose node is exactly 0.  It costs a singular value
  * decomposition per class where Algorithm 2 costs a least-squares solve.

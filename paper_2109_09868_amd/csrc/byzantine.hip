@@ -520,6 +520,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
 //  1. Inverse iteration z <- (R^T R)^-1 z, two triangular solves per round.  When the data are rational up to
 //     rounding -- the case the locator is built for -- the smallest singular value is orders of magnitude below the
 //     next and two to four rounds settle z: successive iterates within 1e-11, or no longer approaching each other.
+//     A steady slow decay (two close smallest singular values) is extrapolated to its limit, Aitken's way.
 //  2. Classes that have not settled after kInverseRounds (no gap: data that fit no rational function; or a zero on
 //     the diagonal) get the full answer from one-sided Jacobi on G = R^T: lane j owns column j of G, which is row j
 //     of mat; a step rotates W2/2 disjoint pairs of columns (round-robin pairing, W2 - 1 steps per sweep) until all
@@ -539,6 +540,7 @@ __device__ __forceinline__ void homogeneous_q(double *mat, int LD, double *coef,
     const double rd = 1.0 / own[j];                     // a zero on the diagonal: nothing settles, Jacobi takes the class
     double z = 1.0 + 0.25 * (j % 3);
     double dd_prev = __builtin_inf();
+    int since_jump = 0;
     bool settled = false;
     for (int round = 0; round < kInverseRounds; ++round) {
         double s = z;                                     // R^T w = z, forward
@@ -569,10 +571,23 @@ __device__ __forceinline__ void homogeneous_q(double *mat, int LD, double *coef,
         double dd = 0.0;
         for (int t = 0; t < W2; ++t) dd += key[t];
         __builtin_amdgcn_wave_barrier();
-        z = zn;
+        const double dd_before = dd_prev;
         // settled: the step is below 1e-11, or it has stopped shrinking at the level rounding allows (false for NaN)
-        settled = dd <= 1e-22 || (dd_prev <= 1e-16 && dd >= 0.25 * dd_prev);
+        settled = settled || dd <= 1e-22 || (dd_prev <= 1e-16 && dd >= 0.25 * dd_prev);
+        z = zn;
         dd_prev = dd;
+        // Two close smallest singular values leave one slowly decaying error mode: z_k = v + r^k e.  Once the steps are
+        // small and shrink by a steady factor r, jump to the limit of that sequence, z + r/(1-r) (z - z_previous); the
+        // next two steps are no longer part of it, so at most every third round.
+        ++since_jump;
+        if (!settled && since_jump >= 3 && dd < 1e-4 && dd_before < __builtin_inf()) {
+            const double r = sqrt(dd / dd_before);
+            if (r > 0.05 && r < 0.97) {
+                z = fma(r / (1.0 - r), dz, zn);
+                since_jump = 0;
+                dd_prev = __builtin_inf();
+            }
+        }
         if (__all((settled || !live) ? 1 : 0)) break;
     }
     if (live && settled && j >= M) coef[j - M] = z;
