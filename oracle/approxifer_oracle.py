@@ -23,9 +23,10 @@ tests/test_oracle_*.py by exact-rational evaluation, closed forms, invariants
 and brute force.  The tie-break conventions of `pick_smallest` and `vote`
 (equal magnitudes / equal counts -> smaller worker index first) are a reading
 of our own, the paper is silent on them: parity unpinned for those two
-conventions.  The behaviour of the least-squares fit on data that is not exactly
-rational (a non-linear hosted model) is fixed only as "ordinary least squares":
-parity unpinned beyond that.  Algorithm 1's homogeneous system is read as "the
+conventions.  On data that is not exactly rational (a non-linear hosted model)
+Algorithm 2's system has no solution; "solve" is read as ordinary least squares,
+and under that reading the fit is pinned to the exact minimiser (normal equations
+over rationals on small systems); the reading itself is ours: parity unpinned.  Algorithm 1's homogeneous system is read as "the
 unit coefficient vector of least residual" (smallest right singular vector); on
 exactly rational data every reading gives the same null vector and the pins
 hold it there, on other data: parity unpinned beyond that reading.

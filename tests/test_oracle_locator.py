@@ -1,5 +1,6 @@
 """Pins for the oracle's adversary locator (Algorithm 2) and Byzantine decoder (no GPU)."""
 import itertools
+from fractions import Fraction
 
 import numpy as np
 import pytest
@@ -95,6 +96,45 @@ def test_locator_agrees_with_brute_force_subset_search(K, A, W):
         assert set(np.argsort(np.abs(a))[:A]) == set(sub)
         a1 = orc.locator_values_homogeneous(x, y, K, A)
         assert set(np.argsort(np.abs(a1))[:A]) == set(sub)
+
+
+def _exact_least_squares(rows, rhs):
+    """argmin ||A s - b||_2 in exact rational arithmetic: the normal equations A^T A s = A^T b solved
+    by Gauss-Jordan elimination over Fractions (A of full column rank)."""
+    m = len(rows[0])
+    N = [[sum(r[i] * r[j] for r in rows) for j in range(m)] + [sum(r[i] * b for r, b in zip(rows, rhs))]
+         for i in range(m)]
+    for i in range(m):
+        piv = next(r for r in range(i, m) if N[r][i] != 0)
+        N[i], N[piv] = N[piv], N[i]
+        N[i] = [v / N[i][i] for v in N[i]]
+        for r in range(m):
+            if r != i and N[r][i] != 0:
+                N[r] = [a - N[r][i] * b for a, b in zip(N[r], N[i])]
+    return [N[i][m] for i in range(m)]
+
+
+@pytest.mark.parametrize("K,A,n,seed", [(1, 1, 4, 0), (1, 1, 6, 1), (2, 1, 6, 2), (2, 1, 9, 3), (1, 2, 7, 4), (3, 1, 8, 5)])
+def test_locator_values_are_the_exact_least_squares_solution_on_inconsistent_data(K, A, n, seed):
+    # data that lie on no rational function: Algorithm 2's system is inconsistent and "solving" it means least
+    # squares.  Rational nodes and values make the minimiser computable exactly (normal equations over Fractions);
+    # the oracle's a_i = Q(x_i) must be that minimiser's, and so must the order of the |a_i|.
+    rng = np.random.default_rng(seed)
+    M = K + A
+    xs = sorted({Fraction(int(v), 8) for v in rng.integers(-8, 9, size=4 * n) if v != 0}, reverse=True)[:n]
+    assert len(xs) == n
+    ys = [Fraction(int(v), 16) for v in rng.integers(-40, 41, size=n)]
+    rows = [[x ** k for k in range(M)] + [-y * x ** k for k in range(1, M)] for x, y in zip(xs, ys)]
+    sol = _exact_least_squares(rows, ys)
+    Q = [Fraction(1)] + sol[M:]
+    a_exact = [sum(q * x ** k for k, q in enumerate(Q)) for x in xs]
+    a = orc.locator_values(np.array([float(x) for x in xs]), np.array([float(y) for y in ys]), K, A)
+    want = np.array([float(v) for v in a_exact])
+    assert np.max(np.abs(a - want)) <= 1e-9 * max(1.0, np.max(np.abs(want)))
+    order_exact = sorted(range(n), key=lambda i: (abs(a_exact[i]), i))[:A]
+    gaps = sorted(abs(v) for v in a_exact)
+    if gaps[A] - gaps[A - 1] > Fraction(1, 10 ** 6):       # the pick is decided by more than rounding
+        assert set(orc.pick_smallest(a, np.arange(n), A).tolist()) == set(order_exact)
 
 
 def test_zero_node_cannot_be_located_with_q0_fixed():
