@@ -137,6 +137,38 @@ def test_locator_values_are_the_exact_least_squares_solution_on_inconsistent_dat
         assert set(orc.pick_smallest(a, np.arange(n), A).tolist()) == set(order_exact)
 
 
+@pytest.mark.parametrize("K,A,seed", [(2, 1, 0), (3, 1, 1), (2, 2, 2), (3, 2, 3), (4, 1, 4)])
+def test_both_locators_return_q_times_the_error_locator_polynomial(K, A, seed):
+    # Appendix A: with y_i = p(x_i)/q(x_i) off the adversaries, P = p Lambda and Q = q Lambda, Lambda(x) =
+    # prod (1 - x/x_i) over the adversaries, satisfy every equation exactly, and at the minimum worker count
+    # they are the only solution up to a factor.  So a_i = Q(x_i) is known in closed form: q(x_i) Lambda(x_i)
+    # (divided by q(0) for Algorithm 2, whose Q(0) = 1; up to one factor for Algorithm 1).
+    rng = np.random.default_rng(seed)
+    M = K + A
+    n = 2 * M
+    xs = sorted({Fraction(int(v), 16) for v in rng.integers(-16, 17, size=6 * n) if v != 0}, reverse=True)[:n]
+    assert len(xs) == n
+    p = [Fraction(int(v), 4) for v in rng.integers(-8, 9, size=K)]
+    q = [Fraction(1)] + [Fraction(int(v), 32) for v in rng.integers(-3, 4, size=K - 1)]
+    ev = lambda c, x: sum(ck * x ** k for k, ck in enumerate(c))
+    assert all(ev(q, x) > Fraction(1, 2) for x in xs)
+    bad = sorted(rng.permutation(n)[:A].tolist())
+    lam = lambda x: np.prod([1 - x / xs[i] for i in bad]) if bad else Fraction(1)
+    ys = [ev(p, x) / ev(q, x) for x in xs]
+    for i in bad:
+        ys[i] += Fraction(int(rng.integers(1, 6)), 2) * (1 if rng.integers(0, 2) else -1)
+    a_exact = np.array([float(ev(q, x) * lam(x) / q[0]) for x in xs])
+    x_f = np.array([float(x) for x in xs])
+    y_f = np.array([float(y) for y in ys])              # sixteenths and small rationals: a few are inexact in binary
+    a2 = orc.locator_values(x_f, y_f, K, A)
+    assert np.max(np.abs(a2 - a_exact)) <= 1e-7 * np.max(np.abs(a_exact))
+    a1 = orc.locator_values_homogeneous(x_f, y_f, K, A)
+    good = [i for i in range(n) if i not in bad]
+    scale = a1[good[0]] / a_exact[good[0]]
+    assert np.max(np.abs(a1 / scale - a_exact)) <= 1e-7 * np.max(np.abs(a_exact))
+    assert np.all(np.abs(a_exact[bad]) == 0.0)
+
+
 def test_zero_node_cannot_be_located_with_q0_fixed():
     # Algorithm 2 fixes Q(0) = 1 while the error locator Lambda(x) = prod (1 - x/x_i) of Appendix A
     # needs x_i != 0.  With an odd number of workers the middle node is 0: a_i = Q(0) = 1 there, so
