@@ -534,10 +534,19 @@ __device__ __forceinline__ void homogeneous_q(double *mat, int LD, double *coef,
                                               bool live) {
     double *own = mat + j * LD;
     // ---- 1. inverse iteration; R mirrored into the lower triangle so that both solves read rows ----------------
-    if (live)
+    double colsq = 0.0;                                   // |column j of R|^2 = |column j of the system|^2
+    for (int t = 0; t <= j; ++t) colsq = fma(mat[t * LD + j], mat[t * LD + j], colsq);
+    if (live) {
         for (int t = 0; t < j; ++t) own[t] = mat[t * LD + j];
+        // An exactly singular system (K = 1: the good workers return one and the same number) leaves a zero on the
+        // diagonal.  Its null vector is the answer, but a zero pivot stops the solves and, in the Jacobi fallback, a
+        // zero singular value wipes out its own vector (the columns there are sigma_i v_i).  A pivot below 1e-24 of
+        // its column is raised to that: the null vector moves by 1e-24, far below the rounding of everything else.
+        const double floor = 1e-24 * sqrt(colsq);
+        if (fabs(own[j]) < floor) own[j] = own[j] < 0.0 ? -floor : floor;
+    }
     __builtin_amdgcn_wave_barrier();
-    const double rd = 1.0 / own[j];                     // a zero on the diagonal: nothing settles, Jacobi takes the class
+    const double rd = 1.0 / own[j];                     // still zero (a zero column): nothing settles, nor matters
     double z = 1.0 + 0.25 * (j % 3);
     double dd_prev = __builtin_inf();
     int since_jump = 0;

@@ -674,6 +674,31 @@ def test_homogeneous_locator_exactly_rational_predictions(gpu, K, A, S, N, C, G)
     assert group_err(out, ref).max() <= TOL
 
 
+def test_homogeneous_locator_exactly_singular_systems(gpu):
+    # K = 1 is replication: every honest worker returns the same float, the homogeneous system is singular to the
+    # last bit (smallest singular value 0 or 1e-17) and its null vector is exact.  The factorisation then leaves a
+    # zero, or rounding noise, on the diagonal of R: the planted workers must still come back, as from the oracle.
+    K, N, C, G = 1, 10, 2, 400
+    rng = np.random.default_rng(108)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    for A, S in ((2, 2), (1, 0), (3, 2)):
+        X = rng.uniform(0, 1, (G, K, 48))
+        clean = (orc.encode(X, alpha, beta) @ (rng.standard_normal((48, C)) / 7)).astype(np.float32)
+        assert np.all(clean == clean[:, :1, :])
+        mask = np.zeros((G, N), np.uint8)
+        adv_true = np.zeros((G, A), np.int32)
+        Y = clean.copy()
+        for g in range(G):
+            avail = np.sort(rng.permutation(N)[: N - S])
+            mask[g, avail] = 1
+            adv_true[g] = np.sort(rng.permutation(avail)[:A])
+            Y[g, adv_true[g]] += (10 * (clean.std() + 1e-3) * rng.standard_normal((A, C))).astype(np.float32)
+        out, adv, st, ref, adv_ref, st_ref = _hom_both(gpu, Y, mask, alpha, beta, S, A)
+        assert np.all(st == 0)
+        assert np.array_equal(adv, adv_true) and np.array_equal(adv_ref, adv_true)
+        assert group_err(out, ref).max() <= TOL
+
+
 def test_homogeneous_locator_finds_the_worker_on_node_zero(gpu):
     # an odd number of workers puts the middle worker on the node 0, where Algorithm 2's Q equals 1 by construction
     # (it can only be picked there if |Q| happens to exceed 1 on every other node); Algorithm 1's Q vanishes on it
