@@ -112,7 +112,21 @@ def cpu_baseline(w, alpha, beta, budget_s, sign_mode):
         cpu += (c1.user - c0.user) + (c1.system - c0.system)
         done = g1
     wall = t_enc + t_dec
+    # the Byzantine decoder of the oracle, both locators, on the first 64 groups of the byzantine workload
+    wb = syn.scaled(syn.WORKLOADS["byzantine"], G=64)
+    ab, bb = orc.chebyshev_nodes(wb.K, wb.W)
+    clean = syn.model_apply(wb, syn.model_params(wb), orc.encode(syn.queries(wb), ab, bb))
+    mb = syn.masks(wb)
+    Yb = syn.corrupt(wb, clean, syn.adversaries(wb, mb))
+    byz = {}
+    for name, locator in (("algorithm2", orc.LOCATOR_ALGORITHM_2), ("algorithm1", orc.LOCATOR_ALGORITHM_1)):
+        t0 = time.perf_counter()
+        orc.decode_byzantine(Yb, mb, ab, bb, wb.S, wb.A, sign_mode, locator)
+        byz[name] = wb.G * wb.K / (time.perf_counter() - t0)
     return {
+        "byzantine_decode_predictions_per_s": byz["algorithm2"],
+        "byzantine_decode_algorithm1_predictions_per_s": byz["algorithm1"],
+        "byzantine_sample": "first 64 of 2048 groups of the byzantine workload (K=8, A=2, 20 of 24 workers, C=10)",
         "value": done * w.W / wall,
         "unit": "coded queries/s",
         "cores": max(1, int(round(cpu / wall))),
