@@ -20,7 +20,11 @@ def main():
 
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="imagenet", choices=sorted(syn.WORKLOADS))
-    ap.add_argument("--op", default="encode", choices=["encode", "decode", "decode_top1", "decode_byzantine"])
+    ap.add_argument("--op", default="encode", choices=["encode", "decode", "decode_top1", "decode_byzantine",
+                                                         "decode_byzantine_homogeneous"])
+    ap.add_argument("--linear-model", action="store_true",
+                    help="Byzantine ops: predictions = a linear map of the coded queries plus noise on A workers "
+                         "(exactly rational data, the case the locators are built for) instead of plain noise")
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--sign-mode", type=int, default=0)
     args = ap.parse_args()
@@ -48,9 +52,17 @@ def main():
         else:
             if w.A < 1:
                 raise SystemExit("workload %s has no adversaries" % w.name)
+            if args.linear_model:
+                q = torch.rand((w.G, w.K, w.D), dtype=torch.float32, device=dev, generator=gen)
+                lin = torch.randn((w.D, w.C), dtype=torch.float32, device=dev, generator=gen) / w.D ** 0.5
+                preds = (binding.approxifer_encode(q, alpha, beta).reshape(-1, w.D) @ lin).reshape(w.G, w.W, w.C)
+                bad = torch.from_numpy(syn.adversaries(w, mask_h)).to(dev).long()           # [G, A]
+                noise = 10 * preds.std() * torch.randn((w.G, w.A, w.C), dtype=torch.float32, device=dev, generator=gen)
+                preds = preds.scatter_add(1, bad[:, :, None].expand(-1, -1, w.C), noise).contiguous()
             adv = torch.empty((w.G, w.A), dtype=torch.int32, device=dev)
-            fn = lambda: binding.approxifer_decode_byzantine(preds, mask, alpha, beta, w.S, w.A, args.sign_mode, out=out,
-                                                             adv=adv, status=st)
+            entry = (binding.approxifer_decode_byzantine if args.op == "decode_byzantine"
+                     else binding.approxifer_decode_byzantine_homogeneous)
+            fn = lambda: entry(preds, mask, alpha, beta, w.S, w.A, args.sign_mode, out=out, adv=adv, status=st)
     for _ in range(args.reps):
         fn()
     torch.cuda.synchronize()
