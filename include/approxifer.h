@@ -128,7 +128,10 @@ int approxifer_decode(const float *d_preds, const uint8_t *d_mask, float *d_out,
  *
  *   d_adv     [G][A] int32, device, written: located workers in ascending order
  *   other arguments as approxifer_decode(); groups with a bad mask leave d_out and
- *   d_adv rows untouched.
+ *   d_adv rows untouched.  While the call runs, the d_out rows of the other groups also
+ *   serve as working storage (with few groups and many classes several workgroups share
+ *   a group and pool their votes there); they hold the result when the work enqueued by
+ *   the call has completed.
  * Requires A >= 1, N - S >= 2 (K + A) (Section 3, eq. (3), the decoding condition) and
  * N - S <= APPROXIFER_MAX_AVAIL_BYZ.  With S = APPROXIFER_S_FROM_MASK a group is decoded when its
  * own number of available workers n satisfies 2 (K + A) <= n <= APPROXIFER_MAX_AVAIL_BYZ and gets

@@ -396,7 +396,7 @@ template <int NB, int RM>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 && NB <= 32 ? 3 : 2))) void decode_byzantine_proj_kernel(
     const float *__restrict__ preds, const uint8_t *__restrict__ mask, float *__restrict__ out,
     int32_t *__restrict__ adv, int32_t *__restrict__ status, int K, int N, int S, int A, int64_t C, int64_t Cv,
-    int vec4, int sign_mode, int n_cap, int cw_log2, const Nodes nodes) {
+    int vec4, int sign_mode, int n_cap, int cw_log2, int splits, const Nodes nodes) {
     extern __shared__ __align__(16) double lds_d[];
     const int KP = round_up4(K);
     const int M = K + A;
@@ -417,7 +417,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
     int *sel = votes + N;
     int *n_sh = sel + N;
 
-    const int64_t g = blockIdx.x;
+    // splits > 1: `splits` workgroups share a group, workgroup `part` taking the class tiles part, part + splits, ..
+    const int64_t g = blockIdx.x / splits;
+    const int part = static_cast<int>(blockIdx.x - g * splits);
     const int wv = wave_id();
     const int tid = threadIdx.x;
     const float *pg = preds + static_cast<size_t>(g) * N * C;
@@ -438,13 +440,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
 
     // first class tile: the loads are issued now and land in LDS after the shared factorisation
     constexpr int kPrefetch = 8;
+    const int64_t cb_first = static_cast<int64_t>(part) * CW;
     const int slots = NB * CW;                            // slot = (row r, class c) = (slot >> cw_log2, slot & (CW-1))
     float pf[kPrefetch];
 #pragma unroll
     for (int u = 0; u < kPrefetch; ++u) {
         const int slot = tid + u * blockDim.x;
         const int r = slot >> cw_log2, c = slot & (CW - 1);
-        pf[u] = (slot < slots && r < n && c < C) ? pg[static_cast<size_t>(avail[r]) * C + c] : 0.0f;
+        pf[u] = (slot < slots && r < n && cb_first + c < C) ? pg[static_cast<size_t>(avail[r]) * C + cb_first + c] : 0.0f;
     }
 
     // powers of the available workers' nodes, x^e by repeated multiplication; rows past n are zero
@@ -460,8 +463,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
     __syncthreads();
     if (wv == 0) shared_complement_basis<NB, RM>(Pw, n, M, Ush);
 
-    for (int64_t cb = 0; cb < C; cb += CW) {              // class tiles
-        if (cb == 0) {
+    for (int64_t cb = cb_first; cb < C; cb += static_cast<int64_t>(splits) * CW) {   // class tiles of this part
+        if (cb == cb_first) {
 #pragma unroll
             for (int u = 0; u < kPrefetch; ++u) {
                 const int slot = tid + u * blockDim.x;
@@ -469,7 +472,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
             }
             for (int slot = tid + kPrefetch * blockDim.x; slot < slots; slot += blockDim.x) {
                 const int r = slot >> cw_log2, c = slot & (CW - 1);
-                Ysh[slot] = (r < n && c < C) ? pg[static_cast<size_t>(avail[r]) * C + c] : 0.0f;
+                Ysh[slot] = (r < n && cb + c < C) ? pg[static_cast<size_t>(avail[r]) * C + cb + c] : 0.0f;
             }
         } else {
             __syncthreads();                              // every wave is done with the previous tile
@@ -487,6 +490,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
     __syncthreads();
 
     float *og = out + static_cast<size_t>(g) * K * C;
+    if (splits > 1) {
+        // The parts of a group meet in the first N+1 words of the group's own output rows (cleared by
+        // clear_group_votes_kernel, overwritten by the decode below): N vote counters and an arrival counter.  No part
+        // waits for another: whichever arrives last holds every vote and finishes the group.
+        // These words are touched by device-scope atomics only, which act where all workgroups of the device see
+        // them.  A part's additions have been carried out once their old values are back; only then does it count
+        // itself in: no cache write-back or invalidation (a fence) is needed, and none of the part's other
+        // memory traffic has to be ordered with this.
+        int *gvotes = reinterpret_cast<int *>(og);
+        int seen = 0;
+        for (int i = tid; i < N; i += blockDim.x)
+            if (votes[i] != 0) seen |= __hip_atomic_fetch_add(&gvotes[i], votes[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("" ::"v"(seen));                     // the returned values are waited for
+        __syncthreads();
+        if (tid == 0)
+            n_sh[1] = __hip_atomic_fetch_add(&gvotes[N], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == splits - 1 ? 1 : 0;
+        __syncthreads();
+        if (n_sh[1] == 0) return;
+        for (int i = tid; i < N; i += blockDim.x)
+            votes[i] = __hip_atomic_load(&gvotes[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+    }
     const bool staged = C <= CW;                          // the one tile holds every prediction of the group
     select_adversaries(adv + g * A, avail, n, N, A, votes, sel, F, Fpos);
     const int nF = n - A;
@@ -841,6 +866,21 @@ __global__ void decode_byzantine_general_kernel(const float *__restrict__ preds,
                  alpha_s, beta_s, votes, sel, F, Fpos, WdT);
 }
 
+// Before a launch in which several workgroups share a group: zero the N+1 words at the head of every group's output
+// rows through which they meet.  Groups whose mask the decoder will reject keep their output untouched.
+__global__ void clear_group_votes_kernel(const uint8_t *__restrict__ mask, float *__restrict__ out, int64_t G, int K, int N,
+                                         int S, int M, int64_t C, int n_cap) {
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * (blockDim.x / kWave) + wave_id();
+    if (g >= G) return;
+    const int lane = lane_id();
+    const uint8_t *row = mask + g * N;
+    const int n = __popcll(__ballot(lane < N && row[lane] != 0)) + __popcll(__ballot(lane + kWave < N && row[lane + kWave] != 0));
+    const bool good = S < 0 ? (n >= 2 * M && n <= n_cap) : n == n_cap;
+    if (!good) return;
+    int *gvotes = reinterpret_cast<int *>(out + static_cast<size_t>(g) * K * C);
+    for (int i = lane; i <= N; i += kWave) gvotes[i] = 0;
+}
+
 template <int NB, int RM>
 int run_proj(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv, int32_t *d_status, int64_t G,
              int K, int N, int S, int A, int64_t C, int n_cap, bool vec4, const Nodes &nodes, int sign_mode,
@@ -860,9 +900,27 @@ int run_proj(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t 
                                          static_cast<size_t>(n_cap - A) * KP + K + N) +
                        sizeof(float) * (static_cast<size_t>(NB) * CW) + sizeof(int) * (5 * static_cast<size_t>(N) + 2);
     if (lds > 64 * 1024) return APPROXIFER_ERR_LIMIT;      // cannot happen inside the projected kernel's domain
-    const dim3 grid(static_cast<unsigned>(G)), block(nw * kWave);
+    // Few groups with many classes: one workgroup per group would leave most of the chip idle while each group walks
+    // through its class tiles.  Then several workgroups share a group, each repeating the shared factorisation and
+    // taking every splits-th tile, up to about 4096 waves in all.  From four tiles on: with fewer the repeated
+    // factorisation and the extra launch cost what the split saves (G = 512, C = 100: 51 us whole, 59 us split).
+    const int64_t tiles = (C + CW - 1) / CW;
+    int splits = 1;
+    if (tiles >= 4 && static_cast<int64_t>(K) * C >= N + 1) {
+        const int64_t want = 4096 / (G * nw);
+        splits = static_cast<int>(want < tiles ? want : tiles);
+        if (splits < 1) splits = 1;
+    }
+    if (G * splits > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    if (splits > 1) {
+        const int per_block = 4;
+        hipLaunchKernelGGL(clear_group_votes_kernel, dim3(static_cast<unsigned>((G + per_block - 1) / per_block)),
+                           dim3(per_block * kWave), 0, stream, d_mask, d_out, G, K, N, S, K + A, C, n_cap);
+        if (hipGetLastError() != hipSuccess) return APPROXIFER_ERR_LAUNCH;
+    }
+    const dim3 grid(static_cast<unsigned>(G * splits)), block(nw * kWave);
     hipLaunchKernelGGL((decode_byzantine_proj_kernel<NB, RM>), grid, block, lds, stream, d_preds, d_mask, d_out, d_adv,
-                       d_status, K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, n_cap, cw_log2, nodes);
+                       d_status, K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, n_cap, cw_log2, splits, nodes);
     return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
 }
 

@@ -489,6 +489,42 @@ def test_byzantine_exactly_rational_predictions(gpu, K, A, S, N, C, G):
     assert group_err(out, ref).max() <= TOL
 
 
+@pytest.mark.parametrize("K,A,N,C,G", [(8, 2, 24, 1000, 5), (12, 2, 30, 257, 6), (4, 1, 12, 4003, 3), (2, 1, 8, 20001, 2)])
+def test_byzantine_many_classes_few_groups(gpu, K, A, N, C, G):
+    # with few groups and four or more class tiles several workgroups share a group and meet through atomics in the
+    # group's own output rows: per-group straggler counts, a rejected mask among the groups (its rows and located
+    # workers must stay untouched), twice in a row on the same buffers
+    torch, binding, dev = gpu
+    rng = np.random.default_rng(K * 1000 + C)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    X = rng.uniform(0, 1, (G, K, 40))
+    clean = (orc.encode(X, alpha, beta) @ (rng.standard_normal((40, C)) / 6)).astype(np.float32)
+    M = K + A
+    mask = np.zeros((G, N), np.uint8)
+    Y = clean.copy()
+    adv_true = np.full((G, A), -7, np.int32)
+    for g in range(G):
+        cnt = 2 * M - 1 if g == 1 else int(rng.integers(2 * M, N + 1))     # group 1: one worker too few
+        avail = np.sort(rng.permutation(N)[:cnt])
+        mask[g, avail] = 1
+        if g != 1:
+            ok = avail[np.abs(beta[avail]) > 1e-9]
+            adv_true[g] = np.sort(rng.permutation(ok)[:A])
+            Y[g, adv_true[g]] += (10 * clean.std() * rng.standard_normal((A, C))).astype(np.float32)
+    ref, adv_ref, st_ref = orc.decode_byzantine(Y, mask, alpha, beta, None, A, 1)
+    out = torch.full((G, K, C), -3.0, dtype=torch.float32, device=dev)
+    adv = torch.full((G, A), -7, dtype=torch.int32, device=dev)
+    Yd, md = torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev)
+    for _ in range(2):
+        _, _, st = binding.approxifer_decode_byzantine(Yd, md, alpha, beta, binding.S_FROM_MASK, A, 1, out=out, adv=adv)
+        o, a, s = out.cpu().numpy(), adv.cpu().numpy(), st.cpu().numpy()
+        assert np.array_equal(s, st_ref) and s[1] == 1 and s.sum() == 1
+        assert np.all(o[1] == -3.0) and np.all(a[1] == -7)
+        good = s == 0
+        assert np.array_equal(a[good], adv_ref[good]) and np.array_equal(a[good], adv_true[good])
+        assert group_err(o[good], ref[good]).max() <= TOL
+
+
 @pytest.mark.parametrize("mode", [0, 1])
 def test_byzantine_sign_modes_and_bad_masks(gpu, mode):
     torch, binding, dev = gpu
@@ -984,7 +1020,7 @@ def test_wait_mask_feeds_the_decoder(gpu):
 def test_calls_can_be_captured_in_a_hip_graph_and_replayed(gpu):
     torch, binding, dev = gpu
     K, N, S, D, C, G = 8, 12, 4, 3072, 100, 32
-    Kb, Ab, Sb, Nb, Cb = 8, 2, 4, 24, 10
+    Kb, Ab, Sb, Nb, Cb = 8, 2, 4, 24, 300      # five class tiles: the Byzantine decoder's workgroups share groups
     rng = np.random.default_rng(123)
     alpha, beta = orc.chebyshev_nodes(K, N)
     alphab, betab = orc.chebyshev_nodes(Kb, Nb)
@@ -1170,7 +1206,7 @@ def test_random_byzantine_shapes(gpu):
         if N % 2 == 1:                                       # keep the zero node out (Q(0) = 1)
             N += 1
             S += 1
-        C = int(rng.choice([1, 2, 3, 4, 7, 10, 16, 17, 40, 65, 130]))
+        C = int(rng.choice([1, 2, 3, 4, 7, 10, 16, 17, 40, 65, 130, 260, 515]))
         G = int(rng.integers(1, 7))
         ragged = bool(rng.integers(0, 2)) and N > 2 * M
         mode = int(rng.integers(0, 2))
