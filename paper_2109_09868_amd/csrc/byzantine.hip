@@ -85,6 +85,32 @@ __device__ __forceinline__ void select_adversaries(int32_t *__restrict__ adv_g, 
     __syncthreads();
 }
 
+// Several workgroups share a group (few groups, many classes: each takes part of the classes).  They meet in the
+// first N+1 words of the group's own output rows -- N vote counters and an arrival counter, cleared by
+// clear_group_votes_kernel before the launch, overwritten by the decode afterwards.  These words are touched by
+// device-scope atomics only, which act where all workgroups of the device see them.  A part's additions have been
+// carried out once their old values are back; only then does it count itself in: no cache write-back or invalidation
+// (a fence) is needed, and none of the part's other memory traffic has to be ordered with this.  No part waits for
+// another: whichever arrives last gets every vote (into `votes`, LDS) and true, and finishes the group.
+// Called by the whole workgroup after a barrier that follows its last vote; ends with a barrier when it returns true.
+__device__ __forceinline__ bool pool_votes_last_arrival(float *og, int *votes, int N, int splits, int *flag) {
+    int *gvotes = reinterpret_cast<int *>(og);
+    const int tid = threadIdx.x;
+    int seen = 0;
+    for (int i = tid; i < N; i += blockDim.x)
+        if (votes[i] != 0) seen |= __hip_atomic_fetch_add(&gvotes[i], votes[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("" ::"v"(seen));                         // the returned values are waited for
+    __syncthreads();
+    if (tid == 0)
+        *flag = __hip_atomic_fetch_add(&gvotes[N], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == splits - 1 ? 1 : 0;
+    __syncthreads();
+    if (*flag == 0) return false;
+    for (int i = tid; i < N; i += blockDim.x)
+        votes[i] = __hip_atomic_load(&gvotes[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    return true;
+}
+
 // vec4: prediction rows are 16-byte aligned and C % 4 == 0, Cv = C / 4; else Cv = C.
 __device__ __forceinline__ void finish_group(const float *__restrict__ pg, float *__restrict__ og,
                                              int32_t *__restrict__ adv_g, const int *avail, int n, int N, int A, int K,
@@ -490,28 +516,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
     __syncthreads();
 
     float *og = out + static_cast<size_t>(g) * K * C;
-    if (splits > 1) {
-        // The parts of a group meet in the first N+1 words of the group's own output rows (cleared by
-        // clear_group_votes_kernel, overwritten by the decode below): N vote counters and an arrival counter.  No part
-        // waits for another: whichever arrives last holds every vote and finishes the group.
-        // These words are touched by device-scope atomics only, which act where all workgroups of the device see
-        // them.  A part's additions have been carried out once their old values are back; only then does it count
-        // itself in: no cache write-back or invalidation (a fence) is needed, and none of the part's other
-        // memory traffic has to be ordered with this.
-        int *gvotes = reinterpret_cast<int *>(og);
-        int seen = 0;
-        for (int i = tid; i < N; i += blockDim.x)
-            if (votes[i] != 0) seen |= __hip_atomic_fetch_add(&gvotes[i], votes[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("" ::"v"(seen));                     // the returned values are waited for
-        __syncthreads();
-        if (tid == 0)
-            n_sh[1] = __hip_atomic_fetch_add(&gvotes[N], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == splits - 1 ? 1 : 0;
-        __syncthreads();
-        if (n_sh[1] == 0) return;
-        for (int i = tid; i < N; i += blockDim.x)
-            votes[i] = __hip_atomic_load(&gvotes[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
-    }
+    if (splits > 1 && !pool_votes_last_arrival(og, votes, N, splits, n_sh + 1)) return;
     const bool staged = C <= CW;                          // the one tile holds every prediction of the group
     select_adversaries(adv + g * A, avail, n, N, A, votes, sel, F, Fpos);
     const int nF = n - A;
@@ -818,7 +823,7 @@ __global__ void decode_byzantine_general_kernel(const float *__restrict__ preds,
                                                 float *__restrict__ out, int32_t *__restrict__ adv,
                                                 int32_t *__restrict__ status, int K, int N, int S, int A, int64_t C,
                                                 int64_t Cv, int vec4, int sign_mode, int cpw, int n_cap,
-                                                const Nodes nodes) {
+                                                int splits, const Nodes nodes) {
     extern __shared__ __align__(16) double lds_d[];
     const int KP = round_up4(K);
     const int M = K + A;
@@ -838,7 +843,9 @@ __global__ void decode_byzantine_general_kernel(const float *__restrict__ preds,
     int *sel = votes + N;
     int *n_sh = sel + N;
 
-    const int64_t g = blockIdx.x;
+    // splits > 1: `splits` workgroups share a group, see pool_votes_last_arrival
+    const int64_t g = blockIdx.x / splits;
+    const int part = static_cast<int>(blockIdx.x - g * splits);
     const int wv = wave_id();
     const float *pg = preds + static_cast<size_t>(g) * N * C;
 
@@ -857,10 +864,11 @@ __global__ void decode_byzantine_general_kernel(const float *__restrict__ preds,
 
     for (int r = threadIdx.x; r < n; r += blockDim.x) xs[r] = beta_s[avail[r]];
     __syncthreads();
-    for (int64_t c0 = static_cast<int64_t>(wv) * cpw; c0 < C; c0 += static_cast<int64_t>(nw) * cpw)
+    for (int64_t c0 = (static_cast<int64_t>(part) * nw + wv) * cpw; c0 < C; c0 += static_cast<int64_t>(splits) * nw * cpw)
         locate_classes_wave<HOMOG>(pg, C, c0, cpw, avail, xs, n, M, A, scratch + static_cast<size_t>(wv) * wave_doubles,
                                    votes);
     __syncthreads();
+    if (splits > 1 && !pool_votes_last_arrival(out + static_cast<size_t>(g) * K * C, votes, N, splits, n_sh + 1)) return;
 
     finish_group(pg, out + static_cast<size_t>(g) * K * C, adv + g * A, avail, n, N, A, K, KP, C, Cv, vec4 != 0, sign_mode,
                  alpha_s, beta_s, votes, sel, F, Fpos, WdT);
@@ -969,13 +977,29 @@ int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *
     if (nw > static_cast<int>((budget - fixed) / per_wave)) nw = static_cast<int>((budget - fixed) / per_wave);
     if (nw < 1) nw = 1;
     const size_t lds = fixed + nw * per_wave;
-    const dim3 grid(static_cast<unsigned>(G)), block(nw * kWave);
+    // few groups, many classes: several workgroups share a group, as in the projected kernel (from four passes of a
+    // workgroup over its classes on)
+    const int64_t passes = (C + static_cast<int64_t>(nw) * cpw - 1) / (static_cast<int64_t>(nw) * cpw);
+    int splits = 1;
+    if (passes >= 4 && static_cast<int64_t>(K) * C >= N + 1) {
+        const int64_t want = 4096 / (G * nw);
+        splits = static_cast<int>(want < passes ? want : passes);
+        if (splits < 1) splits = 1;
+    }
+    if (G * splits > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    if (splits > 1) {
+        const int per_block = 4;
+        hipLaunchKernelGGL(clear_group_votes_kernel, dim3(static_cast<unsigned>((G + per_block - 1) / per_block)),
+                           dim3(per_block * kWave), 0, stream, d_mask, d_out, G, K, N, S, M, C, n);
+        if (hipGetLastError() != hipSuccess) return APPROXIFER_ERR_LAUNCH;
+    }
+    const dim3 grid(static_cast<unsigned>(G * splits)), block(nw * kWave);
     if (homogeneous)
         hipLaunchKernelGGL(decode_byzantine_general_kernel<true>, grid, block, lds, stream, d_preds, d_mask, d_out, d_adv,
-                           d_status, K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, cpw, n, nodes);
+                           d_status, K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, cpw, n, splits, nodes);
     else
         hipLaunchKernelGGL(decode_byzantine_general_kernel<false>, grid, block, lds, stream, d_preds, d_mask, d_out, d_adv,
-                           d_status, K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, cpw, n, nodes);
+                           d_status, K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, cpw, n, splits, nodes);
     return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
 }
 

@@ -489,12 +489,16 @@ def test_byzantine_exactly_rational_predictions(gpu, K, A, S, N, C, G):
     assert group_err(out, ref).max() <= TOL
 
 
-@pytest.mark.parametrize("K,A,N,C,G", [(8, 2, 24, 1000, 5), (12, 2, 30, 257, 6), (4, 1, 12, 4003, 3), (2, 1, 8, 20001, 2)])
-def test_byzantine_many_classes_few_groups(gpu, K, A, N, C, G):
-    # with few groups and four or more class tiles several workgroups share a group and meet through atomics in the
-    # group's own output rows: per-group straggler counts, a rejected mask among the groups (its rows and located
-    # workers must stay untouched), twice in a row on the same buffers
+@pytest.mark.parametrize("locator", [2, 1])
+@pytest.mark.parametrize("K,A,N,C,G", [(8, 2, 24, 1000, 5), (12, 2, 30, 257, 6), (4, 1, 12, 4003, 3), (2, 1, 8, 20001, 2),
+                                       (8, 2, 60, 300, 3)])
+def test_byzantine_many_classes_few_groups(gpu, K, A, N, C, G, locator):
+    # with few groups and many classes several workgroups share a group and meet through atomics in the group's own
+    # output rows (all three kernels: the last shape has up to 60 available workers, Algorithm 2's LDS kernel):
+    # per-group straggler counts, a rejected mask among the groups (its rows and located workers must stay
+    # untouched), twice in a row on the same buffers
     torch, binding, dev = gpu
+    entry = binding.approxifer_decode_byzantine if locator == 2 else binding.approxifer_decode_byzantine_homogeneous
     rng = np.random.default_rng(K * 1000 + C)
     alpha, beta = orc.chebyshev_nodes(K, N)
     X = rng.uniform(0, 1, (G, K, 40))
@@ -511,12 +515,12 @@ def test_byzantine_many_classes_few_groups(gpu, K, A, N, C, G):
             ok = avail[np.abs(beta[avail]) > 1e-9]
             adv_true[g] = np.sort(rng.permutation(ok)[:A])
             Y[g, adv_true[g]] += (10 * clean.std() * rng.standard_normal((A, C))).astype(np.float32)
-    ref, adv_ref, st_ref = orc.decode_byzantine(Y, mask, alpha, beta, None, A, 1)
+    ref, adv_ref, st_ref = orc.decode_byzantine(Y, mask, alpha, beta, None, A, 1, locator)
     out = torch.full((G, K, C), -3.0, dtype=torch.float32, device=dev)
     adv = torch.full((G, A), -7, dtype=torch.int32, device=dev)
     Yd, md = torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev)
     for _ in range(2):
-        _, _, st = binding.approxifer_decode_byzantine(Yd, md, alpha, beta, binding.S_FROM_MASK, A, 1, out=out, adv=adv)
+        _, _, st = entry(Yd, md, alpha, beta, binding.S_FROM_MASK, A, 1, out=out, adv=adv)
         o, a, s = out.cpu().numpy(), adv.cpu().numpy(), st.cpu().numpy()
         assert np.array_equal(s, st_ref) and s[1] == 1 and s.sum() == 1
         assert np.all(o[1] == -3.0) and np.all(a[1] == -7)
