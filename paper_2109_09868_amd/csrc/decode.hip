@@ -79,7 +79,7 @@ template <int VEC>
 __global__ void decode_top1_kernel(const float *__restrict__ preds, const uint8_t *__restrict__ mask,
                                    int32_t *__restrict__ top1, float *__restrict__ score,
                                    int32_t *__restrict__ status, int K, int N, int S, int64_t C, int64_t Cv,
-                                   int sign_mode, const Nodes nodes) {
+                                   int sign_mode, int qsplit, const Nodes nodes) {
     typedef typename PredVec<VEC>::type V;
     extern __shared__ double lds_d[];
     const int KP = round_up4(K);
@@ -89,7 +89,9 @@ __global__ void decode_top1_kernel(const float *__restrict__ preds, const uint8_
     double *beta_s = alpha_s + K;
     int *F = reinterpret_cast<int *>(beta_s + N);
     int *n_sh = F + N;
-    const int64_t g = blockIdx.x;
+    // qsplit > 1 (few groups, very many classes): qsplit = KP/4 workgroups share a group, one quad of queries each
+    const int64_t g = blockIdx.x / qsplit;
+    const int qpart = static_cast<int>(blockIdx.x - g * qsplit);
 
     stage_nodes(nodes, K, N, alpha_s, beta_s);
     for (int e = threadIdx.x; e < nF_cap * KP; e += blockDim.x) WdT[e] = 0.0;
@@ -109,11 +111,12 @@ __global__ void decode_top1_kernel(const float *__restrict__ preds, const uint8_
     const int lane = lane_id();
     const int KQ = KP / 4;
     const int nwaves = blockDim.x / kWave;
-    const int slices = nwaves >= KQ ? nwaves / KQ : 1;          // waves that share one quad split its columns
-    const int qwaves = nwaves >= KQ ? KQ : nwaves;              // quads processed concurrently
+    const bool one_quad = qsplit > 1;                           // this workgroup: quad qpart only, every wave a slice
+    const int slices = one_quad ? nwaves : (nwaves >= KQ ? nwaves / KQ : 1);   // waves that share one quad split its columns
+    const int qwaves = one_quad ? 1 : (nwaves >= KQ ? KQ : nwaves);            // quads processed concurrently
     const int slice = wave_id() / qwaves;
     Best *merged = reinterpret_cast<Best *>((reinterpret_cast<uintptr_t>(n_sh + 1) + 15) & ~static_cast<uintptr_t>(15));   // [KP][slices]
-    for (int q = wave_id() % qwaves; q < KQ && slice < slices; q += qwaves) {
+    for (int q = one_quad ? qpart : wave_id() % qwaves; q < KQ && slice < slices; q += one_quad ? KQ : qwaves) {
         Best best[4];
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
@@ -169,7 +172,9 @@ __global__ void decode_top1_kernel(const float *__restrict__ preds, const uint8_
         }
     }
     __syncthreads();
-    for (int j = threadIdx.x; j < K; j += blockDim.x) {
+    const int j_first = one_quad ? 4 * qpart : 0;
+    const int j_end = one_quad ? (4 * qpart + 4 < K ? 4 * qpart + 4 : K) : K;
+    for (int j = j_first + threadIdx.x; j < j_end; j += blockDim.x) {
         Best b = merged[j * slices];
         for (int sl = 1; sl < slices; ++sl) {
             const Best o = merged[j * slices + sl];
@@ -414,14 +419,24 @@ int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_t
     if (G > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
     const int KQ = KP / 4;
     int slices = static_cast<int>((Cv + kWave - 1) / kWave);     // column slices worth a wave of their own
-    if (slices > 4) slices = 4;
+    const int most = G >= 512 ? 4 : 16;                          // few groups: all sixteen waves of a workgroup
+    if (slices > most) slices = most;
     if (slices * KQ > 16) slices = 16 / KQ;
     if (slices < 1) slices = 1;
-    const int waves = KQ <= 16 ? KQ * slices : 16;
+    int waves = KQ <= 16 ? KQ * slices : 16;
+    // Few groups and very many classes (vocabulary-sized predictions in a small batch): a workgroup per quad of
+    // queries, all sixteen waves slicing the columns.  Every workgroup reads all surviving rows; with so few
+    // groups they come from the cache.
+    int qsplit = 1;
+    if (G * KQ <= 512 && KQ >= 2 && Cv >= 64 * 16) {
+        qsplit = KQ;
+        waves = 16;
+    }
+    const int lds_slices = qsplit > 1 ? waves : (waves >= KQ ? waves / KQ : 1);
     // int F[N] | int n | 1 pad int  keeps the Best array that follows 16-byte aligned when N is even; round up
     size_t lds = sizeof(double) * (static_cast<size_t>(S < 0 ? N : N - S) * KP + K + N) + sizeof(int) * (static_cast<size_t>(N) + 3);
-    lds += 16 + sizeof(double) * 2 * static_cast<size_t>(KP) * (waves >= KQ ? waves / KQ : 1);
-    const dim3 grid(static_cast<unsigned>(G)), block(waves * kWave);
+    lds += 16 + sizeof(double) * 2 * static_cast<size_t>(KP) * lds_slices;
+    const dim3 grid(static_cast<unsigned>(G * qsplit)), block(waves * kWave);
     if (lds > 64 * 1024) {
         const void *fn = vec4 ? reinterpret_cast<const void *>(decode_top1_kernel<4>)
                               : reinterpret_cast<const void *>(decode_top1_kernel<1>);
@@ -430,10 +445,10 @@ int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_t
     }
     if (vec4)
         hipLaunchKernelGGL(decode_top1_kernel<4>, grid, block, lds, stream, d_preds, d_mask, d_top1, d_score, d_status,
-                           K, N, S, C, Cv, sign_mode, nodes);
+                           K, N, S, C, Cv, sign_mode, qsplit, nodes);
     else
         hipLaunchKernelGGL(decode_top1_kernel<1>, grid, block, lds, stream, d_preds, d_mask, d_top1, d_score, d_status,
-                           K, N, S, C, Cv, sign_mode, nodes);
+                           K, N, S, C, Cv, sign_mode, qsplit, nodes);
     return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
 }
 

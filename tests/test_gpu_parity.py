@@ -380,7 +380,9 @@ def test_decode_top1_workloads(gpu, name, mode):
 
 @pytest.mark.parametrize("K,N,S,C,G", [(1, 2, 1, 1, 3), (2, 3, 1, 7, 4), (5, 100, 10, 33, 2), (12, 20, 8, 1003, 2),
                                        (16, 20, 4, 16, 9), (16, 64, 48, 16, 5), (13, 15, 2, 11, 131), (8, 9, 1, 10, 1030),
-                                       (32, 48, 12, 2, 5), (64, 128, 0, 12, 2), (9, 70, 3, 516, 2), (8, 9, 1, 10, 300)])
+                                       (32, 48, 12, 2, 5), (64, 128, 0, 12, 2), (9, 70, 3, 516, 2), (8, 9, 1, 10, 300),
+                                       # few groups, thousands of classes: one workgroup per quad of queries
+                                       (8, 12, 4, 5000, 3), (5, 9, 2, 4099, 2), (12, 20, 8, 20004, 2), (30, 40, 6, 4100, 2)])
 def test_decode_top1_shapes_and_bad_masks(gpu, K, N, S, C, G):
     torch, binding, dev = gpu
     rng = np.random.default_rng(K + 3 * N + S)
