@@ -30,8 +30,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 ENCODE_KERNEL_SOURCES = ("paper_2109_09868_amd/csrc/encode.hip", "paper_2109_09868_amd/csrc/common.h")
 ENCODE_TRAFFIC = {
     "sources_sha256": "e31ff801f124dcb88b4446fe92de3fa6aca3713f8c803cdcc241ebb75700b3f4",
-    "fetch_size_kib": 1806382.2, "fetch_factor": 2.0000,     # counter reads half the bytes of a known copy
-    "write_size_kib": 6021206.3, "write_factor": 1.0000,
+    "fetch_size_kib": 1806382.1, "fetch_factor": 2.0000,     # counter reads half the bytes of a known copy
+    "write_size_kib": 6021151.0, "write_factor": 1.0000,
 }
 
 
@@ -226,6 +226,13 @@ def other_workloads(torch, binding, syn, orc_nodes, dev, sign_mode):
     t = time_launches(torch, lambda: binding.approxifer_decode_top1(preds, mask, alpha, beta, w.S, sign_mode, top1=top1,
                                                                     score=None, status=st, want_score=False), 20, flush=flush)
     res["mnist_k8_decode_top1"] = dict(t, predictions_per_s=w.G * w.K / (t["avg_ms"] * 1e-3), note=COLD)
+    # the wait rule that produces such masks: arrival times -> the W - S fastest workers of every group
+    arrival = torch.rand((w.G, w.W), dtype=torch.float32, device=dev)
+    wmask = torch.empty((w.G, w.W), dtype=torch.uint8, device=dev)
+    wcount = torch.empty((w.G,), dtype=torch.int32, device=dev)
+    t = time_launches(torch, lambda: binding.approxifer_wait_mask(arrival, w.W - w.S, mask=wmask, count=wcount), 20,
+                      flush=flush)
+    res["mnist_k8_wait_mask"] = dict(t, groups_per_s=w.G / (t["avg_ms"] * 1e-3), note=COLD)
     del q, coded, preds, out
 
     # -- CIFAR-shaped: encode and decode timed separately ----------------------------------
