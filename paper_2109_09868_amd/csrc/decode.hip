@@ -188,26 +188,27 @@ __global__ void decode_top1_kernel(const float *__restrict__ preds, const uint8_
 // ------------------------------------------------------------------------------------
 // packed kernel for the small shapes of the image-classification operating points
 // ------------------------------------------------------------------------------------
-// K <= 16 queries, at most 16 surviving workers, C <= 16 classes (e.g. K = 8..12, one to three stragglers,
-// ten classes).  A group is then a few hundred bytes, and a workgroup per group spends its time on launch
+// K <= 16 queries, at most RT = 16 or 32 surviving workers, C <= 16 classes (e.g. K = 8..12, one to three
+// stragglers, ten classes; K = 16 with 18 of 24 workers and two classes).  A group is then a few hundred bytes, and a workgroup per group spends its time on launch
 // and barrier latency.  Here ONE WAVE decodes a group on its own -- four groups per workgroup, the only
 // workgroup barrier is the one after the nodes are staged -- with everything in 16 x 16 tiles in the wave's
-// own LDS: survivors from one ballot, predictions Y[r][c], weights W[j][r] (16 lanes per query node, four
+// own LDS: survivors from one ballot, predictions Y[r][c], weights W[j][r] (RT lanes per query node, 64 / RT
 // nodes per pass), then one lane per output (j, c).  TOP1 adds the argmax over classes.
-constexpr int kPk = 16;                 // tile edge: K, |F| and C are all at most 16
+constexpr int kPk = 16;                 // tile edge for K and C
 constexpr int kPkGroups = 4;            // groups (= waves) per workgroup
 
-template <bool TOP1>
+template <bool TOP1, int RT>
 __global__ __launch_bounds__(kPkGroups *kWave) void decode_packed_kernel(
     const float *__restrict__ preds, const uint8_t *__restrict__ mask, float *__restrict__ out,
     int32_t *__restrict__ top1, float *__restrict__ score, int32_t *__restrict__ status, int64_t G, int K, int N,
     int S, int C, int sign_mode, const Nodes nodes) {
     __shared__ double alpha_s[kPk];
     __shared__ double beta_s[kWave];
-    __shared__ double W_s[kPkGroups][kPk * kPk];       // W[j][r]
+    static_assert(RT == 16 || RT == 32, "survivor tile");
+    __shared__ double W_s[kPkGroups][kPk * RT];        // W[j][r]
     __shared__ double O_s[TOP1 ? kPkGroups : 1][kPk * kPk];
-    __shared__ float Y_s[kPkGroups][kPk * kPk];        // Y[r][c]
-    __shared__ int F_s[kPkGroups][kPk];
+    __shared__ float Y_s[kPkGroups][RT * kPk];         // Y[r][c]
+    __shared__ int F_s[kPkGroups][RT];
 
     const int lane = lane_id();
     const int wv = wave_id();
@@ -227,45 +228,47 @@ __global__ __launch_bounds__(kPkGroups *kWave) void decode_packed_kernel(
     const bool mine = lane < N && mask[g * N + lane] != 0;
     const unsigned long long m = __ballot(mine);
     const int nF = __popcll(m);
-    const bool good = S < 0 ? (nF >= 1 && nF <= kPk) : nF == N - S;
+    const bool good = S < 0 ? (nF >= 1 && nF <= RT) : nF == N - S;
     if (lane == 0 && status != nullptr) status[g] = good ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
     if (!good) return;
     if (mine) F[__popcll(m & ((1ull << lane) - 1ull))] = lane;
     __builtin_amdgcn_wave_barrier();
 
-    // predictions of the survivors: slot (r, c) = (slot / 16, slot % 16), four slots per lane
+    // predictions of the survivors: slot (r, c) = (slot / 16, slot % 16), RT / 4 slots per lane
+    constexpr int kYSlots = RT / 4;
     const float *pg = preds + static_cast<size_t>(g) * N * C;
-    float yv[4];
+    float yv[kYSlots];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kYSlots; ++u) {
         const int slot = lane + u * kWave;
         const int r = slot / kPk, c = slot % kPk;
         yv[u] = (r < nF && c < C) ? pg[static_cast<size_t>(F[r]) * C + c] : 0.0f;
     }
 
-    // weights, Section 3 "ApproxIFER Decoding" step 2: lanes (jsub, r) = (lane / 16, lane % 16)
+    // weights, Section 3 "ApproxIFER Decoding" step 2: lanes (jsub, r) = (lane / RT, lane % RT)
     {
-        const int r = lane % kPk, jsub = lane / kPk;
+        constexpr int kRowsPerPass = kWave / RT;
+        const int r = lane % RT, jsub = lane / RT;
         const bool valid = r < nF;
         const int i = valid ? F[r] : 0;
         const double xb = beta_s[i];
         const int parity = (sign_mode == APPROXIFER_SIGN_WORKER_INDEX) ? (i & 1) : (r & 1);
         const double sign = parity ? -1.0 : 1.0;
-        const unsigned long long group_mask = 0xFFFFull << (jsub * kPk);
+        const unsigned long long group_mask = (RT == 16 ? 0xFFFFull : 0xFFFFFFFFull) << (jsub * RT);
 #pragma unroll
-        for (int p = 0; p < kPk / 4; ++p) {
-            if (4 * p < K) {
-                const int j = 4 * p + jsub;
+        for (int p = 0; p < kPk / kRowsPerPass; ++p) {
+            if (kRowsPerPass * p < K) {
+                const int j = kRowsPerPass * p + jsub;
                 const bool row = j < K;
                 const BerrutTerm bt = berrut_term(alpha_s[row ? j : 0], xb, sign, valid && row);
-                const double rden = 1.0 / row16_sum(bt.t);
+                const double rden = 1.0 / group_sum<RT>(bt.t);
                 const bool any_hit = (__ballot(bt.hit) & group_mask) != 0ull;
-                W[j * kPk + r] = (valid && row) ? (any_hit ? (bt.hit ? 1.0 : 0.0) : bt.t * rden) : 0.0;
+                W[j * RT + r] = (valid && row) ? (any_hit ? (bt.hit ? 1.0 : 0.0) : bt.t * rden) : 0.0;
             }
         }
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) Y[lane + u * kWave] = yv[u];
+    for (int u = 0; u < kYSlots; ++u) Y[lane + u * kWave] = yv[u];
     __builtin_amdgcn_wave_barrier();
 
     // one lane per output (j, c) = (slot / 16, slot % 16); float64 accumulation, one rounding
@@ -278,11 +281,11 @@ __global__ __launch_bounds__(kPkGroups *kWave) void decode_packed_kernel(
             const int j = slot / kPk, c = slot % kPk;
             double acc = 0.0;
 #pragma unroll
-            for (int r0 = 0; r0 < kPk; r0 += 4) {
+            for (int r0 = 0; r0 < RT; r0 += 4) {
                 if (r0 < nF4) {
 #pragma unroll
                     for (int r = r0; r < r0 + 4; ++r)
-                        acc = fma(W[j * kPk + r], static_cast<double>(Y[r * kPk + c]), acc);
+                        acc = fma(W[j * RT + r], static_cast<double>(Y[r * kPk + c]), acc);
                 }
             }
             if (TOP1) O_s[TOP1 ? wv : 0][slot] = acc;
@@ -359,7 +362,7 @@ __global__ __launch_bounds__(kWaitGroups *kWave) void wait_mask_kernel(const flo
 
 bool packed_shape(int K, int N, int S, int64_t C) {
     const int most_survivors = S < 0 ? N : N - S;
-    return K <= kPk && most_survivors <= kPk && N <= kWave && C <= kPk;
+    return K <= kPk && most_survivors <= 32 && N <= kWave && C <= kPk;
 }
 
 int run_packed(bool top1_variant, const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_top1,
@@ -368,12 +371,18 @@ int run_packed(bool top1_variant, const float *d_preds, const uint8_t *d_mask, f
     const int64_t blocks = (G + kPkGroups - 1) / kPkGroups;
     if (blocks > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
     const dim3 grid(static_cast<unsigned>(blocks)), block(kPkGroups * kWave);
-    if (top1_variant)
-        hipLaunchKernelGGL(decode_packed_kernel<true>, grid, block, 0, stream, d_preds, d_mask, d_out, d_top1, d_score,
-                           d_status, G, K, N, S, static_cast<int>(C), sign_mode, nodes);
-    else
-        hipLaunchKernelGGL(decode_packed_kernel<false>, grid, block, 0, stream, d_preds, d_mask, d_out, d_top1, d_score,
-                           d_status, G, K, N, S, static_cast<int>(C), sign_mode, nodes);
+    const bool wide = (S < 0 ? N : N - S) > kPk;          // more than 16 survivors possible: the 32-row tile
+#define APPROXIFER_PACKED(TOP1, RT)                                                                                    \
+    hipLaunchKernelGGL((decode_packed_kernel<TOP1, RT>), grid, block, 0, stream, d_preds, d_mask, d_out, d_top1, d_score, \
+                       d_status, G, K, N, S, static_cast<int>(C), sign_mode, nodes)
+    if (top1_variant) {
+        if (wide) APPROXIFER_PACKED(true, 32);
+        else APPROXIFER_PACKED(true, 16);
+    } else {
+        if (wide) APPROXIFER_PACKED(false, 32);
+        else APPROXIFER_PACKED(false, 16);
+    }
+#undef APPROXIFER_PACKED
     return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
 }
 

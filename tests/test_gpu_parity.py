@@ -212,6 +212,8 @@ def test_decode_tiny_workload(gpu, mode):
     # the packed small-shape kernel at and just past its limits (K, survivors, classes <= 16, N <= 64)
     (16, 20, 4, 16, 9), (16, 64, 48, 16, 5), (16, 20, 3, 16, 5), (16, 20, 4, 17, 5), (13, 15, 2, 11, 131), (3, 64, 61, 1, 7),
     (1, 5, 4, 16, 6), (12, 13, 1, 10, 4099),
+    # .. and its 32-survivor tile: 17 to 32 survivors, and one more
+    (16, 24, 6, 2, 1031), (8, 24, 4, 10, 300), (16, 64, 32, 16, 9), (16, 40, 8, 16, 5), (3, 34, 2, 5, 70), (11, 18, 0, 13, 66),
 ])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_decode_shapes(gpu, K, N, S, C, G, mode):
@@ -381,6 +383,7 @@ def test_decode_top1_workloads(gpu, name, mode):
 @pytest.mark.parametrize("K,N,S,C,G", [(1, 2, 1, 1, 3), (2, 3, 1, 7, 4), (5, 100, 10, 33, 2), (12, 20, 8, 1003, 2),
                                        (16, 20, 4, 16, 9), (16, 64, 48, 16, 5), (13, 15, 2, 11, 131), (8, 9, 1, 10, 1030),
                                        (32, 48, 12, 2, 5), (64, 128, 0, 12, 2), (9, 70, 3, 516, 2), (8, 9, 1, 10, 300),
+                                       (16, 24, 6, 2, 300), (8, 24, 4, 10, 131), (16, 64, 32, 16, 9), (16, 40, 7, 16, 5),
                                        # few groups, thousands of classes: one workgroup per quad of queries
                                        (8, 12, 4, 5000, 3), (5, 9, 2, 4099, 2), (12, 20, 8, 20004, 2), (30, 40, 6, 4100, 2)])
 def test_decode_top1_shapes_and_bad_masks(gpu, K, N, S, C, G):
@@ -915,7 +918,8 @@ def test_paper_operating_point_workloads_full_size(gpu):
 # --------------------------------------------------------------------------------------
 # per-group straggler counts (S = APPROXIFER_S_FROM_MASK): ragged masks
 # --------------------------------------------------------------------------------------
-@pytest.mark.parametrize("K,N,C,G", [(3, 9, 5, 12), (8, 12, 100, 40), (12, 20, 1000, 24), (16, 70, 36, 10), (5, 128, 3, 9)])
+@pytest.mark.parametrize("K,N,C,G", [(3, 9, 5, 12), (8, 12, 100, 40), (12, 20, 1000, 24), (16, 70, 36, 10), (5, 128, 3, 9),
+                                     (10, 30, 10, 64), (16, 32, 16, 33)])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_decode_ragged_masks(gpu, K, N, C, G, mode):
     torch, binding, dev = gpu
