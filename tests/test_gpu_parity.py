@@ -75,6 +75,8 @@ def test_encode_tiny_workload(gpu):
     (12, 28, 784, 5), (8, 24, 4 * 50, 3), (20, 30, 4 * 70, 3), (32, 48, 4 * 10, 7), (17, 20, 4 * 1, 9),
     # residency caps: K = 1, 2, 4 run with many more waves per CU
     (1, 2, 4 * 64 * 40, 3), (2, 3, 4 * 64 * 33, 3), (4, 6, 4 * 64 * 21, 2),
+    # short ragged rows (D % 4 != 0, D <= 128) take 4-byte accesses for every column; 129 and up: 128-bit + tail
+    (8, 12, 30, 700), (12, 20, 7, 300), (8, 24, 126, 40), (20, 30, 127, 9), (33, 40, 5, 11), (8, 12, 129, 40), (12, 28, 130, 9),
 ])
 def test_encode_shapes_with_ragged_tails(gpu, K, N, D, G):
     torch, binding, dev = gpu
@@ -89,6 +91,7 @@ def test_encode_shapes_with_ragged_tails(gpu, K, N, D, G):
 @pytest.mark.parametrize("K,N,D,G,off_in,off_out", [
     (6, 10, 1000, 2, 1, 3), (6, 10, 1003, 3, 0, 0), (6, 10, 1001, 2, 1, 2), (12, 20, 4 * 64 * 3 + 2, 2, 3, 1),
     (8, 24, 4 * 64 * 2 + 1, 2, 2, 2), (20, 30, 4 * 64 + 3, 2, 1, 1), (33, 40, 4 * 64 * 2, 1, 3, 3), (3, 5, 2, 4, 1, 1),
+    (8, 12, 30, 50, 1, 2), (12, 20, 127, 6, 3, 1),
 ])
 def test_encode_unaligned_pointers_and_canaries(gpu, K, N, D, G, off_in, off_out):
     # rows that are only 4-byte aligned (odd row length and/or offset base pointers): 128-bit accesses through the
