@@ -329,6 +329,16 @@ def other_workloads(torch, binding, syn, orc_nodes, dev, sign_mode):
                                      hbm_gbs=encode_bytes(w) / (t["avg_ms"] * 1e6),
                                      fp32_tflops=2.0 * w.K * w.W * w.D * w.G / (t["avg_ms"] * 1e9))
         del q, coded
+        # its decode moves under 1 MB (two classes): launch-latency-bound; seeded normal logits stand in for the model
+        preds = torch.from_numpy(syn.iid_logits(w)).to(dev)
+        mask = torch.from_numpy(syn.masks(w)).to(dev)
+        out = torch.empty((w.G, w.K, w.C), dtype=torch.float32, device=dev)
+        st = torch.empty((w.G,), dtype=torch.int32, device=dev)
+        t = time_launches(torch, lambda: binding.approxifer_decode(preds, mask, alpha, beta, w.S, sign_mode, out=out,
+                                                                   status=st), 20, flush=flush)
+        res[name + "_decode"] = dict(t, predictions_per_s=w.G * w.K / (t["avg_ms"] * 1e-3),
+                                     hbm_gbs=decode_bytes(w) / (t["avg_ms"] * 1e6), note=COLD)
+        del preds, mask, out
     del flush
     return res
 
