@@ -188,27 +188,26 @@ __global__ void decode_top1_kernel(const float *__restrict__ preds, const uint8_
 // ------------------------------------------------------------------------------------
 // packed kernel for the small shapes of the image-classification operating points
 // ------------------------------------------------------------------------------------
-// K <= 16 queries, at most RT = 16 or 32 surviving workers, C <= 16 classes (e.g. K = 8..12, one to three
-// stragglers, ten classes; K = 16 with 18 of 24 workers and two classes).  A group is then a few hundred bytes, and a workgroup per group spends its time on launch
-// and barrier latency.  Here ONE WAVE decodes a group on its own -- four groups per workgroup, the only
+// K <= KT queries, at most RT surviving workers, C <= 16 classes, (KT, RT) = (16, 16), (16, 32) or (32, 64) (e.g.
+// K = 8..12, one to three stragglers, ten classes; K = 16 with 18 of 24 workers and K = 32 with 36 of 48, two classes).  A group is then a few hundred bytes, and a workgroup per group spends its time on launch
+// and barrier latency.  Here ONE WAVE decodes a group on its own -- four (two for the largest tile) groups per workgroup, the only
 // workgroup barrier is the one after the nodes are staged -- with everything in 16 x 16 tiles in the wave's
 // own LDS: survivors from one ballot, predictions Y[r][c], weights W[j][r] (RT lanes per query node, 64 / RT
 // nodes per pass), then one lane per output (j, c).  TOP1 adds the argmax over classes.
-constexpr int kPk = 16;                 // tile edge for K and C
-constexpr int kPkGroups = 4;            // groups (= waves) per workgroup
+constexpr int kPk = 16;                 // tile edge for C (and for K in the smaller tiles)
 
-template <bool TOP1, int RT>
-__global__ __launch_bounds__(kPkGroups *kWave) void decode_packed_kernel(
+template <bool TOP1, int KT, int RT, int GROUPS>
+__global__ __launch_bounds__(GROUPS *kWave) void decode_packed_kernel(
     const float *__restrict__ preds, const uint8_t *__restrict__ mask, float *__restrict__ out,
     int32_t *__restrict__ top1, float *__restrict__ score, int32_t *__restrict__ status, int64_t G, int K, int N,
     int S, int C, int sign_mode, const Nodes nodes) {
-    __shared__ double alpha_s[kPk];
+    static_assert((KT == 16 && (RT == 16 || RT == 32)) || (KT == 32 && RT == 64), "tile");
+    __shared__ double alpha_s[KT];
     __shared__ double beta_s[kWave];
-    static_assert(RT == 16 || RT == 32, "survivor tile");
-    __shared__ double W_s[kPkGroups][kPk * RT];        // W[j][r]
-    __shared__ double O_s[TOP1 ? kPkGroups : 1][kPk * kPk];
-    __shared__ float Y_s[kPkGroups][RT * kPk];         // Y[r][c]
-    __shared__ int F_s[kPkGroups][RT];
+    __shared__ double W_s[GROUPS][KT * RT];            // W[j][r]
+    __shared__ double O_s[TOP1 ? GROUPS : 1][KT * kPk];
+    __shared__ float Y_s[GROUPS][RT * kPk];            // Y[r][c]
+    __shared__ int F_s[GROUPS][RT];
 
     const int lane = lane_id();
     const int wv = wave_id();
@@ -217,7 +216,7 @@ __global__ __launch_bounds__(kPkGroups *kWave) void decode_packed_kernel(
         else beta_s[t - K] = nodes.beta[t - K];
     }
     __syncthreads();
-    const int64_t g = static_cast<int64_t>(blockIdx.x) * kPkGroups + wv;
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * GROUPS + wv;
     if (g >= G) return;
 
     double *W = W_s[wv];
@@ -254,9 +253,9 @@ __global__ __launch_bounds__(kPkGroups *kWave) void decode_packed_kernel(
         const double xb = beta_s[i];
         const int parity = (sign_mode == APPROXIFER_SIGN_WORKER_INDEX) ? (i & 1) : (r & 1);
         const double sign = parity ? -1.0 : 1.0;
-        const unsigned long long group_mask = (RT == 16 ? 0xFFFFull : 0xFFFFFFFFull) << (jsub * RT);
+        const unsigned long long group_mask = RT == 64 ? ~0ull : (RT == 16 ? 0xFFFFull : 0xFFFFFFFFull) << (jsub * (RT & 63));
 #pragma unroll
-        for (int p = 0; p < kPk / kRowsPerPass; ++p) {
+        for (int p = 0; p < KT / kRowsPerPass; ++p) {
             if (kRowsPerPass * p < K) {
                 const int j = kRowsPerPass * p + jsub;
                 const bool row = j < K;
@@ -275,7 +274,7 @@ __global__ __launch_bounds__(kPkGroups *kWave) void decode_packed_kernel(
     const int nF4 = (nF + 3) & ~3;                       // rows nF.. of W and Y are zero
     float *og = out + static_cast<size_t>(g) * K * C;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < KT / 4; ++u) {
         if (u * 4 < K) {
             const int slot = lane + u * kWave;
             const int j = slot / kPk, c = slot % kPk;
@@ -361,26 +360,30 @@ __global__ __launch_bounds__(kWaitGroups *kWave) void wait_mask_kernel(const flo
 }
 
 bool packed_shape(int K, int N, int S, int64_t C) {
-    const int most_survivors = S < 0 ? N : N - S;
-    return K <= kPk && most_survivors <= 32 && N <= kWave && C <= kPk;
+    return K <= 32 && N <= kWave && C <= kPk;             // N <= 64: the survivors fit the largest tile
 }
 
 int run_packed(bool top1_variant, const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_top1,
                float *d_score, int32_t *d_status, int64_t G, int K, int N, int S, int64_t C, const Nodes &nodes,
                int sign_mode, hipStream_t stream) {
-    const int64_t blocks = (G + kPkGroups - 1) / kPkGroups;
+    const int most_survivors = S < 0 ? N : N - S;
+    // the smallest tile (queries, survivors) that holds the shape; the largest takes two groups per workgroup
+    const int tile = (K <= 16 && most_survivors <= 16) ? 0 : ((K <= 16 && most_survivors <= 32) ? 1 : 2);
+    const int groups = tile == 2 ? 2 : 4;
+    const int64_t blocks = (G + groups - 1) / groups;
     if (blocks > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
-    const dim3 grid(static_cast<unsigned>(blocks)), block(kPkGroups * kWave);
-    const bool wide = (S < 0 ? N : N - S) > kPk;          // more than 16 survivors possible: the 32-row tile
-#define APPROXIFER_PACKED(TOP1, RT)                                                                                    \
-    hipLaunchKernelGGL((decode_packed_kernel<TOP1, RT>), grid, block, 0, stream, d_preds, d_mask, d_out, d_top1, d_score, \
-                       d_status, G, K, N, S, static_cast<int>(C), sign_mode, nodes)
+    const dim3 grid(static_cast<unsigned>(blocks)), block(groups * kWave);
+#define APPROXIFER_PACKED(TOP1, KT, RT, GROUPS)                                                                        \
+    hipLaunchKernelGGL((decode_packed_kernel<TOP1, KT, RT, GROUPS>), grid, block, 0, stream, d_preds, d_mask, d_out,      \
+                       d_top1, d_score, d_status, G, K, N, S, static_cast<int>(C), sign_mode, nodes)
     if (top1_variant) {
-        if (wide) APPROXIFER_PACKED(true, 32);
-        else APPROXIFER_PACKED(true, 16);
+        if (tile == 0) APPROXIFER_PACKED(true, 16, 16, 4);
+        else if (tile == 1) APPROXIFER_PACKED(true, 16, 32, 4);
+        else APPROXIFER_PACKED(true, 32, 64, 2);
     } else {
-        if (wide) APPROXIFER_PACKED(false, 32);
-        else APPROXIFER_PACKED(false, 16);
+        if (tile == 0) APPROXIFER_PACKED(false, 16, 16, 4);
+        else if (tile == 1) APPROXIFER_PACKED(false, 16, 32, 4);
+        else APPROXIFER_PACKED(false, 32, 64, 2);
     }
 #undef APPROXIFER_PACKED
     return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;

@@ -217,6 +217,8 @@ def test_decode_tiny_workload(gpu, mode):
     (1, 5, 4, 16, 6), (12, 13, 1, 10, 4099),
     # .. and its 32-survivor tile: 17 to 32 survivors, and one more
     (16, 24, 6, 2, 1031), (8, 24, 4, 10, 300), (16, 64, 32, 16, 9), (16, 40, 8, 16, 5), (3, 34, 2, 5, 70), (11, 18, 0, 13, 66),
+    # .. and its (32 queries, 64 survivors) tile, two groups per workgroup
+    (32, 48, 12, 2, 1025), (20, 30, 4, 4, 301), (32, 64, 0, 16, 7), (17, 40, 4, 9, 50), (8, 60, 4, 10, 21), (32, 34, 2, 16, 3),
 ])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_decode_shapes(gpu, K, N, S, C, G, mode):
@@ -387,6 +389,7 @@ def test_decode_top1_workloads(gpu, name, mode):
                                        (16, 20, 4, 16, 9), (16, 64, 48, 16, 5), (13, 15, 2, 11, 131), (8, 9, 1, 10, 1030),
                                        (32, 48, 12, 2, 5), (64, 128, 0, 12, 2), (9, 70, 3, 516, 2), (8, 9, 1, 10, 300),
                                        (16, 24, 6, 2, 300), (8, 24, 4, 10, 131), (16, 64, 32, 16, 9), (16, 40, 7, 16, 5),
+                                       (32, 48, 12, 2, 300), (20, 30, 4, 4, 301), (32, 64, 0, 16, 7), (17, 40, 3, 9, 50), (8, 60, 4, 10, 21),
                                        # few groups, thousands of classes: one workgroup per quad of queries
                                        (8, 12, 4, 5000, 3), (5, 9, 2, 4099, 2), (12, 20, 8, 20004, 2), (30, 40, 6, 4100, 2)])
 def test_decode_top1_shapes_and_bad_masks(gpu, K, N, S, C, G):
