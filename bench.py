@@ -31,7 +31,7 @@ ENCODE_KERNEL_SOURCES = ("paper_2109_09868_amd/csrc/encode.hip", "paper_2109_098
 ENCODE_TRAFFIC = {
     "sources_sha256": "edc2bb98e9bfab05ab50440f48cf6f5d243b5857b18677d8fb10fe4aa6da9f95",
     "fetch_size_kib": 1806382.2, "fetch_factor": 2.0000,     # counter reads half the bytes of a known copy
-    "write_size_kib": 6021140.0, "write_factor": 1.0000,
+    "write_size_kib": 6021161.7, "write_factor": 1.0000,
 }
 
 
