@@ -419,7 +419,7 @@ __device__ __forceinline__ void locate_classes_proj(const float *Ysh, int CW, in
 // dynamic LDS (doubles): Ush[ush_rows(RM)*ush_stride(NB)] | Pw[NB*16] | xs[NB] | WdT[(n_cap-A)*KP] | alpha_s[K] | beta_s[N]
 //               then float Ysh[NB*CW], then ints: avail[N] | F[N] | Fpos[N] | votes[N] | sel[N] | n
 template <int NB, int RM>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 && NB <= 32 ? 3 : 2))) void decode_byzantine_proj_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 && NB <= 28 ? 3 : 2))) void decode_byzantine_proj_kernel(
     const float *__restrict__ preds, const uint8_t *__restrict__ mask, float *__restrict__ out,
     int32_t *__restrict__ adv, int32_t *__restrict__ status, int K, int N, int S, int A, int64_t C, int64_t Cv,
     int vec4, int sign_mode, int n_cap, int cw_log2, int splits, const Nodes nodes) {
