@@ -51,7 +51,7 @@ namespace {
 #define APPROXIFER_ENCODE_MFMA_BLOCKS_PER_CU 4       // matrix-core variant (four waves of 64 columns)
 #endif
 #ifndef APPROXIFER_ENCODE_SCALAR_ROWS_MAX_D
-#define APPROXIFER_ENCODE_SCALAR_ROWS_MAX_D 128      // ragged rows (D % 4 != 0) this short: 4-byte accesses for all columns
+#define APPROXIFER_ENCODE_SCALAR_ROWS_MAX_D 128      // ragged rows (D % 4 != 0) this short: 64-bit or 4-byte accesses only
 #endif
 constexpr int kLdsPerCu = 160 * 1024;                // gfx950
 
@@ -397,10 +397,14 @@ int run_encode_k(const float *d_queries, float *d_coded, int64_t G, int N, int64
     const bool aligned16 = (reinterpret_cast<uintptr_t>(d_queries) % 16 == 0) &&
                            (reinterpret_cast<uintptr_t>(d_coded) % 16 == 0) && (D % 4 == 0);
     if (aligned16) return run_encode_wide<K, false>(d_queries, d_coded, G, N, D, nodes, stream);
-    // rows only 4-byte aligned: 128-bit accesses on the first 4 * (D / 4) columns, 4-byte accesses on the rest
+    // rows only 4-byte aligned: 128-bit accesses on the first 4 * (D / 4) columns, 4-byte accesses on the rest;
+    // short ragged rows: aligned 64-bit accesses throughout where the rows allow them, else 4-byte accesses
     const int64_t tail = D % 4;
-    if (tail != 0 && D <= APPROXIFER_ENCODE_SCALAR_ROWS_MAX_D)
+    if (tail != 0 && D <= APPROXIFER_ENCODE_SCALAR_ROWS_MAX_D) {
+        if (D % 2 == 0 && reinterpret_cast<uintptr_t>(d_queries) % 8 == 0 && reinterpret_cast<uintptr_t>(d_coded) % 8 == 0)
+            return run_encode<K, 2, false>(d_queries, d_coded, G, N, D, D / 2, 0, nodes, stream);
         return run_encode<K, 1, false>(d_queries, d_coded, G, N, D, D, 0, nodes, stream);
+    }
     if (D >= 4) {
         const int rc = run_encode_wide<K, true>(d_queries, d_coded, G, N, D, nodes, stream);
         if (rc != APPROXIFER_OK) return rc;

@@ -91,7 +91,7 @@ def test_encode_shapes_with_ragged_tails(gpu, K, N, D, G):
 @pytest.mark.parametrize("K,N,D,G,off_in,off_out", [
     (6, 10, 1000, 2, 1, 3), (6, 10, 1003, 3, 0, 0), (6, 10, 1001, 2, 1, 2), (12, 20, 4 * 64 * 3 + 2, 2, 3, 1),
     (8, 24, 4 * 64 * 2 + 1, 2, 2, 2), (20, 30, 4 * 64 + 3, 2, 1, 1), (33, 40, 4 * 64 * 2, 1, 3, 3), (3, 5, 2, 4, 1, 1),
-    (8, 12, 30, 50, 1, 2), (12, 20, 127, 6, 3, 1),
+    (8, 12, 30, 50, 1, 2), (12, 20, 127, 6, 3, 1), (8, 12, 30, 50, 2, 2), (5, 7, 126, 9, 0, 2),
 ])
 def test_encode_unaligned_pointers_and_canaries(gpu, K, N, D, G, off_in, off_out):
     # rows that are only 4-byte aligned (odd row length and/or offset base pointers): 128-bit accesses through the
