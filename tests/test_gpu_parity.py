@@ -235,6 +235,39 @@ def test_decode_shapes(gpu, K, N, S, C, G, mode):
     assert group_err(out, ref).max() <= TOL
 
 
+@pytest.mark.parametrize("K,N,S,C,G", [(3, 6, 1, 280, 8300), (7, 12, 4, 132, 16500), (12, 20, 8, 1000, 4200),
+                                       (16, 70, 10, 260, 8200), (9, 14, 0, 4 * 64 * 2 + 4, 5600)])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_decode_streaming_kernel(gpu, K, N, S, C, G, mode):
+    # 16-byte rows and K <= 16: one wave keeps all K accumulator rows; many groups, ragged last tiles, a rejected mask
+    # and per-group straggler counts among the groups
+    torch, binding, dev = gpu
+    rng = np.random.default_rng(K * 977 + C)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    Y = rng.standard_normal((G, N, C)).astype(np.float32)
+    mask = np.zeros((G, N), np.uint8)
+    for g in range(G):
+        mask[g, rng.permutation(N)[: N - S]] = 1
+    mask[7, np.nonzero(mask[7])[0][0]] = 0                 # one survivor too few
+    Y[mask == 0] = np.nan
+    out = torch.full((G, K, C), -3.0, dtype=torch.float32, device=dev)
+    Yd, md = torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev)
+    _, st = binding.approxifer_decode(Yd, md, alpha, beta, S, mode, out=out)
+    ref, st_ref = orc.decode(Y, mask, alpha, beta, S, mode)
+    o, s = out.cpu().numpy(), st.cpu().numpy()
+    assert np.array_equal(s, st_ref) and s[7] == 1 and s.sum() == 1
+    assert np.all(o[7] == -3.0)
+    good = (s == 0) & well_posed(alpha, beta, mask, mode)
+    assert good.sum() >= 0.9 * G
+    assert group_err(o[good], ref[good]).max() <= TOL
+    # per-group straggler counts: the same masks, read off group by group
+    out2, st2 = binding.approxifer_decode(Yd, md, alpha, beta, binding.S_FROM_MASK, mode)
+    ref2, _ = orc.decode(Y[:64], mask[:64], alpha, beta, None, mode)
+    ok2 = well_posed(alpha, beta, mask[:64], mode)
+    assert np.all(st2.cpu().numpy() == 0)
+    assert group_err(out2.cpu().numpy()[:64][ok2], ref2[ok2]).max() <= TOL
+
+
 def test_decode_bad_masks_leave_rows_untouched(gpu):
     torch, binding, dev = gpu
     K, N, S, C = 3, 7, 2, 40
