@@ -69,8 +69,24 @@ __global__ void decode_kernel(const float *__restrict__ preds, const uint8_t *__
 // a group's tile costs one wave's worth of prologue instead of K/4.  16-byte-aligned rows, K <= 16, up to 64
 // survivors; measured against decode_kernel: 512 x 12 x 1000 classes 23.1 -> 20.7 us, 4096 x 8 x 100 classes
 // 17.3 -> 13.8 us, 1.1 GB (K = 16, 4096 classes) 336 -> 235 us.
+// UNAL: rows are only 4-byte aligned (C % 4 != 0 or offset tensors): the same 128-bit accesses through a
+// 4-byte-aligned vector type, and the lane that holds a row's last, partial vector (C % 4 floats) moves it float
+// by float.  Cv = ceil(C / 4) then counts that partial vector.
 // dynamic LDS: as decode_kernel.
-template <int KQ>
+typedef v4f v4f_dword_aligned __attribute__((aligned(4)));
+
+template <bool UNAL>
+__device__ __forceinline__ v4f load_pred_vector(const float *p, int floats) {
+    if (!UNAL) return *reinterpret_cast<const v4f *>(p);
+    if (floats >= 4) return *reinterpret_cast<const v4f_dword_aligned *>(p);
+    v4f v = v4f(0.0f);
+    v[0] = p[0];
+    if (floats > 1) v[1] = p[1];
+    if (floats > 2) v[2] = p[2];
+    return v;
+}
+
+template <int KQ, bool UNAL>
 __global__ __launch_bounds__(kWave) void decode_stream_kernel(const float *__restrict__ preds,
                                                               const uint8_t *__restrict__ mask, float *__restrict__ out,
                                                               int32_t *__restrict__ status, int K, int N, int S, int64_t C,
@@ -98,9 +114,12 @@ __global__ __launch_bounds__(kWave) void decode_stream_kernel(const float *__res
     const int64_t cv_raw = ct * kColsPerTile + lane;
     const bool ok = cv_raw < Cv;
     const int64_t cv = ok ? cv_raw : ct * kColsPerTile;    // lanes past the ragged end read the tile's first column
-    const float *pg = preds + static_cast<size_t>(g) * N * C;
+    const int floats = (UNAL && C - 4 * cv < 4) ? static_cast<int>(C - 4 * cv) : 4;   // of this lane's vector
+    const float *pg = preds + static_cast<size_t>(g) * N * C + 4 * cv;
     v4f y[kRowChunk];
-    load_row_chunk<4>(pg, F, nF, 0, C, cv, y);            // in flight while the weights are evaluated
+#pragma unroll
+    for (int u = 0; u < kRowChunk; ++u)                    // in flight while the weights are evaluated
+        y[u] = load_pred_vector<UNAL>(pg + static_cast<size_t>(F[u < nF ? u : nF - 1]) * C, floats);
 
     decoder_weights(alpha_s, beta_s, F, nF, K, KP, sign_mode, WdT);
     __syncthreads();
@@ -111,7 +130,11 @@ __global__ __launch_bounds__(kWave) void decode_stream_kernel(const float *__res
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc[j][e] = 0.0;
     for (int r0 = 0; r0 < nF; r0 += kRowChunk) {
-        if (r0 > 0) load_row_chunk<4>(pg, F, nF, r0, C, cv, y);
+        if (r0 > 0) {
+#pragma unroll
+            for (int u = 0; u < kRowChunk; ++u)
+                y[u] = load_pred_vector<UNAL>(pg + static_cast<size_t>(F[r0 + u < nF ? r0 + u : nF - 1]) * C, floats);
+        }
 #pragma unroll
         for (int u = 0; u < kRowChunk; ++u) {
             if (r0 + u < nF) {
@@ -131,8 +154,25 @@ __global__ __launch_bounds__(kWave) void decode_stream_kernel(const float *__res
     if (!ok) return;
     float *og = out + static_cast<size_t>(g) * K * C + cv * 4;
 #pragma unroll
-    for (int j = 0; j < KP; ++j)
-        if (j < K) store_row<4>(og + static_cast<size_t>(j) * C, acc[j]);
+    for (int j = 0; j < KP; ++j) {
+        if (j < K) {
+            float *dst = og + static_cast<size_t>(j) * C;
+            if (!UNAL) {
+                store_row<4>(dst, acc[j]);
+            } else if (floats >= 4) {
+                v4f v;
+                v[0] = static_cast<float>(acc[j][0]);
+                v[1] = static_cast<float>(acc[j][1]);
+                v[2] = static_cast<float>(acc[j][2]);
+                v[3] = static_cast<float>(acc[j][3]);
+                *reinterpret_cast<v4f_dword_aligned *>(dst) = v;
+            } else {
+                dst[0] = static_cast<float>(acc[j][0]);
+                if (floats > 1) dst[1] = static_cast<float>(acc[j][1]);
+                if (floats > 2) dst[2] = static_cast<float>(acc[j][2]);
+            }
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------
@@ -480,17 +520,24 @@ int launch_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int
     int waves = KP / 4;
     if (waves > 4) waves = 4;
     const size_t lds = sizeof(double) * (static_cast<size_t>(S < 0 ? N : N - S) * KP + K + N) + sizeof(int) * (static_cast<size_t>(N) + 2);
-    // 16-byte rows, K <= 16, up to 64 survivors: one wave per tile with all K accumulator rows (faster at every size
-    // measured, 26 MB to 1.1 GB; capping its residency as in the encoder changes nothing: 4 to 12 waves per CU +-3 %)
+    // K <= 16, up to 64 survivors: one wave per tile with all K accumulator rows (faster at every size measured, 26 MB
+    // to 1.1 GB; capping its residency as in the encoder changes nothing: 4 to 12 waves per CU +-3 %)
     const int most_survivors = S < 0 ? N : N - S;
-    if (vec4 && K <= 16 && most_survivors <= 64) {
-        const dim3 sgrid(static_cast<unsigned>(blocks)), sblock(kWave);
+    if (K <= 16 && most_survivors <= 64 && C >= 4) {
+        const int64_t sCv = (C + 3) / 4;                  // counts a partial last vector
+        const int64_t stiles = (sCv + kColsPerTile - 1) / kColsPerTile;
+        if (G * stiles > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+        const dim3 sgrid(static_cast<unsigned>(G * stiles)), sblock(kWave);
+#define APPROXIFER_STREAM(KQ, UNAL)                                                                                    \
+    hipLaunchKernelGGL((decode_stream_kernel<KQ, UNAL>), sgrid, sblock, lds, stream, d_preds, d_mask, d_out, d_status, K, \
+                       N, S, C, sCv, stiles, sign_mode, nodes)
         switch (KP / 4) {
-            case 1: hipLaunchKernelGGL(decode_stream_kernel<1>, sgrid, sblock, lds, stream, d_preds, d_mask, d_out, d_status, K, N, S, C, Cv, ctiles, sign_mode, nodes); break;
-            case 2: hipLaunchKernelGGL(decode_stream_kernel<2>, sgrid, sblock, lds, stream, d_preds, d_mask, d_out, d_status, K, N, S, C, Cv, ctiles, sign_mode, nodes); break;
-            case 3: hipLaunchKernelGGL(decode_stream_kernel<3>, sgrid, sblock, lds, stream, d_preds, d_mask, d_out, d_status, K, N, S, C, Cv, ctiles, sign_mode, nodes); break;
-            default: hipLaunchKernelGGL(decode_stream_kernel<4>, sgrid, sblock, lds, stream, d_preds, d_mask, d_out, d_status, K, N, S, C, Cv, ctiles, sign_mode, nodes); break;
+            case 1: if (vec4) APPROXIFER_STREAM(1, false); else APPROXIFER_STREAM(1, true); break;
+            case 2: if (vec4) APPROXIFER_STREAM(2, false); else APPROXIFER_STREAM(2, true); break;
+            case 3: if (vec4) APPROXIFER_STREAM(3, false); else APPROXIFER_STREAM(3, true); break;
+            default: if (vec4) APPROXIFER_STREAM(4, false); else APPROXIFER_STREAM(4, true); break;
         }
+#undef APPROXIFER_STREAM
         return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
     }
     const dim3 grid(static_cast<unsigned>(blocks)), block(waves * kWave);

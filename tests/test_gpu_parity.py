@@ -268,6 +268,34 @@ def test_decode_streaming_kernel(gpu, K, N, S, C, G, mode):
     assert group_err(out2.cpu().numpy()[:64][ok2], ref2[ok2]).max() <= TOL
 
 
+@pytest.mark.parametrize("K,N,S,C,G,off_in,off_out", [
+    (12, 20, 8, 1001, 3, 0, 0), (8, 12, 4, 101, 40, 1, 3), (5, 9, 2, 4 * 64 + 1, 7, 2, 1), (16, 70, 10, 4 * 64 * 2 + 3, 3, 3, 2),
+    (7, 12, 4, 256, 9, 1, 1), (3, 6, 1, 5, 600, 0, 1), (20, 30, 4, 131, 5, 1, 2), (8, 12, 4, 4 * 130 + 2, 300, 0, 0),
+])
+def test_decode_rows_that_are_only_4_byte_aligned(gpu, K, N, S, C, G, off_in, off_out):
+    # class counts that are not a multiple of four and/or offset tensors: 128-bit accesses through the 4-byte-aligned
+    # vector type, the last partial vector of a row float by float; nothing outside the output tensor may be touched
+    torch, binding, dev = gpu
+    rng = np.random.default_rng(C * 7 + K)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    Y = rng.standard_normal((G, N, C)).astype(np.float32)
+    mask = np.zeros((G, N), np.uint8)
+    for g in range(G):
+        mask[g, rng.permutation(N)[: N - S]] = 1
+    Y[mask == 0] = np.nan
+    flat_in = torch.zeros(G * N * C + off_in + 5, dtype=torch.float32, device=dev)
+    flat_in[off_in:off_in + G * N * C] = torch.from_numpy(Y).to(dev).reshape(-1)
+    flat_out = torch.full((G * K * C + off_out + 9,), -77.0, dtype=torch.float32, device=dev)
+    preds = flat_in[off_in:off_in + G * N * C].view(G, N, C)
+    out = flat_out[off_out:off_out + G * K * C].view(G, K, C)
+    _, st = binding.approxifer_decode(preds, torch.from_numpy(mask).to(dev), alpha, beta, S, 1, out=out)
+    ref, st_ref = orc.decode(Y, mask, alpha, beta, S, 1)
+    assert np.array_equal(st.cpu().numpy(), st_ref) and np.all(st_ref == 0)
+    assert group_err(out.cpu().numpy(), ref).max() <= TOL
+    host = flat_out.cpu().numpy()
+    assert np.all(host[:off_out] == -77.0) and np.all(host[off_out + G * K * C:] == -77.0)
+
+
 def test_decode_bad_masks_leave_rows_untouched(gpu):
     torch, binding, dev = gpu
     K, N, S, C = 3, 7, 2, 40
