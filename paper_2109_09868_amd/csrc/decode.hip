@@ -301,6 +301,157 @@ __global__ void decode_top1_kernel(const float *__restrict__ preds, const uint8_
     }
 }
 
+// one step of a (value, class) maximum inside the 16-lane rows: larger value first, equal values: smaller class
+template <int CTRL>
+__device__ __forceinline__ void best_step(Best &b) {
+    const double ov = dpp_exchange<CTRL>(b.v);
+    const int oi = __builtin_amdgcn_update_dpp(0, b.i, CTRL, 0xF, 0xF, true);
+    if (better(ov, oi, b)) {
+        b.v = ov;
+        b.i = oi;
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// fused decoder + top-1 with all K accumulator rows in one wave (K <= 16, up to 64 survivors)
+// ------------------------------------------------------------------------------------
+// One workgroup per group; its waves take the column tiles wave, wave + nwaves, .. and each keeps, per lane, the
+// float64 accumulators of all K queries for four columns and the best (value, class) seen so far for every query.
+// Nothing is stored inside the tile loop, so the next tile's loads are not held up by stores.  At the end a
+// butterfly merges the lanes, LDS merges the waves.  Ties: the smaller class index.
+// dynamic LDS: as decode_kernel, then pad to 16 bytes | Best merged[KP][nwaves].
+template <int KQ, bool UNAL>
+__global__ __launch_bounds__(256) void decode_top1_stream_kernel(const float *__restrict__ preds,
+                                                                  const uint8_t *__restrict__ mask,
+                                                                  int32_t *__restrict__ top1, float *__restrict__ score,
+                                                                  int32_t *__restrict__ status, int K, int N, int S,
+                                                                  int64_t C, int64_t Cv, int64_t ctiles, int sign_mode,
+                                                                  const Nodes nodes) {
+    constexpr int KP = 4 * KQ;
+    extern __shared__ double lds_d[];
+    const int nF_cap = S < 0 ? N : N - S;
+    double *WdT = lds_d;
+    double *alpha_s = WdT + nF_cap * KP;
+    double *beta_s = alpha_s + K;
+    int *F = reinterpret_cast<int *>(beta_s + N);
+    int *n_sh = F + N;
+    Best *merged = reinterpret_cast<Best *>((reinterpret_cast<uintptr_t>(n_sh + 1) + 15) & ~static_cast<uintptr_t>(15));
+    const int64_t g = blockIdx.x;
+    const int lane = lane_id();
+    const int wv = wave_id();
+    const int nwaves = blockDim.x / kWave;
+
+    stage_nodes(nodes, K, N, alpha_s, beta_s);
+    for (int e = threadIdx.x; e < nF_cap * KP; e += blockDim.x) WdT[e] = 0.0;
+    if (wv == 0) {
+        const int n = survivors_from_mask(mask + g * N, N, F);
+        if (lane == 0) *n_sh = n;
+    }
+    __syncthreads();
+    const int nF = *n_sh;
+    const bool good = S < 0 ? nF >= 1 : nF == nF_cap;
+    if (threadIdx.x == 0 && status != nullptr) status[g] = good ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
+    if (!good) return;
+
+    const float *pgroup = preds + static_cast<size_t>(g) * N * C;
+    // first tile of this wave: its first rows are in flight while the weights are evaluated
+    v4f y[kRowChunk];
+    {
+        const int64_t cv_raw = static_cast<int64_t>(wv) * kColsPerTile + lane;
+        const int64_t cv = cv_raw < Cv ? cv_raw : 0;
+        const int floats = (UNAL && C - 4 * cv < 4) ? static_cast<int>(C - 4 * cv) : 4;
+#pragma unroll
+        for (int u = 0; u < kRowChunk; ++u)
+            y[u] = load_pred_vector<UNAL>(pgroup + 4 * cv + static_cast<size_t>(F[u < nF ? u : nF - 1]) * C, floats);
+    }
+    decoder_weights(alpha_s, beta_s, F, nF, K, KP, sign_mode, WdT);
+    __syncthreads();
+
+    Best best[KP];
+#pragma unroll
+    for (int j = 0; j < KP; ++j) {
+        best[j].v = -__builtin_inf();
+        best[j].i = 0x7fffffff;
+    }
+    for (int64_t ct = wv; ct < ctiles; ct += nwaves) {
+        const int64_t cv_raw = ct * kColsPerTile + lane;
+        const bool ok = cv_raw < Cv;
+        const int64_t cv = ok ? cv_raw : 0;
+        const int floats = (UNAL && C - 4 * cv < 4) ? static_cast<int>(C - 4 * cv) : 4;
+        const float *pg = pgroup + 4 * cv;
+        double acc[KP][4];
+#pragma unroll
+        for (int j = 0; j < KP; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[j][e] = 0.0;
+        for (int r0 = 0; r0 < nF; r0 += kRowChunk) {
+            if (r0 > 0 || ct != wv) {
+#pragma unroll
+                for (int u = 0; u < kRowChunk; ++u)
+                    y[u] = load_pred_vector<UNAL>(pg + static_cast<size_t>(F[r0 + u < nF ? r0 + u : nF - 1]) * C, floats);
+            }
+#pragma unroll
+            for (int u = 0; u < kRowChunk; ++u) {
+                if (r0 + u < nF) {
+                    const double *w = WdT + (r0 + u) * KP;
+                    const double y0 = y[u][0], y1 = y[u][1], y2 = y[u][2], y3 = y[u][3];
+#pragma unroll
+                    for (int j = 0; j < KP; ++j) {
+                        const double wj = w[j];
+                        acc[j][0] = fma(wj, y0, acc[j][0]);
+                        acc[j][1] = fma(wj, y1, acc[j][1]);
+                        acc[j][2] = fma(wj, y2, acc[j][2]);
+                        acc[j][3] = fma(wj, y3, acc[j][3]);
+                    }
+                }
+            }
+        }
+        if (ok) {
+#pragma unroll
+            for (int j = 0; j < KP; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int idx = static_cast<int>(cv * 4 + e);
+                    if (e < floats && better(acc[j][e], idx, best[j])) {
+                        best[j].v = acc[j][e];
+                        best[j].i = idx;
+                    }
+                }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < KP; ++j) {
+        // the wave's best: four DPP steps inside each row of 16 lanes, then the four rows by v_readlane
+        best_step<kDppQuadXor1>(best[j]);
+        best_step<kDppQuadXor2>(best[j]);
+        best_step<kDppRowHalfMirror>(best[j]);
+        best_step<kDppRowMirror>(best[j]);
+        Best b = best[j];
+        b.v = read_lane(best[j].v, 0);
+        b.i = __builtin_amdgcn_readlane(best[j].i, 0);
+#pragma unroll
+        for (int row = 1; row < 4; ++row) {
+            const double ov = read_lane(best[j].v, 16 * row);
+            const int oi = __builtin_amdgcn_readlane(best[j].i, 16 * row);
+            if (better(ov, oi, b)) {
+                b.v = ov;
+                b.i = oi;
+            }
+        }
+        if (lane == 0) merged[j * nwaves + wv] = b;
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < K; j += blockDim.x) {
+        Best b = merged[j * nwaves];
+        for (int w2 = 1; w2 < nwaves; ++w2) {
+            const Best o = merged[j * nwaves + w2];
+            if (better(o.v, o.i, b)) b = o;
+        }
+        top1[g * K + j] = b.i == 0x7fffffff ? 0 : b.i;
+        if (score != nullptr) score[g * K + j] = static_cast<float>(b.v);
+    }
+}
+
 // ------------------------------------------------------------------------------------
 // packed kernel for the small shapes of the image-classification operating points
 // ------------------------------------------------------------------------------------
@@ -566,6 +717,27 @@ int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_t
     const int64_t Cv = vec4 ? C / 4 : C;
     if (G > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
     const int KQ = KP / 4;
+    // K <= 16, up to 64 survivors, enough groups to fill the chip: a workgroup per group whose waves keep all K
+    // accumulator rows (few groups with very many classes stay with the quad-per-workgroup split below)
+    if (K <= 16 && (S < 0 ? N : N - S) <= 64 && C >= 4 && !(G * KQ <= 512 && (C + 3) / 4 >= 64 * 16)) {
+        const int64_t sCv = (C + 3) / 4;
+        const int64_t stiles = (sCv + kColsPerTile - 1) / kColsPerTile;
+        const int nwaves = stiles < 4 ? static_cast<int>(stiles) : 4;
+        size_t slds = sizeof(double) * (static_cast<size_t>(S < 0 ? N : N - S) * KP + K + N) + sizeof(int) * (static_cast<size_t>(N) + 3);
+        slds += 16 + sizeof(double) * 2 * static_cast<size_t>(KP) * nwaves;
+        const dim3 sgrid(static_cast<unsigned>(G)), sblock(nwaves * kWave);
+#define APPROXIFER_TOP1_STREAM(KQV, UNAL)                                                                              \
+    hipLaunchKernelGGL((decode_top1_stream_kernel<KQV, UNAL>), sgrid, sblock, slds, stream, d_preds, d_mask, d_top1,      \
+                       d_score, d_status, K, N, S, C, sCv, stiles, sign_mode, nodes)
+        switch (KQ) {
+            case 1: if (vec4) APPROXIFER_TOP1_STREAM(1, false); else APPROXIFER_TOP1_STREAM(1, true); break;
+            case 2: if (vec4) APPROXIFER_TOP1_STREAM(2, false); else APPROXIFER_TOP1_STREAM(2, true); break;
+            case 3: if (vec4) APPROXIFER_TOP1_STREAM(3, false); else APPROXIFER_TOP1_STREAM(3, true); break;
+            default: if (vec4) APPROXIFER_TOP1_STREAM(4, false); else APPROXIFER_TOP1_STREAM(4, true); break;
+        }
+#undef APPROXIFER_TOP1_STREAM
+        return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+    }
     int slices = static_cast<int>((Cv + kWave - 1) / kWave);     // column slices worth a wave of their own
     const int most = G >= 512 ? 4 : 16;                          // few groups: all sixteen waves of a workgroup
     if (slices > most) slices = most;
