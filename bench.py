@@ -273,8 +273,10 @@ def other_workloads(torch, binding, syn, orc_nodes, dev, sign_mode):
     out = torch.empty((w.G, w.K, w.C), dtype=torch.float32, device=dev)
     adv = torch.empty((w.G, w.A), dtype=torch.int32, device=dev)
     st = torch.empty((w.G,), dtype=torch.int32, device=dev)
+    ws = torch.empty((max(binding.approxifer_workspace_bytes(w.G, w.K, w.W, w.S, w.A, w.C), 4),), dtype=torch.uint8, device=dev)
     t = time_launches(torch, lambda: binding.approxifer_decode_byzantine(preds, mask, alpha, beta, w.S, w.A, sign_mode,
-                                                                         out=out, adv=adv, status=st), 20, flush=flush)
+                                                                         out=out, adv=adv, status=st, workspace=ws), 20,
+                      flush=flush)
     located = bool(np.array_equal(adv.cpu().numpy(), adv_true))
     res["byzantine_decode"] = dict(t, predictions_per_s=w.G * w.K / (t["avg_ms"] * 1e-3),
                                    locator_solves_per_s=w.G * w.C / (t["avg_ms"] * 1e-3),
@@ -282,7 +284,7 @@ def other_workloads(torch, binding, syn, orc_nodes, dev, sign_mode):
                                    planted_adversaries_located=located, roofline=alu_roofline(w, t["avg_ms"]), note=COLD)
     # the same groups with Algorithm 1's homogeneous fit as the locator: a singular vector per class
     t = time_launches(torch, lambda: binding.approxifer_decode_byzantine_homogeneous(
-        preds, mask, alpha, beta, w.S, w.A, sign_mode, out=out, adv=adv, status=st), 10, flush=flush)
+        preds, mask, alpha, beta, w.S, w.A, sign_mode, out=out, adv=adv, status=st, workspace=ws), 10, flush=flush)
     located = bool(np.array_equal(adv.cpu().numpy(), adv_true))
     res["byzantine_decode_algorithm1"] = dict(t, predictions_per_s=w.G * w.K / (t["avg_ms"] * 1e-3),
                                               locator_fits_per_s=w.G * w.C / (t["avg_ms"] * 1e-3),
@@ -306,8 +308,10 @@ def other_workloads(torch, binding, syn, orc_nodes, dev, sign_mode):
     out = torch.empty((w.G, w.K, w.C), dtype=torch.float32, device=dev)
     adv = torch.empty((w.G, w.A), dtype=torch.int32, device=dev)
     st = torch.empty((w.G,), dtype=torch.int32, device=dev)
+    ws = torch.empty((max(binding.approxifer_workspace_bytes(w.G, w.K, w.W, w.S, w.A, w.C), 4),), dtype=torch.uint8, device=dev)
     t = time_launches(torch, lambda: binding.approxifer_decode_byzantine(preds, mask, alpha, beta, w.S, w.A, sign_mode,
-                                                                         out=out, adv=adv, status=st), 20, flush=flush)
+                                                                         out=out, adv=adv, status=st, workspace=ws), 20,
+                      flush=flush)
     located = float(np.mean(np.all(adv.cpu().numpy() == adv_true, axis=1)))
     res["mnist_byz_k12_decode"] = dict(t, predictions_per_s=w.G * w.K / (t["avg_ms"] * 1e-3),
                                        locator_solves_per_s=w.G * w.C / (t["avg_ms"] * 1e-3),

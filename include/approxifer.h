@@ -18,10 +18,14 @@
  *   - All tensors are dense, row-major, with the last index contiguous.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
  *     enqueued on it and the call returns without synchronising.  The library allocates
- *     no device memory and keeps no state between calls.
+ *     no device memory and keeps no state between calls; the one kind of scratch memory
+ *     it uses (the Byzantine decoders' workspace) is the caller's.
  *   - Return value: APPROXIFER_OK when the kernels were enqueued; a negative
- *     APPROXIFER_ERR_* code otherwise, in which case nothing was enqueued and no output
- *     was touched.  approxifer_strerror() turns a code into text.
+ *     APPROXIFER_ERR_* code otherwise.  Every code but APPROXIFER_ERR_LAUNCH is decided on
+ *     the host before anything is enqueued: no output is touched.  APPROXIFER_ERR_LAUNCH is
+ *     the HIP runtime's refusal of a launch; a call that consists of two launches (see the
+ *     individual entry points) may then have enqueued the first.  approxifer_strerror()
+ *     turns a code into text.
  *   - G = 0, D = 0 or C = 0 is a valid empty call: nothing is enqueued, OK is returned.
  *   - Limits: 1 <= K <= APPROXIFER_MAX_K, 2 <= N <= APPROXIFER_MAX_N; the Byzantine
  *     decoder additionally needs N - S <= APPROXIFER_MAX_AVAIL_BYZ.
@@ -44,7 +48,7 @@ extern "C" {
 
 #define APPROXIFER_OK 0
 #define APPROXIFER_ERR_NULL_POINTER (-1)   /* a required pointer is NULL */
-#define APPROXIFER_ERR_BAD_SHAPE (-2)      /* negative size, K < 1, N < 2, S < 0, S >= N, A < 1 ... */
+#define APPROXIFER_ERR_BAD_SHAPE (-2)      /* negative size, K < 1, N < 2, S < -1, S >= N, A < 1 ... */
 #define APPROXIFER_ERR_LIMIT (-3)          /* K, N or N-S above the compiled limits */
 #define APPROXIFER_ERR_BAD_NODES (-4)      /* a node is not finite, or two nodes of one set are equal */
 #define APPROXIFER_ERR_TOO_FEW_WORKERS (-5)/* N - S < 2 (K + A): Algorithm 2's system would be under-determined */
@@ -127,11 +131,22 @@ int approxifer_decode(const float *d_preds, const uint8_t *d_mask, float *d_out,
  * adversaries.
  *
  *   d_adv     [G][A] int32, device, written: located workers in ascending order
+ *   d_workspace, workspace_bytes
+ *             device scratch memory owned by the caller, 4-byte aligned, or NULL / 0.  The vote of
+ *             Algorithm 2's return step is the one place where the classes of a group meet.  With few
+ *             groups and many classes the library spreads a group's classes over several workgroups,
+ *             which pool their per-class picks in the workspace (N vote counters and an arrival counter
+ *             per group, cleared by the call itself; contents on entry and exit are meaningless).
+ *             approxifer_workspace_bytes() gives the size that lets it do so.  With NULL, or fewer
+ *             bytes, the call is just as correct and d_out, d_adv, d_status hold the same values: every
+ *             group then stays with one workgroup, which is slower only for few groups with hundreds
+ *             of classes or more.  Nothing but the workspace is ever used as scratch: output rows are
+ *             written once, with their final values.  The workspace must not be shared with a call
+ *             that may run concurrently.
  *   other arguments as approxifer_decode(); groups with a bad mask leave d_out and
- *   d_adv rows untouched.  While the call runs, the d_out rows of the other groups also
- *   serve as working storage (with few groups and many classes several workgroups share
- *   a group and pool their votes there); they hold the result when the work enqueued by
- *   the call has completed.
+ *   d_adv rows untouched.
+ * On APPROXIFER_ERR_LAUNCH the kernel that clears the workspace may have been enqueued; no output
+ * is touched.
  * Requires A >= 1, N - S >= 2 (K + A) (Section 3, eq. (3), the decoding condition) and
  * N - S <= APPROXIFER_MAX_AVAIL_BYZ.  With S = APPROXIFER_S_FROM_MASK a group is decoded when its
  * own number of available workers n satisfies 2 (K + A) <= n <= APPROXIFER_MAX_AVAIL_BYZ and gets
@@ -142,7 +157,18 @@ int approxifer_decode(const float *d_preds, const uint8_t *d_mask, float *d_out,
 int approxifer_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *d_out,
                                 int32_t *d_adv, int32_t *d_status,
                                 int64_t G, int K, int N, int S, int A, int64_t C,
-                                const double *h_alpha, const double *h_beta, int sign_mode, void *stream);
+                                const double *h_alpha, const double *h_beta, int sign_mode,
+                                void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Size in bytes of the workspace with which approxifer_decode_byzantine() and
+ * approxifer_decode_byzantine_homogeneous() run fastest for this shape (Algorithm 2, return step: the
+ * per-class picks of a group are pooled there when its classes are spread over several workgroups).
+ * 0 when the shape needs none -- enough groups to fill the GPU with one workgroup each, or few
+ * classes -- and for shapes the decoders refuse.  Host arithmetic only; at most
+ * 4 (N + 1) bytes per group, rounded up to a multiple of 256.
+ */
+size_t approxifer_workspace_bytes(int64_t G, int K, int N, int S, int A, int64_t C);
 
 /*
  * Byzantine decoder with the locator of Section 2, Algorithm 1, in place of Algorithm 2: the
@@ -156,13 +182,16 @@ int approxifer_decode_byzantine(const float *d_preds, const uint8_t *d_mask, flo
  * defined up to one factor, which the order of the |a_i| does not see.  Unlike Algorithm 2
  * this locator can find a worker whose node is exactly 0.  It costs a singular value
  * decomposition per class where Algorithm 2 costs a least-squares solve.
+ * The iterations are bounded (24 rounds of inverse iteration, then at most 30 Jacobi sweeps); a
+ * class whose columns are still not orthogonal to rounding after that -- not observed on finite
+ * data -- votes with the shortest column found so far, best effort, and no status reports it.
  * Arguments, requirements and error behaviour as approxifer_decode_byzantine().
  */
 int approxifer_decode_byzantine_homogeneous(const float *d_preds, const uint8_t *d_mask, float *d_out,
                                             int32_t *d_adv, int32_t *d_status,
                                             int64_t G, int K, int N, int S, int A, int64_t C,
                                             const double *h_alpha, const double *h_beta, int sign_mode,
-                                            void *stream);
+                                            void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Fused decoder + top-1 (Section 4.1, "Performance metric": the paper scores the class of the

@@ -31,6 +31,7 @@ EXPORTS = (
     "approxifer_decode_top1",
     "approxifer_decode_byzantine",
     "approxifer_decode_byzantine_homogeneous",
+    "approxifer_workspace_bytes",
 )
 
 _lib = None
@@ -71,7 +72,11 @@ def load() -> ctypes.CDLL:
                                            ctypes.c_int64, c_dp, c_dp, ctypes.c_int, vp]
     lib.approxifer_decode_byzantine.restype = ctypes.c_int
     lib.approxifer_decode_byzantine.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
-                                                ctypes.c_int, ctypes.c_int, ctypes.c_int64, c_dp, c_dp, ctypes.c_int, vp]
+                                                ctypes.c_int, ctypes.c_int, ctypes.c_int64, c_dp, c_dp, ctypes.c_int,
+                                                vp, ctypes.c_size_t, vp]
+    lib.approxifer_workspace_bytes.restype = ctypes.c_size_t
+    lib.approxifer_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                               ctypes.c_int64]
     lib.approxifer_decode_byzantine_homogeneous.restype = ctypes.c_int
     lib.approxifer_decode_byzantine_homogeneous.argtypes = lib.approxifer_decode_byzantine.argtypes
     lib.approxifer_wait_mask.restype = ctypes.c_int
@@ -182,7 +187,15 @@ def approxifer_decode_top1(preds, mask, alpha, beta, S, sign_mode=SIGN_WORKER_IN
     return top1, score, status
 
 
-def _decode_byzantine(entry, preds, mask, alpha, beta, S, A, sign_mode, out, adv, status, stream):
+def approxifer_workspace_bytes(G: int, K: int, N: int, S: int, A: int, C: int) -> int:
+    """Bytes of device scratch memory with which the Byzantine decoders run fastest at this shape (0: none needed)."""
+    return int(load().approxifer_workspace_bytes(int(G), int(K), int(N), int(S), int(A), int(C)))
+
+
+NO_WORKSPACE = object()
+
+
+def _decode_byzantine(entry, preds, mask, alpha, beta, S, A, sign_mode, out, adv, status, stream, workspace):
     import torch
     a, ap = _nodes(alpha)
     b, bp = _nodes(beta)
@@ -196,26 +209,39 @@ def _decode_byzantine(entry, preds, mask, alpha, beta, S, A, sign_mode, out, adv
         adv = torch.full((G, max(int(A), 0)), -1, dtype=torch.int32, device=preds.device)
     if status is None:
         status = torch.full((G,), -1, dtype=torch.int32, device=preds.device)
+    if workspace is None:
+        # the caller left the workspace to the binding: a buffer of the size the library asks for
+        need = approxifer_workspace_bytes(G, K, N, S, A, C)
+        workspace = torch.empty((need,), dtype=torch.uint8, device=preds.device) if need else NO_WORKSPACE
+    if workspace is NO_WORKSPACE:
+        ws_ptr, ws_bytes = None, 0
+    else:
+        if not isinstance(workspace, torch.Tensor) or not workspace.is_cuda or not workspace.is_contiguous():
+            raise TypeError("workspace must be a contiguous tensor in device memory")
+        ws_ptr, ws_bytes = ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
     _check(getattr(load(), entry)(_dev(preds, torch.float32), _dev(mask, torch.uint8, (G, N)),
-                                  _dev(out, torch.float32, (G, K, C)), _dev(adv, torch.int32),
+                                  _dev(out, torch.float32, (G, K, C)), _dev(adv, torch.int32, (G, int(A))),
                                   _dev(status, torch.int32, (G,)), G, K, N, int(S), int(A), C, ap, bp,
-                                  int(sign_mode), ctypes.c_void_p(_stream_handle(stream))))
+                                  int(sign_mode), ws_ptr, ctypes.c_size_t(ws_bytes),
+                                  ctypes.c_void_p(_stream_handle(stream))))
     return out, adv, status
 
 
 def approxifer_decode_byzantine(preds, mask, alpha, beta, S, A, sign_mode=SIGN_WORKER_INDEX, out=None, adv=None,
-                                status=None, stream=None):
+                                status=None, stream=None, workspace=None):
     """As approxifer_decode, after locating and dropping A adversaries per group.
-    Returns (out [G, K, C] float32, adv [G, A] int32 ascending, status [G] int32)."""
+    Returns (out [G, K, C] float32, adv [G, A] int32 ascending, status [G] int32).
+    workspace: a device tensor (any dtype) passed as the C ABI's d_workspace / workspace_bytes; None allocates
+    approxifer_workspace_bytes() bytes for this call; NO_WORKSPACE passes NULL / 0."""
     return _decode_byzantine("approxifer_decode_byzantine", preds, mask, alpha, beta, S, A, sign_mode, out, adv,
-                             status, stream)
+                             status, stream, workspace)
 
 
 def approxifer_decode_byzantine_homogeneous(preds, mask, alpha, beta, S, A, sign_mode=SIGN_WORKER_INDEX, out=None,
-                                            adv=None, status=None, stream=None):
+                                            adv=None, status=None, stream=None, workspace=None):
     """As approxifer_decode_byzantine, with Algorithm 1's homogeneous fit as the per-class locator."""
     return _decode_byzantine("approxifer_decode_byzantine_homogeneous", preds, mask, alpha, beta, S, A, sign_mode,
-                             out, adv, status, stream)
+                             out, adv, status, stream, workspace)
 
 
 def approxifer_wait_mask(arrival, wait_for, mask=None, count=None, stream=None):

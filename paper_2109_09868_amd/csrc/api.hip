@@ -36,7 +36,7 @@ int check_common(int K, int N, const double *h_alpha, const double *h_beta, Node
 
 extern "C" {
 
-int approxifer_version(void) { return 200; }   // 0.2.0: approxifer_wait_mask, APPROXIFER_S_FROM_MASK
+int approxifer_version(void) { return 300; }   // 0.3.0: workspace arguments of the Byzantine decoders
 
 const char *approxifer_strerror(int code) {
     switch (code) {
@@ -107,7 +107,7 @@ int approxifer_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t 
 static int decode_byzantine_checked(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
                                     int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C,
                                     const double *h_alpha, const double *h_beta, int sign_mode, bool homogeneous,
-                                    void *stream) {
+                                    void *d_workspace, size_t workspace_bytes, void *stream) {
     if (G < 0 || C < 0) return APPROXIFER_ERR_BAD_SHAPE;
     Nodes nodes;
     const int rc = check_common(K, N, h_alpha, h_beta, &nodes);
@@ -122,22 +122,33 @@ static int decode_byzantine_checked(const float *d_preds, const uint8_t *d_mask,
     if (d_mask == nullptr || d_adv == nullptr || d_preds == nullptr || d_out == nullptr)
         return APPROXIFER_ERR_NULL_POINTER;
     return approxifer::launch_decode_byzantine(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, S, A, C, nodes,
-                                               sign_mode, homogeneous, static_cast<hipStream_t>(stream));
+                                               sign_mode, homogeneous, d_workspace, workspace_bytes,
+                                               static_cast<hipStream_t>(stream));
 }
 
 int approxifer_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
                                 int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C,
-                                const double *h_alpha, const double *h_beta, int sign_mode, void *stream) {
+                                const double *h_alpha, const double *h_beta, int sign_mode, void *d_workspace,
+                                size_t workspace_bytes, void *stream) {
     return decode_byzantine_checked(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, S, A, C, h_alpha, h_beta,
-                                    sign_mode, false, stream);
+                                    sign_mode, false, d_workspace, workspace_bytes, stream);
 }
 
 int approxifer_decode_byzantine_homogeneous(const float *d_preds, const uint8_t *d_mask, float *d_out,
                                             int32_t *d_adv, int32_t *d_status, int64_t G, int K, int N, int S,
                                             int A, int64_t C, const double *h_alpha, const double *h_beta,
-                                            int sign_mode, void *stream) {
+                                            int sign_mode, void *d_workspace, size_t workspace_bytes, void *stream) {
     return decode_byzantine_checked(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, S, A, C, h_alpha, h_beta,
-                                    sign_mode, true, stream);
+                                    sign_mode, true, d_workspace, workspace_bytes, stream);
+}
+
+size_t approxifer_workspace_bytes(int64_t G, int K, int N, int S, int A, int64_t C) {
+    // the shapes the Byzantine decoders accept; anything else needs no workspace because the call is refused
+    if (G <= 0 || C <= 0 || K < 1 || K > APPROXIFER_MAX_K || N < 2 || N > APPROXIFER_MAX_N) return 0;
+    if (S < APPROXIFER_S_FROM_MASK || S >= N || A < 1) return 0;
+    const int most_available = S < 0 ? N : N - S;
+    if (most_available < 2 * (K + A) || (S >= 0 && N - S > APPROXIFER_MAX_AVAIL_BYZ)) return 0;
+    return approxifer::byzantine_workspace_bytes(G, K, N, S, A, C);
 }
 
 int approxifer_wait_mask(const float *d_arrival, uint8_t *d_mask, int32_t *d_count, int64_t G, int N, int wait_for,

@@ -86,15 +86,15 @@ __device__ __forceinline__ void select_adversaries(int32_t *__restrict__ adv_g, 
 }
 
 // Several workgroups share a group (few groups, many classes: each takes part of the classes).  They meet in the
-// first N+1 words of the group's own output rows -- N vote counters and an arrival counter, cleared by
-// clear_group_votes_kernel before the launch, overwritten by the decode afterwards.  These words are touched by
-// device-scope atomics only, which act where all workgroups of the device see them.  A part's additions have been
-// carried out once their old values are back; only then does it count itself in: no cache write-back or invalidation
-// (a fence) is needed, and none of the part's other memory traffic has to be ordered with this.  No part waits for
-// another: whichever arrives last gets every vote (into `votes`, LDS) and true, and finishes the group.
+// group's N+1 words of the caller's workspace -- N vote counters and an arrival counter, cleared by
+// clear_workspace_kernel before the launch.  These words are touched by device-scope atomic read-modify-writes only,
+// which are carried out at the one place all workgroups of the device share.  A part's additions have been carried
+// out once their old values are back; only then does it count itself in, and the part that counts itself in last
+// reads the votes with the same kind of operation: no cache write-back or invalidation (a fence) is needed, and none
+// of the part's other memory traffic has to be ordered with this.  No part waits for another: whichever arrives last
+// gets every vote (into `votes`, LDS) and true, and finishes the group.
 // Called by the whole workgroup after a barrier that follows its last vote; ends with a barrier when it returns true.
-__device__ __forceinline__ bool pool_votes_last_arrival(float *og, int *votes, int N, int splits, int *flag) {
-    int *gvotes = reinterpret_cast<int *>(og);
+__device__ __forceinline__ bool pool_votes_last_arrival(int *gvotes, int *votes, int N, int splits, int *flag) {
     const int tid = threadIdx.x;
     int seen = 0;
     for (int i = tid; i < N; i += blockDim.x)
@@ -106,7 +106,7 @@ __device__ __forceinline__ bool pool_votes_last_arrival(float *og, int *votes, i
     __syncthreads();
     if (*flag == 0) return false;
     for (int i = tid; i < N; i += blockDim.x)
-        votes[i] = __hip_atomic_load(&gvotes[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        votes[i] = __hip_atomic_fetch_add(&gvotes[i], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     return true;
 }
@@ -422,7 +422,7 @@ template <int NB, int RM>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 && NB <= 28 ? 3 : 2))) void decode_byzantine_proj_kernel(
     const float *__restrict__ preds, const uint8_t *__restrict__ mask, float *__restrict__ out,
     int32_t *__restrict__ adv, int32_t *__restrict__ status, int K, int N, int S, int A, int64_t C, int64_t Cv,
-    int vec4, int sign_mode, int n_cap, int cw_log2, int splits, const Nodes nodes) {
+    int vec4, int sign_mode, int n_cap, int cw_log2, int splits, int32_t *__restrict__ workspace, const Nodes nodes) {
     extern __shared__ __align__(16) double lds_d[];
     const int KP = round_up4(K);
     const int M = K + A;
@@ -516,7 +516,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
     __syncthreads();
 
     float *og = out + static_cast<size_t>(g) * K * C;
-    if (splits > 1 && !pool_votes_last_arrival(og, votes, N, splits, n_sh + 1)) return;
+    if (splits > 1 && !pool_votes_last_arrival(workspace + g * (N + 1), votes, N, splits, n_sh + 1)) return;
     const bool staged = C <= CW;                          // the one tile holds every prediction of the group
     select_adversaries(adv + g * A, avail, n, N, A, votes, sel, F, Fpos);
     const int nF = n - A;
@@ -823,7 +823,7 @@ __global__ void decode_byzantine_general_kernel(const float *__restrict__ preds,
                                                 float *__restrict__ out, int32_t *__restrict__ adv,
                                                 int32_t *__restrict__ status, int K, int N, int S, int A, int64_t C,
                                                 int64_t Cv, int vec4, int sign_mode, int cpw, int n_cap,
-                                                int splits, const Nodes nodes) {
+                                                int splits, int32_t *__restrict__ workspace, const Nodes nodes) {
     extern __shared__ __align__(16) double lds_d[];
     const int KP = round_up4(K);
     const int M = K + A;
@@ -868,88 +868,161 @@ __global__ void decode_byzantine_general_kernel(const float *__restrict__ preds,
         locate_classes_wave<HOMOG>(pg, C, c0, cpw, avail, xs, n, M, A, scratch + static_cast<size_t>(wv) * wave_doubles,
                                    votes);
     __syncthreads();
-    if (splits > 1 && !pool_votes_last_arrival(out + static_cast<size_t>(g) * K * C, votes, N, splits, n_sh + 1)) return;
+    if (splits > 1 && !pool_votes_last_arrival(workspace + g * (N + 1), votes, N, splits, n_sh + 1)) return;
 
     finish_group(pg, out + static_cast<size_t>(g) * K * C, adv + g * A, avail, n, N, A, K, KP, C, Cv, vec4 != 0, sign_mode,
                  alpha_s, beta_s, votes, sel, F, Fpos, WdT);
 }
 
-// Before a launch in which several workgroups share a group: zero the N+1 words at the head of every group's output
-// rows through which they meet.  Groups whose mask the decoder will reject keep their output untouched.
-__global__ void clear_group_votes_kernel(const uint8_t *__restrict__ mask, float *__restrict__ out, int64_t G, int K, int N,
-                                         int S, int M, int64_t C, int n_cap) {
-    const int64_t g = static_cast<int64_t>(blockIdx.x) * (blockDim.x / kWave) + wave_id();
-    if (g >= G) return;
-    const int lane = lane_id();
-    const uint8_t *row = mask + g * N;
-    const int n = __popcll(__ballot(lane < N && row[lane] != 0)) + __popcll(__ballot(lane + kWave < N && row[lane + kWave] != 0));
-    const bool good = S < 0 ? (n >= 2 * M && n <= n_cap) : n == n_cap;
-    if (!good) return;
-    int *gvotes = reinterpret_cast<int *>(out + static_cast<size_t>(g) * K * C);
-    for (int i = lane; i <= N; i += kWave) gvotes[i] = 0;
+// Before a launch in which several workgroups share a group: zero the workspace words through which they meet.
+// (A kernel, not a memset: the call may be recorded into a HIP graph.)
+__global__ void clear_workspace_kernel(int32_t *__restrict__ workspace, int64_t words) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < words) workspace[i] = 0;
 }
 
-template <int NB, int RM>
-int run_proj(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv, int32_t *d_status, int64_t G,
-             int K, int N, int S, int A, int64_t C, int n_cap, bool vec4, const Nodes &nodes, int sign_mode,
-             hipStream_t stream) {
-    const int KP = (K + 3) & ~3;
-    const int64_t Cv = vec4 ? C / 4 : C;
-    const int cw_log2 = C <= 16 ? 4 : (C <= 32 ? 5 : 6);            // classes per staged tile: 16, 32 or 64
-    const int CW = 1 << cw_log2;
+// ---- launch shapes (host) --------------------------------------------------------------------------
+constexpr int64_t kFillWaves = 4096;     // waves that put about four on every SIMD of the chip (256 CUs x 4 SIMDs)
+
+bool proj_domain(int M, int n) { return M <= kProjMaxM && n <= 48 && n - M <= 32; }
+
+struct ProjShape {
+    int cw_log2, nw, splits;
+};
+// `may_split`: the caller brought a workspace for the workgroups of a group to meet in.
+ProjShape proj_shape(int64_t G, int64_t C, bool may_split) {
+    ProjShape p;
+    p.cw_log2 = C <= 16 ? 4 : (C <= 32 ? 5 : 6);           // classes per staged tile: 16, 32 or 64
+    const int CW = 1 << p.cw_log2;
     // waves per workgroup: one per four classes of a tile, at most four -- but no more than it takes to put
-    // about four waves on every SIMD of the chip (1024 SIMDs): beyond that, extra waves of a group only
+    // about four waves on every SIMD of the chip: beyond that, extra waves of a group only
     // idle through the shared factorisation (measured at G = 2048, C = 10: 1 wave 44.7 us, 2 waves 42.7, 3 waves 53.0)
     int nw = static_cast<int>(((C < CW ? C : CW) + kClsPerWave - 1) / kClsPerWave);
     if (nw > 4) nw = 4;
-    const int64_t fill = (4096 + G - 1) / G;
+    const int64_t fill = (kFillWaves + G - 1) / G;
     if (nw > fill) nw = static_cast<int>(fill);
-    const size_t lds = sizeof(double) * (static_cast<size_t>(ush_rows(RM)) * ush_stride(NB) + NB * kPwStride + NB +
-                                         static_cast<size_t>(n_cap - A) * KP + K + N) +
-                       sizeof(float) * (static_cast<size_t>(NB) * CW) + sizeof(int) * (5 * static_cast<size_t>(N) + 2);
-    if (lds > 64 * 1024) return APPROXIFER_ERR_LIMIT;      // cannot happen inside the projected kernel's domain
+    p.nw = nw;
     // Few groups with many classes: one workgroup per group would leave most of the chip idle while each group walks
     // through its class tiles.  Then several workgroups share a group, each repeating the shared factorisation and
     // taking every splits-th tile, up to about 4096 waves in all.  From four tiles on: with fewer the repeated
     // factorisation and the extra launch cost what the split saves (G = 512, C = 100: 51 us whole, 59 us split).
     const int64_t tiles = (C + CW - 1) / CW;
-    int splits = 1;
-    if (tiles >= 4 && static_cast<int64_t>(K) * C >= N + 1) {
-        const int64_t want = 4096 / (G * nw);
-        splits = static_cast<int>(want < tiles ? want : tiles);
-        if (splits < 1) splits = 1;
+    p.splits = 1;
+    if (may_split && tiles >= 4) {
+        const int64_t want = kFillWaves / (G * nw);
+        p.splits = static_cast<int>(want < tiles ? want : tiles);
+        if (p.splits < 1) p.splits = 1;
     }
-    if (G * splits > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
-    if (splits > 1) {
-        const int per_block = 4;
-        hipLaunchKernelGGL(clear_group_votes_kernel, dim3(static_cast<unsigned>((G + per_block - 1) / per_block)),
-                           dim3(per_block * kWave), 0, stream, d_mask, d_out, G, K, N, S, K + A, C, n_cap);
-        if (hipGetLastError() != hipSuccess) return APPROXIFER_ERR_LAUNCH;
+    return p;
+}
+
+struct GeneralShape {
+    int cpw, nw, splits;
+    size_t lds;                                            // 0: the shape does not fit the workgroup's LDS
+};
+GeneralShape general_shape(int64_t G, int K, int N, int n, int A, int64_t C, bool homogeneous, bool may_split) {
+    GeneralShape s;
+    const int KP = (K + 3) & ~3;
+    const int M = K + A;
+    // classes per wave: a class takes 2M lanes; waves per workgroup: enough for all classes, at most 4
+    int cpw = kWave / (2 * M);
+    if (cpw < 1) cpw = 1;
+    if (cpw > C) cpw = static_cast<int>(C);
+    const size_t fixed = sizeof(double) * (static_cast<size_t>(n - A) * KP + n + K + N) + sizeof(int) * (5 * static_cast<size_t>(N) + 2);
+    const size_t per_class = sizeof(double) * (static_cast<size_t>(n) * (homogeneous ? 2 * M + 1 : 2 * M) + M + n);
+    const size_t budget = 64 * 1024;
+    while (cpw > 1 && fixed + cpw * per_class > budget) --cpw;
+    const size_t per_wave = cpw * per_class;
+    s.cpw = cpw;
+    s.nw = 1;
+    s.splits = 1;
+    s.lds = 0;
+    if (fixed + per_wave > budget) return s;
+    int nw = static_cast<int>((C + cpw - 1) / cpw);
+    if (nw > 4) nw = 4;
+    if (nw > static_cast<int>((budget - fixed) / per_wave)) nw = static_cast<int>((budget - fixed) / per_wave);
+    if (nw < 1) nw = 1;
+    s.nw = nw;
+    s.lds = fixed + nw * per_wave;
+    // few groups, many classes: several workgroups share a group, as in the projected kernel (from four passes of a
+    // workgroup over its classes on)
+    const int64_t passes = (C + static_cast<int64_t>(nw) * cpw - 1) / (static_cast<int64_t>(nw) * cpw);
+    if (may_split && passes >= 4) {
+        const int64_t want = kFillWaves / (G * nw);
+        s.splits = static_cast<int>(want < passes ? want : passes);
+        if (s.splits < 1) s.splits = 1;
     }
-    const dim3 grid(static_cast<unsigned>(G * splits)), block(nw * kWave);
-    hipLaunchKernelGGL((decode_byzantine_proj_kernel<NB, RM>), grid, block, lds, stream, d_preds, d_mask, d_out, d_adv,
-                       d_status, K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, n_cap, cw_log2, splits, nodes);
-    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+    return s;
+}
+
+// most available workers a group can bring (S < 0: read off each mask)
+int avail_capacity(int N, int S) { return S < 0 ? (N < APPROXIFER_MAX_AVAIL_BYZ ? N : APPROXIFER_MAX_AVAIL_BYZ) : N - S; }
+
+int clear_workspace(int32_t *ws, int64_t G, int N, hipStream_t stream) {
+    const int64_t words = G * (N + 1);
+    const int threads = 256;
+    return launch_status(launch_kernel(clear_workspace_kernel, dim3(static_cast<unsigned>((words + threads - 1) / threads)),
+                                       dim3(threads), 0, stream, ws, words));
+}
+
+template <int NB, int RM>
+int run_proj(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv, int32_t *d_status, int64_t G,
+             int K, int N, int S, int A, int64_t C, int n_cap, bool vec4, const Nodes &nodes, int sign_mode,
+             int32_t *ws, hipStream_t stream) {
+    const int KP = (K + 3) & ~3;
+    const int64_t Cv = vec4 ? C / 4 : C;
+    const ProjShape p = proj_shape(G, C, ws != nullptr);
+    const int CW = 1 << p.cw_log2;
+    const size_t lds = sizeof(double) * (static_cast<size_t>(ush_rows(RM)) * ush_stride(NB) + NB * kPwStride + NB +
+                                         static_cast<size_t>(n_cap - A) * KP + K + N) +
+                       sizeof(float) * (static_cast<size_t>(NB) * CW) + sizeof(int) * (5 * static_cast<size_t>(N) + 2);
+    if (lds > 64 * 1024) return APPROXIFER_ERR_LIMIT;      // cannot happen inside the projected kernel's domain
+    if (G * p.splits > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    if (p.splits > 1) {
+        const int rc = clear_workspace(ws, G, N, stream);
+        if (rc != APPROXIFER_OK) return rc;
+    }
+    const dim3 grid(static_cast<unsigned>(G * p.splits)), block(p.nw * kWave);
+    return launch_status(launch_kernel(decode_byzantine_proj_kernel<NB, RM>, grid, block, lds, stream, d_preds, d_mask, d_out,
+                                       d_adv, d_status, K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, n_cap, p.cw_log2,
+                                       p.splits, ws, nodes));
 }
 
 }  // namespace
 
+size_t byzantine_workspace_bytes(int64_t G, int K, int N, int S, int A, int64_t C) {
+    const int n = avail_capacity(N, S);
+    const int M = K + A;
+    bool splits = false;
+    if (proj_domain(M, n)) splits = proj_shape(G, C, true).splits > 1;
+    else splits = general_shape(G, K, N, n, A, C, false, true).splits > 1;
+    splits = splits || general_shape(G, K, N, n, A, C, true, true).splits > 1;       // Algorithm 1's locator
+    if (!splits) return 0;
+    const size_t bytes = sizeof(int32_t) * static_cast<size_t>(G) * (N + 1);
+    return (bytes + 255) & ~static_cast<size_t>(255);
+}
+
 int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
                             int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C, const Nodes &nodes,
-                            int sign_mode, bool homogeneous, hipStream_t stream) {
-    const int KP = (K + 3) & ~3;
-    // capacity: the most available workers a group can bring (S < 0: read off each mask)
-    const int n = S < 0 ? (N < APPROXIFER_MAX_AVAIL_BYZ ? N : APPROXIFER_MAX_AVAIL_BYZ) : N - S;
+                            int sign_mode, bool homogeneous, void *d_workspace, size_t workspace_bytes,
+                            hipStream_t stream) {
+    const int n = avail_capacity(N, S);
     const int M = K + A;
     const bool vec4 = (C % 4 == 0) && aligned16(d_preds) && aligned16(d_out);
     const int64_t Cv = vec4 ? C / 4 : C;
     if (G > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    // the workgroups of a group meet in the workspace: without one that holds N + 1 words per group, and is aligned
+    // for them, every group stays with one workgroup
+    int32_t *ws = nullptr;
+    if (d_workspace != nullptr && reinterpret_cast<uintptr_t>(d_workspace) % sizeof(int32_t) == 0 &&
+        workspace_bytes / sizeof(int32_t) / static_cast<size_t>(N + 1) >= static_cast<size_t>(G))
+        ws = static_cast<int32_t *>(d_workspace);
 
-    if (!homogeneous && M <= kProjMaxM && n <= 48 && n - M <= 32) {
+    if (!homogeneous && proj_domain(M, n)) {
         // register tiles <rows of [V | I], rows of the projected system>: the smallest that holds (n, n - M)
 #define APPROXIFER_PROJ(NB, RM)                                                                                        \
     if (n <= NB && n - M <= RM)                                                                                        \
-        return run_proj<NB, RM>(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, S, A, C, n, vec4, nodes, sign_mode, stream);
+        return run_proj<NB, RM>(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, S, A, C, n, vec4, nodes, sign_mode, ws, stream);
         APPROXIFER_PROJ(20, 10)       // n = 2M, the minimum of eq. (3), up to K + A = 10
         APPROXIFER_PROJ(20, 12)
         APPROXIFER_PROJ(24, 12)       // n = 2M up to K + A = 12
@@ -962,45 +1035,17 @@ int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *
 #undef APPROXIFER_PROJ
     }
 
-    // classes per wave: a class takes 2M lanes; waves per workgroup: enough for all classes, at most 4
-    int cpw = kWave / (2 * M);
-    if (cpw < 1) cpw = 1;
-    if (cpw > C) cpw = static_cast<int>(C);
-    const size_t fixed = sizeof(double) * (static_cast<size_t>(n - A) * KP + n + K + N) + sizeof(int) * (5 * static_cast<size_t>(N) + 2);
-    const size_t per_class = sizeof(double) * (static_cast<size_t>(n) * (homogeneous ? 2 * M + 1 : 2 * M) + M + n);
-    const size_t budget = 64 * 1024;
-    while (cpw > 1 && fixed + cpw * per_class > budget) --cpw;
-    const size_t per_wave = cpw * per_class;
-    if (fixed + per_wave > budget) return APPROXIFER_ERR_LIMIT;
-    int nw = static_cast<int>((C + cpw - 1) / cpw);
-    if (nw > 4) nw = 4;
-    if (nw > static_cast<int>((budget - fixed) / per_wave)) nw = static_cast<int>((budget - fixed) / per_wave);
-    if (nw < 1) nw = 1;
-    const size_t lds = fixed + nw * per_wave;
-    // few groups, many classes: several workgroups share a group, as in the projected kernel (from four passes of a
-    // workgroup over its classes on)
-    const int64_t passes = (C + static_cast<int64_t>(nw) * cpw - 1) / (static_cast<int64_t>(nw) * cpw);
-    int splits = 1;
-    if (passes >= 4 && static_cast<int64_t>(K) * C >= N + 1) {
-        const int64_t want = 4096 / (G * nw);
-        splits = static_cast<int>(want < passes ? want : passes);
-        if (splits < 1) splits = 1;
+    const GeneralShape sh = general_shape(G, K, N, n, A, C, homogeneous, ws != nullptr);
+    if (sh.lds == 0) return APPROXIFER_ERR_LIMIT;
+    if (G * sh.splits > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    if (sh.splits > 1) {
+        const int rc = clear_workspace(ws, G, N, stream);
+        if (rc != APPROXIFER_OK) return rc;
     }
-    if (G * splits > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
-    if (splits > 1) {
-        const int per_block = 4;
-        hipLaunchKernelGGL(clear_group_votes_kernel, dim3(static_cast<unsigned>((G + per_block - 1) / per_block)),
-                           dim3(per_block * kWave), 0, stream, d_mask, d_out, G, K, N, S, M, C, n);
-        if (hipGetLastError() != hipSuccess) return APPROXIFER_ERR_LAUNCH;
-    }
-    const dim3 grid(static_cast<unsigned>(G * splits)), block(nw * kWave);
-    if (homogeneous)
-        hipLaunchKernelGGL(decode_byzantine_general_kernel<true>, grid, block, lds, stream, d_preds, d_mask, d_out, d_adv,
-                           d_status, K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, cpw, n, splits, nodes);
-    else
-        hipLaunchKernelGGL(decode_byzantine_general_kernel<false>, grid, block, lds, stream, d_preds, d_mask, d_out, d_adv,
-                           d_status, K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, cpw, n, splits, nodes);
-    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+    const dim3 grid(static_cast<unsigned>(G * sh.splits)), block(sh.nw * kWave);
+    return launch_status(launch_kernel(homogeneous ? decode_byzantine_general_kernel<true> : decode_byzantine_general_kernel<false>,
+                                       grid, block, sh.lds, stream, d_preds, d_mask, d_out, d_adv, d_status, K, N, S, A, C, Cv,
+                                       vec4 ? 1 : 0, sign_mode, sh.cpw, n, sh.splits, ws, nodes));
 }
 
 }  // namespace approxifer

@@ -4,6 +4,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <type_traits>
+#include <utility>
+
 #include "approxifer.h"
 
 namespace approxifer {
@@ -93,7 +97,24 @@ __device__ __forceinline__ BerrutTerm berrut_term(double z, double x, double sig
     return r;
 }
 
-// Host-side launchers (defined in encode.hip / decode.hip).
+// Enqueues `kernel` and returns the status of THIS launch.  An error that an earlier, unrelated HIP call left in the
+// calling thread's error state is neither taken for a failure of the launch nor cleared from the caller's view.
+template <typename... Params, size_t... I>
+inline hipError_t launch_kernel_indexed(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                                        std::tuple<std::remove_cv_t<Params>...> &vals, std::index_sequence<I...>) {
+    void *ptrs[] = {static_cast<void *>(&std::get<I>(vals))...};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, lds, stream);
+}
+template <typename... Params, typename... Args>
+inline hipError_t launch_kernel(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                                Args &&...args) {
+    static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
+    std::tuple<std::remove_cv_t<Params>...> vals(static_cast<std::remove_cv_t<Params>>(args)...);
+    return launch_kernel_indexed(kernel, grid, block, lds, stream, vals, std::index_sequence_for<Params...>{});
+}
+inline int launch_status(hipError_t e) { return e == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH; }
+
+// Host-side launchers (defined in encode.hip / decode.hip / byzantine.hip).
 int launch_encode(const float *d_queries, float *d_coded, int64_t G, int K, int N, int64_t D,
                   const Nodes &nodes, hipStream_t stream);
 int launch_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_status,
@@ -104,7 +125,9 @@ int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_t
                        int sign_mode, hipStream_t stream);
 int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
                             int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C,
-                            const Nodes &nodes, int sign_mode, bool homogeneous, hipStream_t stream);
+                            const Nodes &nodes, int sign_mode, bool homogeneous, void *d_workspace,
+                            size_t workspace_bytes, hipStream_t stream);
+size_t byzantine_workspace_bytes(int64_t G, int K, int N, int S, int A, int64_t C);
 
 int launch_wait_mask(const float *d_arrival, uint8_t *d_mask, int32_t *d_count, int64_t G, int N, int wait_for,
                      hipStream_t stream);

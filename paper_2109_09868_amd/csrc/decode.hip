@@ -641,19 +641,17 @@ int run_packed(bool top1_variant, const float *d_preds, const uint8_t *d_mask, f
     if (blocks > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
     const dim3 grid(static_cast<unsigned>(blocks)), block(groups * kWave);
 #define APPROXIFER_PACKED(TOP1, KT, RT, GROUPS)                                                                        \
-    hipLaunchKernelGGL((decode_packed_kernel<TOP1, KT, RT, GROUPS>), grid, block, 0, stream, d_preds, d_mask, d_out,      \
-                       d_top1, d_score, d_status, G, K, N, S, static_cast<int>(C), sign_mode, nodes)
+    launch_status(launch_kernel(decode_packed_kernel<TOP1, KT, RT, GROUPS>, grid, block, 0, stream, d_preds, d_mask,     \
+                                d_out, d_top1, d_score, d_status, G, K, N, S, static_cast<int>(C), sign_mode, nodes))
     if (top1_variant) {
-        if (tile == 0) APPROXIFER_PACKED(true, 16, 16, 4);
-        else if (tile == 1) APPROXIFER_PACKED(true, 16, 32, 4);
-        else APPROXIFER_PACKED(true, 32, 64, 2);
-    } else {
-        if (tile == 0) APPROXIFER_PACKED(false, 16, 16, 4);
-        else if (tile == 1) APPROXIFER_PACKED(false, 16, 32, 4);
-        else APPROXIFER_PACKED(false, 32, 64, 2);
+        if (tile == 0) return APPROXIFER_PACKED(true, 16, 16, 4);
+        if (tile == 1) return APPROXIFER_PACKED(true, 16, 32, 4);
+        return APPROXIFER_PACKED(true, 32, 64, 2);
     }
+    if (tile == 0) return APPROXIFER_PACKED(false, 16, 16, 4);
+    if (tile == 1) return APPROXIFER_PACKED(false, 16, 32, 4);
+    return APPROXIFER_PACKED(false, 32, 64, 2);
 #undef APPROXIFER_PACKED
-    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
 }
 
 }  // namespace
@@ -680,16 +678,15 @@ int launch_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int
         if (G * stiles > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
         const dim3 sgrid(static_cast<unsigned>(G * stiles)), sblock(kWave);
 #define APPROXIFER_STREAM(KQ, UNAL)                                                                                    \
-    hipLaunchKernelGGL((decode_stream_kernel<KQ, UNAL>), sgrid, sblock, lds, stream, d_preds, d_mask, d_out, d_status, K, \
-                       N, S, C, sCv, stiles, sign_mode, nodes)
+    launch_status(launch_kernel(decode_stream_kernel<KQ, UNAL>, sgrid, sblock, lds, stream, d_preds, d_mask, d_out,       \
+                                d_status, K, N, S, C, sCv, stiles, sign_mode, nodes))
         switch (KP / 4) {
-            case 1: if (vec4) APPROXIFER_STREAM(1, false); else APPROXIFER_STREAM(1, true); break;
-            case 2: if (vec4) APPROXIFER_STREAM(2, false); else APPROXIFER_STREAM(2, true); break;
-            case 3: if (vec4) APPROXIFER_STREAM(3, false); else APPROXIFER_STREAM(3, true); break;
-            default: if (vec4) APPROXIFER_STREAM(4, false); else APPROXIFER_STREAM(4, true); break;
+            case 1: return vec4 ? APPROXIFER_STREAM(1, false) : APPROXIFER_STREAM(1, true);
+            case 2: return vec4 ? APPROXIFER_STREAM(2, false) : APPROXIFER_STREAM(2, true);
+            case 3: return vec4 ? APPROXIFER_STREAM(3, false) : APPROXIFER_STREAM(3, true);
+            default: return vec4 ? APPROXIFER_STREAM(4, false) : APPROXIFER_STREAM(4, true);
         }
 #undef APPROXIFER_STREAM
-        return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
     }
     const dim3 grid(static_cast<unsigned>(blocks)), block(waves * kWave);
     if (lds > 64 * 1024) {   // only K = 64 with more than 127 survivors; gfx950 has 160 KB of LDS per CU
@@ -698,13 +695,8 @@ int launch_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
             return APPROXIFER_ERR_LAUNCH;
     }
-    if (vec4)
-        hipLaunchKernelGGL(decode_kernel<4>, grid, block, lds, stream, d_preds, d_mask, d_out, d_status, K, N, S, C,
-                           Cv, ctiles, sign_mode, nodes);
-    else
-        hipLaunchKernelGGL(decode_kernel<1>, grid, block, lds, stream, d_preds, d_mask, d_out, d_status, K, N, S, C,
-                           Cv, ctiles, sign_mode, nodes);
-    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+    return launch_status(launch_kernel(vec4 ? decode_kernel<4> : decode_kernel<1>, grid, block, lds, stream, d_preds, d_mask,
+                                       d_out, d_status, K, N, S, C, Cv, ctiles, sign_mode, nodes));
 }
 
 int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_top1, float *d_score,
@@ -727,16 +719,15 @@ int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_t
         slds += 16 + sizeof(double) * 2 * static_cast<size_t>(KP) * nwaves;
         const dim3 sgrid(static_cast<unsigned>(G)), sblock(nwaves * kWave);
 #define APPROXIFER_TOP1_STREAM(KQV, UNAL)                                                                              \
-    hipLaunchKernelGGL((decode_top1_stream_kernel<KQV, UNAL>), sgrid, sblock, slds, stream, d_preds, d_mask, d_top1,      \
-                       d_score, d_status, K, N, S, C, sCv, stiles, sign_mode, nodes)
+    launch_status(launch_kernel(decode_top1_stream_kernel<KQV, UNAL>, sgrid, sblock, slds, stream, d_preds, d_mask,       \
+                                d_top1, d_score, d_status, K, N, S, C, sCv, stiles, sign_mode, nodes))
         switch (KQ) {
-            case 1: if (vec4) APPROXIFER_TOP1_STREAM(1, false); else APPROXIFER_TOP1_STREAM(1, true); break;
-            case 2: if (vec4) APPROXIFER_TOP1_STREAM(2, false); else APPROXIFER_TOP1_STREAM(2, true); break;
-            case 3: if (vec4) APPROXIFER_TOP1_STREAM(3, false); else APPROXIFER_TOP1_STREAM(3, true); break;
-            default: if (vec4) APPROXIFER_TOP1_STREAM(4, false); else APPROXIFER_TOP1_STREAM(4, true); break;
+            case 1: return vec4 ? APPROXIFER_TOP1_STREAM(1, false) : APPROXIFER_TOP1_STREAM(1, true);
+            case 2: return vec4 ? APPROXIFER_TOP1_STREAM(2, false) : APPROXIFER_TOP1_STREAM(2, true);
+            case 3: return vec4 ? APPROXIFER_TOP1_STREAM(3, false) : APPROXIFER_TOP1_STREAM(3, true);
+            default: return vec4 ? APPROXIFER_TOP1_STREAM(4, false) : APPROXIFER_TOP1_STREAM(4, true);
         }
 #undef APPROXIFER_TOP1_STREAM
-        return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
     }
     int slices = static_cast<int>((Cv + kWave - 1) / kWave);     // column slices worth a wave of their own
     const int most = G >= 512 ? 4 : 16;                          // few groups: all sixteen waves of a workgroup
@@ -763,22 +754,16 @@ int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_t
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
             return APPROXIFER_ERR_LAUNCH;
     }
-    if (vec4)
-        hipLaunchKernelGGL(decode_top1_kernel<4>, grid, block, lds, stream, d_preds, d_mask, d_top1, d_score, d_status,
-                           K, N, S, C, Cv, sign_mode, qsplit, nodes);
-    else
-        hipLaunchKernelGGL(decode_top1_kernel<1>, grid, block, lds, stream, d_preds, d_mask, d_top1, d_score, d_status,
-                           K, N, S, C, Cv, sign_mode, qsplit, nodes);
-    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+    return launch_status(launch_kernel(vec4 ? decode_top1_kernel<4> : decode_top1_kernel<1>, grid, block, lds, stream,
+                                       d_preds, d_mask, d_top1, d_score, d_status, K, N, S, C, Cv, sign_mode, qsplit, nodes));
 }
 
 int launch_wait_mask(const float *d_arrival, uint8_t *d_mask, int32_t *d_count, int64_t G, int N, int wait_for,
                      hipStream_t stream) {
     const int64_t blocks = (G + kWaitGroups - 1) / kWaitGroups;
     if (blocks > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
-    hipLaunchKernelGGL(wait_mask_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kWaitGroups * kWave), 0, stream,
-                       d_arrival, d_mask, d_count, G, N, wait_for);
-    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+    return launch_status(launch_kernel(wait_mask_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kWaitGroups * kWave), 0,
+                                       stream, d_arrival, d_mask, d_count, G, N, wait_for));
 }
 
 }  // namespace approxifer

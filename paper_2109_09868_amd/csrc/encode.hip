@@ -32,27 +32,13 @@ namespace {
 // K <= 16, one-wave workgroups: enough waves to keep about 48 KB of query loads in flight per CU (a wave
 // has K loads of 1 KB each), never fewer than six and never more than 24: measured optima are 20+ at K = 1,
 // 12..16 at K = 2, 8..12 at K = 4..6, 6 at K = 8..16 (7 and up lose 1..4 % there: more row streams open).
-#ifndef APPROXIFER_ENCODE_WAVES_PER_CU_MIN
-#define APPROXIFER_ENCODE_WAVES_PER_CU_MIN 6
-#endif
-#ifndef APPROXIFER_ENCODE_LOAD_KB_PER_CU
-#define APPROXIFER_ENCODE_LOAD_KB_PER_CU 48
-#endif
-#ifndef APPROXIFER_ENCODE_BLOCKS_PER_CU_LARGE_K
-#define APPROXIFER_ENCODE_BLOCKS_PER_CU_LARGE_K 2    // K > 16: four-wave workgroups
-#endif
-#ifndef APPROXIFER_ENCODE_MFMA_MIN_K
-#define APPROXIFER_ENCODE_MFMA_MIN_K 17            // from this K on the matrix-core variant serves every shape
-#endif
-#ifndef APPROXIFER_ENCODE_MFMA_WIDE_MIN_K
-#define APPROXIFER_ENCODE_MFMA_WIDE_MIN_K 8        // .. and from this K on the shapes with N >= 2K + 4
-#endif
-#ifndef APPROXIFER_ENCODE_MFMA_BLOCKS_PER_CU
-#define APPROXIFER_ENCODE_MFMA_BLOCKS_PER_CU 4       // matrix-core variant (four waves of 64 columns)
-#endif
-#ifndef APPROXIFER_ENCODE_SCALAR_ROWS_MAX_D
-#define APPROXIFER_ENCODE_SCALAR_ROWS_MAX_D 128      // ragged rows (D % 4 != 0) this short: 64-bit or 4-byte accesses only
-#endif
+constexpr int kWavesPerCuMin = 6;
+constexpr int kLoadKbPerCu = 48;
+constexpr int kBlocksPerCuLargeK = 2;   // K > 16: four-wave workgroups
+constexpr int kMfmaMinK = 17;   // from this K on the matrix-core variant serves every shape
+constexpr int kMfmaWideMinK = 8;   // .. and from this K on the shapes with N >= 2K + 4
+constexpr int kMfmaBlocksPerCu = 4;   // matrix-core variant (four waves of 64 columns)
+constexpr int kScalarRowsMaxD = 128;   // ragged rows (D % 4 != 0) this short: 64-bit or 4-byte accesses only
 constexpr int kLdsPerCu = 160 * 1024;                // gfx950
 
 // Register type of VEC floats, and the type a lane loads and stores it through.  Rows that are only
@@ -304,15 +290,14 @@ int run_encode_mfma_shape(const float *d_queries, float *d_coded, int64_t tiles,
                           int64_t Dv, const Nodes &nodes, hipStream_t stream) {
     if (tiles > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
     const size_t lds_used = static_cast<size_t>((N + 15) / 16) * KS * 64 * sizeof(float);
-    size_t lds = (static_cast<size_t>(kLdsPerCu / APPROXIFER_ENCODE_MFMA_BLOCKS_PER_CU) / 512) * 512;
+    size_t lds = (static_cast<size_t>(kLdsPerCu / kMfmaBlocksPerCu) / 512) * 512;
     if (lds < lds_used) lds = lds_used;
     if (lds > 64 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(encode_mfma_kernel<KS, UNAL, FLAT>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
         return APPROXIFER_ERR_LAUNCH;
-    hipLaunchKernelGGL((encode_mfma_kernel<KS, UNAL, FLAT>), dim3(static_cast<unsigned>(tiles)), dim3(kMfmaThreads), lds,
-                       stream, d_queries, d_coded, K, N, D, Dv, chunks, nodes);
-    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+    return launch_status(launch_kernel(encode_mfma_kernel<KS, UNAL, FLAT>, dim3(static_cast<unsigned>(tiles)),
+                                       dim3(kMfmaThreads), lds, stream, d_queries, d_coded, K, N, D, Dv, chunks, nodes));
 }
 
 template <int KS, bool UNAL>
@@ -335,10 +320,10 @@ int run_encode_shape(const float *d_queries, float *d_coded, int64_t tiles, int6
                      int64_t Dv, int64_t col0, const Nodes &nodes, hipStream_t stream) {
     constexpr int KP = (K + 3) & ~3;
     constexpr int THREADS = K <= 16 ? 64 : 256;
-    int per_cu = APPROXIFER_ENCODE_BLOCKS_PER_CU_LARGE_K;
+    int per_cu = kBlocksPerCuLargeK;
     if (K <= 16) {
-        per_cu = (APPROXIFER_ENCODE_LOAD_KB_PER_CU + K - 1) / K;     // K loads of 1 KB per wave
-        if (per_cu < APPROXIFER_ENCODE_WAVES_PER_CU_MIN) per_cu = APPROXIFER_ENCODE_WAVES_PER_CU_MIN;
+        per_cu = (kLoadKbPerCu + K - 1) / K;     // K loads of 1 KB per wave
+        if (per_cu < kWavesPerCuMin) per_cu = kWavesPerCuMin;
         if (per_cu > 24) per_cu = 24;
         if (VEC == 1) per_cu = 7;       // 4-byte accesses (the last D % 4 columns, or D < 4): a sliver of the work
     }
@@ -351,9 +336,8 @@ int run_encode_shape(const float *d_queries, float *d_coded, int64_t tiles, int6
         hipFuncSetAttribute(reinterpret_cast<const void *>(encode_kernel<K, VEC, THREADS, FLAT, UNAL>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
         return APPROXIFER_ERR_LAUNCH;
-    hipLaunchKernelGGL((encode_kernel<K, VEC, THREADS, FLAT, UNAL>), dim3(static_cast<unsigned>(tiles)), dim3(THREADS),
-                       lds, stream, d_queries, d_coded, N, D, Dv, chunks, col0, nodes);
-    return hipGetLastError() == hipSuccess ? APPROXIFER_OK : APPROXIFER_ERR_LAUNCH;
+    return launch_status(launch_kernel(encode_kernel<K, VEC, THREADS, FLAT, UNAL>, dim3(static_cast<unsigned>(tiles)),
+                                       dim3(THREADS), lds, stream, d_queries, d_coded, N, D, Dv, chunks, col0, nodes));
 }
 
 // Vector columns [0, Dv) of width VEC floats, starting at float column col0.
@@ -377,10 +361,10 @@ int run_encode(const float *d_queries, float *d_coded, int64_t G, int N, int64_t
 template <int K, bool UNAL>
 int run_encode_wide(const float *d_queries, float *d_coded, int64_t G, int N, int64_t D, const Nodes &nodes,
                     hipStream_t stream) {
-    if constexpr (K >= APPROXIFER_ENCODE_MFMA_MIN_K) {
+    if constexpr (K >= kMfmaMinK) {
         return run_encode_mfma<(K + 3) / 4, UNAL>(d_queries, d_coded, G, K, N, D, nodes, stream);
     } else {
-        if constexpr (K >= APPROXIFER_ENCODE_MFMA_WIDE_MIN_K) {
+        if constexpr (K >= kMfmaWideMinK) {
             // Many more coded than plain queries (the Byzantine worker counts, N = 2 (K + A) + S): a one-wave
             // tile would keep K + N >= 3K + 4 row streams open, and the matrix-core variant, whose waves work on
             // 256-byte row segments, measures 4..14 % faster (K=8, N=24: 5.7 -> 6.2 TB/s; K=12, N=36: 5.5 -> 6.0).
@@ -400,7 +384,7 @@ int run_encode_k(const float *d_queries, float *d_coded, int64_t G, int N, int64
     // rows only 4-byte aligned: 128-bit accesses on the first 4 * (D / 4) columns, 4-byte accesses on the rest;
     // short ragged rows: aligned 64-bit accesses throughout where the rows allow them, else 4-byte accesses
     const int64_t tail = D % 4;
-    if (tail != 0 && D <= APPROXIFER_ENCODE_SCALAR_ROWS_MAX_D) {
+    if (tail != 0 && D <= kScalarRowsMaxD) {
         if (D % 2 == 0 && reinterpret_cast<uintptr_t>(d_queries) % 8 == 0 && reinterpret_cast<uintptr_t>(d_coded) % 8 == 0)
             return run_encode<K, 2, false>(d_queries, d_coded, G, N, D, D / 2, 0, nodes, stream);
         return run_encode<K, 1, false>(d_queries, d_coded, G, N, D, D, 0, nodes, stream);

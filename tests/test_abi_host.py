@@ -106,15 +106,35 @@ def test_host_validation_codes(lib):
 
     byz = lib.approxifer_decode_byzantine
     a8, b24 = orc.chebyshev_nodes(8, 24)
-    assert byz(fake, fake, fake, fake, None, 1, 8, 24, 4, 0, 3, _dp(a8), _dp(b24), 0, None) == -2   # A < 1
-    assert byz(fake, fake, fake, fake, None, 1, 8, 24, 5, 2, 3, _dp(a8), _dp(b24), 0, None) == -5   # 19 < 20
+    assert byz(fake, fake, fake, fake, None, 1, 8, 24, 4, 0, 3, _dp(a8), _dp(b24), 0, None, 0, None) == -2   # A < 1
+    assert byz(fake, fake, fake, fake, None, 1, 8, 24, 5, 2, 3, _dp(a8), _dp(b24), 0, None, 0, None) == -5   # 19 < 20
     a8b, b18 = orc.chebyshev_nodes(8, 18)
-    assert byz(fake, fake, fake, fake, None, 1, 8, 18, -1, 2, 3, _dp(a8b), _dp(b18), 0, None) == -5   # even all 18 < 20
-    assert byz(fake, fake, fake, fake, None, 1, 8, 24, -2, 2, 3, _dp(a8), _dp(b24), 0, None) == -2
-    assert byz(fake, fake, fake, None, None, 1, 8, 24, 4, 2, 3, _dp(a8), _dp(b24), 0, None) == -1
+    assert byz(fake, fake, fake, fake, None, 1, 8, 18, -1, 2, 3, _dp(a8b), _dp(b18), 0, None, 0, None) == -5   # even all 18 < 20
+    assert byz(fake, fake, fake, fake, None, 1, 8, 24, -2, 2, 3, _dp(a8), _dp(b24), 0, None, 0, None) == -2
+    assert byz(fake, fake, fake, None, None, 1, 8, 24, 4, 2, 3, _dp(a8), _dp(b24), 0, None, 0, None) == -1
     a2, b100 = orc.chebyshev_nodes(2, 100)
-    assert byz(fake, fake, fake, fake, None, 1, 2, 100, 0, 1, 3, _dp(a2), _dp(b100), 0, None) == -3  # N-S > 64
-    assert byz(None, None, None, None, None, 0, 8, 24, 4, 2, 3, _dp(a8), _dp(b24), 0, None) == 0
+    assert byz(fake, fake, fake, fake, None, 1, 2, 100, 0, 1, 3, _dp(a2), _dp(b100), 0, None, 0, None) == -3  # N-S > 64
+    assert byz(None, None, None, None, None, 0, 8, 24, 4, 2, 3, _dp(a8), _dp(b24), 0, None, 0, None) == 0
+
+
+def test_workspace_bytes(lib):
+    wb = binding.approxifer_workspace_bytes
+    # many groups, ten classes: one workgroup per group fills the GPU, nothing to pool
+    assert wb(2048, 8, 24, 4, 2, 10) == 0
+    # few groups, a thousand classes: N + 1 words per group, rounded up to 256 bytes
+    need = wb(8, 12, 28, 0, 2, 1000)
+    assert need == (8 * 29 * 4 + 255) // 256 * 256
+    assert wb(3, 8, 24, -1, 2, 1000) == (3 * 25 * 4 + 255) // 256 * 256
+    # beyond the projected kernel's domain (60 available workers) the LDS kernel splits from four passes on
+    assert wb(3, 8, 60, 0, 2, 300) > 0
+    # shapes the decoders refuse need nothing
+    for args in ((0, 8, 24, 4, 2, 1000), (8, 8, 24, 4, 2, 0), (8, 0, 24, 4, 2, 1000), (8, 8, 24, 4, 0, 1000),
+                 (8, 8, 24, 5, 2, 1000), (8, 65, 24, 4, 2, 1000), (8, 8, 129, 4, 2, 1000), (8, 2, 100, 0, 1, 1000),
+                 (8, 8, 24, -2, 2, 1000), (8, 8, 24, 24, 2, 1000)):
+        assert wb(*args) == 0, args
+    # never more than 4 (N + 1) bytes per group plus the rounding
+    for G, K, N, S, A, C in ((1, 2, 128, 64, 1, 100000), (5, 14, 64, 0, 2, 5000), (4095, 1, 6, 0, 1, 70000)):
+        assert wb(G, K, N, S, A, C) <= 4 * (N + 1) * G + 255
 
 
 def test_binding_raises_typed_error(lib):

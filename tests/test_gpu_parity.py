@@ -9,10 +9,10 @@ import pytest
 
 from oracle import approxifer_oracle as orc
 from paper_2109_09868_amd import synthetic as syn
+from parity_cases import (TOL, ILL_POSED_FUZZ_ALL, ILL_POSED_FUZZ_BYZANTINE, ILL_POSED_RAGGED, assert_rounding_ties,
+                          fuzz_all_cases, fuzz_byzantine_cases, group_err, ragged_decode_case, well_posed)
 
 pytestmark = pytest.mark.gpu
-
-TOL = 1e-5
 
 
 @pytest.fixture(scope="module")
@@ -22,30 +22,6 @@ def gpu():
     assert torch.cuda.is_available(), "these tests need the MI355X"
     binding.load()                      # raises if the HIP library was not built: no fallback
     return torch, binding, torch.device("cuda:0")
-
-
-def well_posed(alpha, beta, mask, mode, limit=1e8):
-    """Groups whose decoder weights have a Lebesgue constant max_j sum_i |w_ji| below `limit`.  With the
-    worker-index signs of the printed formula a missing worker can put a real pole of the interpolant on a query
-    node (the denominator then cancels to rounding noise): two float64 evaluations of such a group agree in
-    nothing, and the 1e-5 bar applies to the groups float64 can decide, Lebesgue constant x 1e-16 << 1e-5."""
-    ok = np.zeros(mask.shape[0], bool)
-    for g in range(mask.shape[0]):
-        F = np.nonzero(mask[g])[0]
-        if F.size == 0:
-            continue
-        with np.errstate(all="ignore"):
-            leb = np.abs(orc.decode_weights(alpha, beta, F, mode)).sum(axis=1).max()
-        ok[g] = np.isfinite(leb) and leb <= limit
-    return ok
-
-
-def group_err(got, ref):
-    got = np.asarray(got, dtype=np.float64).reshape(ref.shape[0], -1)
-    ref = np.asarray(ref, dtype=np.float64).reshape(ref.shape[0], -1)
-    scale = np.max(np.abs(ref), axis=1)
-    scale[scale == 0] = 1.0
-    return np.max(np.abs(got - ref), axis=1) / scale
 
 
 # --------------------------------------------------------------------------------------
@@ -189,6 +165,44 @@ def test_encode_text_k32_full_size_sampled(gpu):
     _full_size_encode_sampled(gpu, "text_k32", [0, 1023])
 
 
+def _full_size_encode_every_element(gpu, name, chunk):
+    """Full-size launch (the configuration the benchmark times), EVERY element of every group compared with the
+    oracle, `chunk` groups at a time (the oracle's float64 copy of a chunk is what bounds host memory)."""
+    import sys
+    torch, binding, dev = gpu
+    w = syn.WORKLOADS[name]
+    alpha, beta = orc.chebyshev_nodes(w.K, w.W)
+    dX = torch.empty((w.G, w.K, w.D), dtype=torch.float32, device=dev)
+    for g0 in range(0, w.G, chunk):
+        dX[g0:g0 + chunk] = torch.from_numpy(syn.queries(w, g0, min(g0 + chunk, w.G), threads=16)).to(dev)
+    coded = binding.approxifer_encode(dX, alpha, beta)          # one launch over all G groups
+    torch.cuda.synchronize()
+    del dX
+    worst = 0.0
+    for g0 in range(0, w.G, chunk):
+        g1 = min(g0 + chunk, w.G)
+        ref = orc.encode(syn.queries(w, g0, g1, threads=16), alpha, beta)
+        worst = max(worst, group_err(coded[g0:g1].cpu().numpy(), ref).max())
+        print("%s encode: groups %d..%d of %d compared, worst %.3g" % (name, g0, g1, w.G, worst), flush=True)
+        sys.stdout.flush()
+        assert worst <= TOL, (g0, worst)
+
+
+@pytest.mark.timeout(1200)
+def test_encode_imagenet_full_size_every_element(gpu):
+    _full_size_encode_every_element(gpu, "imagenet", 32)
+
+
+@pytest.mark.timeout(1200)
+def test_encode_text_full_size_every_element(gpu):
+    _full_size_encode_every_element(gpu, "text", 64)
+
+
+@pytest.mark.timeout(1200)
+def test_encode_text_k32_full_size_every_element(gpu):
+    _full_size_encode_every_element(gpu, "text_k32", 32)
+
+
 # --------------------------------------------------------------------------------------
 # decoder
 # --------------------------------------------------------------------------------------
@@ -257,15 +271,14 @@ def test_decode_streaming_kernel(gpu, K, N, S, C, G, mode):
     o, s = out.cpu().numpy(), st.cpu().numpy()
     assert np.array_equal(s, st_ref) and s[7] == 1 and s.sum() == 1
     assert np.all(o[7] == -3.0)
-    good = (s == 0) & well_posed(alpha, beta, mask, mode)
-    assert good.sum() >= 0.9 * G
+    good = s == 0                                          # every accepted group is compared: none of these seeds
+    assert good.sum() == G - 1                             # draws a mask whose weights float64 cannot decide
     assert group_err(o[good], ref[good]).max() <= TOL
     # per-group straggler counts: the same masks, read off group by group
     out2, st2 = binding.approxifer_decode(Yd, md, alpha, beta, binding.S_FROM_MASK, mode)
     ref2, _ = orc.decode(Y[:64], mask[:64], alpha, beta, None, mode)
-    ok2 = well_posed(alpha, beta, mask[:64], mode)
     assert np.all(st2.cpu().numpy() == 0)
-    assert group_err(out2.cpu().numpy()[:64][ok2], ref2[ok2]).max() <= TOL
+    assert group_err(out2.cpu().numpy()[:64], ref2).max() <= TOL
 
 
 @pytest.mark.parametrize("K,N,S,C,G,off_in,off_out", [
@@ -565,8 +578,8 @@ def test_byzantine_exactly_rational_predictions(gpu, K, A, S, N, C, G):
 @pytest.mark.parametrize("K,A,N,C,G", [(8, 2, 24, 1000, 5), (12, 2, 30, 257, 6), (4, 1, 12, 4003, 3), (2, 1, 8, 20001, 2),
                                        (8, 2, 60, 300, 3)])
 def test_byzantine_many_classes_few_groups(gpu, K, A, N, C, G, locator):
-    # with few groups and many classes several workgroups share a group and meet through atomics in the group's own
-    # output rows (all three kernels: the last shape has up to 60 available workers, Algorithm 2's LDS kernel):
+    # with few groups and many classes several workgroups share a group and meet through atomics in the caller's
+    # workspace (all three kernels: the last shape has up to 60 available workers, Algorithm 2's LDS kernel):
     # per-group straggler counts, a rejected mask among the groups (its rows and located workers must stay
     # untouched), twice in a row on the same buffers
     torch, binding, dev = gpu
@@ -599,6 +612,74 @@ def test_byzantine_many_classes_few_groups(gpu, K, A, N, C, G, locator):
         good = s == 0
         assert np.array_equal(a[good], adv_ref[good]) and np.array_equal(a[good], adv_true[good])
         assert group_err(o[good], ref[good]).max() <= TOL
+
+
+@pytest.mark.parametrize("entry", ["approxifer_decode_byzantine", "approxifer_decode_byzantine_homogeneous"])
+@pytest.mark.parametrize("K,A,N,C,G", [(8, 2, 24, 1000, 5), (3, 1, 10, 4003, 3), (8, 2, 60, 300, 3)])
+def test_byzantine_workspace_through_the_c_abi(gpu, entry, K, A, N, C, G):
+    # the raw C ABI with a workspace of the size approxifer_workspace_bytes() gives: the classes of a group are spread
+    # over several workgroups that meet there.  The workspace and every output sit between canaries; the workspace
+    # arrives full of garbage; output rows of a rejected group keep their contents.  Then the same call with
+    # NULL / 0, with a workspace one byte short, and with a misaligned one: one workgroup per group, and the same
+    # bits in every output.
+    import ctypes
+    torch, binding, dev = gpu
+    lib = binding.load()
+    rng = np.random.default_rng(K * 31 + C)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    X = rng.uniform(0, 1, (G, K, 40))
+    clean = (orc.encode(X, alpha, beta) @ (rng.standard_normal((40, C)) / 6)).astype(np.float32)
+    M = K + A
+    mask = np.zeros((G, N), np.uint8)
+    Y = clean.copy()
+    for g in range(G):
+        cnt = 2 * M - 1 if g == 1 else int(rng.integers(2 * M, N + 1))     # group 1: one worker too few
+        avail = np.sort(rng.permutation(N)[:cnt])
+        mask[g, avail] = 1
+        ok = avail[np.abs(beta[avail]) > 1e-9]
+        bad = np.sort(rng.permutation(ok)[:A])
+        Y[g, bad] += (10 * clean.std() * rng.standard_normal((A, C))).astype(np.float32)
+    locator = orc.LOCATOR_ALGORITHM_2 if entry == "approxifer_decode_byzantine" else orc.LOCATOR_ALGORITHM_1
+    ref, adv_ref, st_ref = orc.decode_byzantine(Y, mask, alpha, beta, None, A, 1, locator)
+    need = binding.approxifer_workspace_bytes(G, K, N, binding.S_FROM_MASK, A, C)
+    assert need >= 4 * (N + 1) * G                               # these shapes are shared between workgroups
+    dp = ctypes.POINTER(ctypes.c_double)
+    a64, b64 = np.ascontiguousarray(alpha), np.ascontiguousarray(beta)
+    Yd, md = torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev)
+    pad = 64
+
+    def framed(n_elems, dtype, fill):
+        buf = torch.full((n_elems + 2 * pad,), fill, dtype=dtype, device=dev)
+        return buf, buf[pad:pad + n_elems]
+
+    def call(ws_ptr, ws_bytes):
+        out_buf, out = framed(G * K * C, torch.float32, -3.0)
+        adv_buf, adv = framed(G * A, torch.int32, -7)
+        st_buf, st = framed(G, torch.int32, -9)
+        rc = getattr(lib, entry)(Yd.data_ptr(), md.data_ptr(), out.data_ptr(), adv.data_ptr(), st.data_ptr(), G, K, N,
+                                 binding.S_FROM_MASK, A, C, a64.ctypes.data_as(dp), b64.ctypes.data_as(dp), 1,
+                                 ws_ptr, ctypes.c_size_t(ws_bytes), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert rc == 0
+        for buf, fill in ((out_buf, -3.0), (adv_buf, -7), (st_buf, -9)):
+            assert torch.all(buf[:pad] == fill) and torch.all(buf[-pad:] == fill)
+        return out.view(G, K, C).cpu().numpy(), adv.view(G, A).cpu().numpy(), st.cpu().numpy()
+
+    ws_buf = torch.randint(-2 ** 31, 2 ** 31 - 1, (need // 4 + 2 * pad,), dtype=torch.int32, device=dev)
+    before = ws_buf.clone()
+    ws = ws_buf[pad:pad + need // 4]
+    o, a, s = call(ws.data_ptr(), need)
+    assert torch.equal(ws_buf[:pad], before[:pad]) and torch.equal(ws_buf[-pad:], before[-pad:])
+    assert np.array_equal(s, st_ref) and s[1] == 1 and s.sum() == 1
+    assert np.all(o[1] == -3.0) and np.all(a[1] == -7)
+    good = s == 0
+    assert np.array_equal(a[good], adv_ref[good])
+    assert group_err(o[good], ref[good]).max() <= TOL
+    o2, a2, s2 = call(ws.data_ptr(), need)                      # again, on the workspace the first call left behind
+    assert np.array_equal(o2, o) and np.array_equal(a2, a) and np.array_equal(s2, s)
+    for ptr, nbytes in ((None, 0), (ws.data_ptr(), 4 * (N + 1) * G - 1), (ws.data_ptr() + 1, need - 1), (None, need)):
+        o3, a3, s3 = call(ptr, nbytes)
+        assert np.array_equal(o3, o) and np.array_equal(a3, a) and np.array_equal(s3, s)
 
 
 @pytest.mark.parametrize("mode", [0, 1])
@@ -649,6 +730,7 @@ def test_byzantine_nonlinear_model_votes(gpu):
     assert np.array_equal(adv[clear], adv_ref[clear])
     same = np.all(adv == adv_ref, axis=1)
     assert same.mean() >= 0.97
+    assert_rounding_ties(Y, mask, beta, K, A, adv, adv_ref)             # the rest differ on float64 ties only
     assert group_err(out[same], ref[same]).max() <= TOL
 
 
@@ -685,6 +767,7 @@ def test_byzantine_fewer_real_adversaries_than_A(gpu, real):
         decisive[g] = top[A - 1] - top[A] >= 2
     same = np.all(adv == adv_ref, axis=1)
     assert np.all(same[decisive]) and same.mean() >= 0.9
+    assert_rounding_ties(Y, mask, beta, K, A, adv, adv_ref)             # rank-deficient fits: every class is a tie
     assert group_err(out[same], ref[same]).max() <= TOL
     for g in np.nonzero(~same)[0]:                          # decode parity given the kernel's own survivor set
         m2 = mask[g:g + 1].copy()
@@ -854,6 +937,7 @@ def test_homogeneous_locator_on_data_that_is_not_rational(gpu):
     assert np.array_equal(adv[clear], adv_ref[clear])
     same = np.all(adv == adv_ref, axis=1)
     assert same.mean() >= 0.95
+    assert_rounding_ties(Y, mask, beta, K, A, adv, adv_ref, orc.LOCATOR_ALGORITHM_1)
     assert group_err(out[same], ref[same]).max() <= TOL
 
 
@@ -990,15 +1074,7 @@ def test_paper_operating_point_workloads_full_size(gpu):
 @pytest.mark.parametrize("mode", [0, 1])
 def test_decode_ragged_masks(gpu, K, N, C, G, mode):
     torch, binding, dev = gpu
-    rng = np.random.default_rng(K * 17 + N + mode)
-    alpha, beta = orc.chebyshev_nodes(K, N)
-    Y = rng.standard_normal((G, N, C)).astype(np.float32)
-    mask = np.zeros((G, N), np.uint8)
-    counts = rng.integers(1, N + 1, G)
-    counts[0], counts[1], counts[2] = N, 1, 0                 # everyone, a single survivor, nobody
-    for g in range(G):
-        mask[g, rng.permutation(N)[: counts[g]]] = 1
-    Y[mask == 0] = np.nan
+    alpha, beta, Y, mask = ragged_decode_case(K, N, C, G, mode)
     out = torch.full((G, K, C), -9.0, dtype=torch.float32, device=dev)
     out, st = binding.approxifer_decode(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev), alpha, beta,
                                         binding.S_FROM_MASK, mode, out=out)
@@ -1007,8 +1083,11 @@ def test_decode_ragged_masks(gpu, K, N, C, G, mode):
     out, st = out.cpu().numpy(), st.cpu().numpy()
     assert np.array_equal(st, st_ref) and st[2] == 1 and st.sum() == 1
     assert np.all(out[2] == -9.0)
+    # every decoded group is compared, bar the ones the oracle-side conditioning test sets aside for this seed
+    # (ILL_POSED_RAGGED, checked against the oracle by the CPU suite): none, or the one group whose mask puts a
+    # pole of the printed sign rule on a query node
     finite = np.all(np.isfinite(ref.reshape(G, -1)), axis=1) & (st == 0) & well_posed(alpha, beta, mask, mode)
-    assert finite.sum() >= G - 4
+    assert G - 1 - finite.sum() == ILL_POSED_RAGGED.get((K, N, C, G, mode), 0)
     assert group_err(out[finite], ref[finite]).max() <= TOL
     assert np.array_equal(out[1], np.broadcast_to(Y[1, np.nonzero(mask[1])[0][0]], (K, C)))
     top1, score, st1 = binding.approxifer_decode_top1(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev),
@@ -1118,14 +1197,19 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed(gpu):
     outh = torch.zeros((G, Kb, Cb), dtype=torch.float32, device=dev)
     advh = torch.zeros((G, Ab), dtype=torch.int32, device=dev)
 
+    need = binding.approxifer_workspace_bytes(G, Kb, Nb, Sb, Ab, Cb)
+    assert need > 0
+    wsb = torch.empty((need,), dtype=torch.uint8, device=dev)    # the two Byzantine calls run one after the other
+
     def calls():
         binding.approxifer_encode(q, alpha, beta, coded=coded)
         binding.approxifer_wait_mask(arrival, N - S, mask=mask, count=count)
         binding.approxifer_decode(preds, mask, alpha, beta, S, 1, out=out, status=st)
         binding.approxifer_decode_top1(preds, mask, alpha, beta, S, 1, top1=top1, status=st, want_score=False)
-        binding.approxifer_decode_byzantine(predsb, maskb, alphab, betab, Sb, Ab, 1, out=outb, adv=advb, status=stb)
+        binding.approxifer_decode_byzantine(predsb, maskb, alphab, betab, Sb, Ab, 1, out=outb, adv=advb, status=stb,
+                                            workspace=wsb)
         binding.approxifer_decode_byzantine_homogeneous(predsb, maskb, alphab, betab, Sb, Ab, 1, out=outh, adv=advh,
-                                                        status=stb)
+                                                        status=stb, workspace=wsb)
 
     def fresh_inputs(seed):
         r = np.random.default_rng(seed)
@@ -1193,30 +1277,21 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed(gpu):
 def test_random_shapes_all_entry_points(gpu):
     # APPROXIFER_FUZZ_SEED / APPROXIFER_FUZZ_TRIALS widen the sweep by hand; the defaults are what the suite runs
     import os
+    from parity_cases import FUZZ_ALL_SEED, FUZZ_ALL_TRIALS
     torch, binding, dev = gpu
-    rng = np.random.default_rng(int(os.environ.get("APPROXIFER_FUZZ_SEED", "20210909")))
-    for trial in range(int(os.environ.get("APPROXIFER_FUZZ_TRIALS", "60"))):
-        K = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 11, 12, 13, 16, 17, 19, 24, 31, 32, 40, 64]))
-        S = int(rng.integers(0, 6))
-        N = int(min(128, max(2, K + S + int(rng.integers(0, 4)))))
-        S = min(S, N - 1)
-        D = int(rng.choice([1, 2, 3, 4, 7, 8, 60, 64, 252, 256, 260, 1000, 1023, 1024, 1028, 3072]))
-        C = int(rng.choice([1, 2, 3, 4, 5, 8, 10, 100, 252, 256, 260, 1000]))
-        G = int(rng.integers(1, 6))
-        mode = int(rng.integers(0, 2))
-        print("trial", trial, dict(K=K, N=N, S=S, D=D, C=C, G=G, mode=mode), flush=True)
-        alpha, beta = orc.chebyshev_nodes(K, N)
-        X = rng.standard_normal((G, K, D)).astype(np.float32)
+    seed = int(os.environ.get("APPROXIFER_FUZZ_SEED", FUZZ_ALL_SEED))
+    trials = int(os.environ.get("APPROXIFER_FUZZ_TRIALS", FUZZ_ALL_TRIALS))
+    set_aside = 0
+    for t in fuzz_all_cases(seed, trials):
+        K, N, S, C, G, mode, alpha, beta = t["K"], t["N"], t["S"], t["C"], t["G"], t["mode"], t["alpha"], t["beta"]
+        print("trial", t["trial"], dict(K=K, N=N, S=S, D=t["D"], C=C, G=G, mode=mode), flush=True)
+        X, Y, mask = t["X"], t["Y"], t["mask"]
         coded = binding.approxifer_encode(torch.from_numpy(X).to(dev), alpha, beta).cpu().numpy()
         assert group_err(coded, orc.encode(X, alpha, beta)).max() <= TOL
-        Y = rng.standard_normal((G, N, C)).astype(np.float32)
-        mask = np.zeros((G, N), np.uint8)
-        for g in range(G):
-            mask[g, rng.permutation(N)[: N - S]] = 1
-        Y[mask == 0] = np.nan
         with np.errstate(all="ignore"):
             ref, st_ref = orc.decode(Y, mask, alpha, beta, S, mode)
         finite = np.all(np.isfinite(ref.reshape(G, -1)), axis=1) & well_posed(alpha, beta, mask, mode)
+        set_aside += int(G - finite.sum())
         out, st = binding.approxifer_decode(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev), alpha, beta, S, mode)
         assert np.array_equal(st.cpu().numpy(), st_ref)
         if finite.any():
@@ -1228,38 +1303,20 @@ def test_random_shapes_all_entry_points(gpu):
             clear = (srt[..., -1] - srt[..., -2]) > 1e-9 * np.abs(ref[finite]).max(axis=-1)
             assert np.array_equal(top1.cpu().numpy()[finite][clear], ref[finite].argmax(-1)[clear])
         # Byzantine decoder on a shape that satisfies its counting rule
-        A = int(rng.integers(1, 3))
-        Kb = int(rng.integers(1, 9))
-        Sb = int(rng.integers(0, 4))
-        Nb = 2 * (Kb + A) + Sb + int(rng.integers(0, 3))
-        if Nb % 2 == 1:
-            Nb += 1                                                     # keep the zero node out (Q(0) = 1)
-        alpha, beta = orc.chebyshev_nodes(Kb, Nb)
-        Xb = rng.uniform(0, 1, (G, Kb, 32))
-        Mf = rng.standard_normal((32, C))
-        clean = (orc.encode(Xb, alpha, beta) @ Mf).astype(np.float32)
-        maskb = np.zeros((G, Nb), np.uint8)
-        Yb = clean.copy()
-        for g in range(G):
-            avail = np.sort(rng.permutation(Nb)[: Nb - Sb])
-            maskb[g, avail] = 1
-            bad = rng.permutation(avail)[:A]
-            Yb[g, bad] += (10 * (clean.std() + 1e-3) * rng.standard_normal((A, C))).astype(np.float32)
+        A, Kb, Sb, alphab, betab, Yb, maskb = t["A"], t["Kb"], t["Sb"], t["alphab"], t["betab"], t["Yb"], t["maskb"]
         outb, advb, stb = binding.approxifer_decode_byzantine(torch.from_numpy(Yb).to(dev), torch.from_numpy(maskb).to(dev),
-                                                              alpha, beta, Sb, A, 1)
-        refb, adv_ref, st_refb = orc.decode_byzantine(Yb, maskb, alpha, beta, Sb, A, 1)
+                                                              alphab, betab, Sb, A, 1)
+        refb, adv_ref, st_refb = orc.decode_byzantine(Yb, maskb, alphab, betab, Sb, A, 1)
         assert np.array_equal(stb.cpu().numpy(), st_refb)
-        same = np.all(advb.cpu().numpy() == adv_ref, axis=1)
-        # with a single class, or tiny separations, a pick may sit on a rounding tie: demand agreement wherever
-        # the oracle's own vote is decisive, and never less than 90 % of groups
-        decisive = np.zeros(G, bool)
-        for g in range(G):
-            _, _, counts = orc.locate(Yb[g], np.nonzero(maskb[g])[0], beta, Kb, A)
-            top = np.sort(counts)[::-1]
-            decisive[g] = top[A - 1] - top[A] >= 2
-        assert np.all(same[decisive])
+        advb = advb.cpu().numpy()
+        same = np.all(advb == adv_ref, axis=1)
+        # a located set may differ from the oracle's only where a class's pick is a float64 rounding tie (a single
+        # class, or separations at the noise floor), and then only by as many votes as there are such classes
+        assert_rounding_ties(Yb, maskb, betab, Kb, A, advb, adv_ref)
         if same.any():
             assert group_err(outb.cpu().numpy()[same], refb[same]).max() <= TOL
+    if (seed, trials) == (FUZZ_ALL_SEED, FUZZ_ALL_TRIALS):
+        assert set_aside == ILL_POSED_FUZZ_ALL              # no decoded group left out beyond the oracle-side count
 
 
 def test_random_byzantine_shapes(gpu):
@@ -1268,39 +1325,16 @@ def test_random_byzantine_shapes(gpu):
     # hundred classes; exactly rational data (linear model), so the planted adversaries must come back wherever
     # float32 data still separate them
     import os
+    from parity_cases import FUZZ_BYZ_SEED, FUZZ_BYZ_TRIALS
     torch, binding, dev = gpu
-    rng = np.random.default_rng(int(os.environ.get("APPROXIFER_FUZZ_SEED", "909868")))
-    for trial in range(int(os.environ.get("APPROXIFER_FUZZ_TRIALS", "40"))):
-        K = int(rng.integers(1, 15))
-        A = int(rng.integers(1, 4))
-        if K + A > 16:
-            K = 16 - A
+    seed = int(os.environ.get("APPROXIFER_FUZZ_SEED", FUZZ_BYZ_SEED))
+    trials = int(os.environ.get("APPROXIFER_FUZZ_TRIALS", FUZZ_BYZ_TRIALS))
+    set_aside = 0
+    for t in fuzz_byzantine_cases(seed, trials):
+        K, A, S, N, C, G, ragged, mode = t["K"], t["A"], t["S"], t["N"], t["C"], t["G"], t["ragged"], t["mode"]
+        alpha, beta, Y, mask, adv_true = t["alpha"], t["beta"], t["Y"], t["mask"], t["adv_true"]
         M = K + A
-        S = int(rng.integers(0, 5))
-        extra = int(rng.choice([0, 0, 0, 1, 2, 5, 11, 30]))
-        n = min(2 * M + extra, 64)
-        N = n + S
-        if N % 2 == 1:                                       # keep the zero node out (Q(0) = 1)
-            N += 1
-            S += 1
-        C = int(rng.choice([1, 2, 3, 4, 7, 10, 16, 17, 40, 65, 130, 260, 515]))
-        G = int(rng.integers(1, 7))
-        ragged = bool(rng.integers(0, 2)) and N > 2 * M
-        mode = int(rng.integers(0, 2))
-        print("trial", trial, dict(K=K, A=A, S=S, N=N, C=C, G=G, ragged=ragged, mode=mode), flush=True)
-        alpha, beta = orc.chebyshev_nodes(K, N)
-        X = rng.uniform(0, 1, (G, K, 48))
-        Mf = rng.standard_normal((48, C)) / 7
-        clean = (orc.encode(X, alpha, beta) @ Mf).astype(np.float32)
-        mask = np.zeros((G, N), np.uint8)
-        Y = clean.copy()
-        adv_true = np.zeros((G, A), np.int32)
-        for g in range(G):
-            cnt = int(rng.integers(2 * M, min(N, 64) + 1)) if ragged else N - S
-            avail = np.sort(rng.permutation(N)[:cnt])
-            mask[g, avail] = 1
-            adv_true[g] = np.sort(rng.permutation(avail)[:A])
-            Y[g, adv_true[g]] += (10 * (clean.std() + 1e-3) * rng.standard_normal((A, C))).astype(np.float32)
+        print("trial", t["trial"], dict(K=K, A=A, S=S, N=N, C=C, G=G, ragged=ragged, mode=mode), flush=True)
         S_arg = binding.S_FROM_MASK if ragged else S
         for locator, entry in ((orc.LOCATOR_ALGORITHM_2, binding.approxifer_decode_byzantine),
                                (orc.LOCATOR_ALGORITHM_1, binding.approxifer_decode_byzantine_homogeneous)):
@@ -1309,18 +1343,16 @@ def test_random_byzantine_shapes(gpu):
             out, adv, st = out.cpu().numpy(), adv.cpu().numpy(), st.cpu().numpy()
             assert np.array_equal(st, st_ref) and np.all(st == 0)
             same = np.all(adv == adv_ref, axis=1)
-            decisive = np.zeros(G, bool)
-            for g in range(G):
-                _, _, counts = orc.locate(Y[g], np.nonzero(mask[g])[0], beta, K, A, locator)
-                top = np.sort(counts)[::-1]
-                decisive[g] = top[A - 1] - top[A] >= 2
-            assert np.all(same[decisive]), (locator, adv, adv_ref)
+            assert_rounding_ties(Y, mask, beta, K, A, adv, adv_ref, locator)
             if M <= 12 and C >= 7:
-                assert np.array_equal(adv[decisive], adv_true[decisive]), locator
+                assert np.array_equal(adv[same], adv_true[same]), locator
             for g in range(G):                               # decode parity over the kernel's own survivor set
                 m2 = mask[g:g + 1].copy()
                 m2[0, adv[g]] = 0
                 if not well_posed(alpha, beta, m2, mode)[0]:
+                    set_aside += 1
                     continue
                 ref_g, _ = orc.decode(Y[g:g + 1], m2, alpha, beta, None, mode)
                 assert group_err(out[g:g + 1], ref_g).max() <= TOL
+    if (seed, trials) == (FUZZ_BYZ_SEED, FUZZ_BYZ_TRIALS):
+        assert set_aside == ILL_POSED_FUZZ_BYZANTINE
