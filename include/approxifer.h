@@ -54,6 +54,7 @@ extern "C" {
 #define APPROXIFER_ERR_TOO_FEW_WORKERS (-5)/* N - S < 2 (K + A): Algorithm 2's system would be under-determined */
 #define APPROXIFER_ERR_BAD_SIGN_MODE (-6)  /* sign_mode is neither 0 nor 1 */
 #define APPROXIFER_ERR_LAUNCH (-7)         /* the HIP runtime refused the launch */
+#define APPROXIFER_ERR_WORKSPACE_LIMIT (-8)/* approxifer_decode_byzantine_static(): the built-in workspace is too small */
 
 /* Decoder sign conventions, see approxifer_decode(). */
 #define APPROXIFER_SIGN_WORKER_INDEX 0
@@ -169,6 +170,30 @@ int approxifer_decode_byzantine(const float *d_preds, const uint8_t *d_mask, flo
  * 4 (N + 1) bytes per group, rounded up to a multiple of 256.
  */
 size_t approxifer_workspace_bytes(int64_t G, int K, int N, int S, int A, int64_t C);
+
+/*
+ * approxifer_decode_byzantine() for callers that cannot allocate device memory, not even a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same call with
+ * the workspace arguments left out; the scratch memory is an array of APPROXIFER_STATIC_WORKSPACE_BYTES
+ * bytes built into the library's device code (every GPU the library runs on holds one copy until the
+ * process ends).  The call allocates and frees nothing and calls no allocating routine; inputs and outputs
+ * are still the caller's.
+ *   - A shape for which approxifer_workspace_bytes() exceeds APPROXIFER_STATIC_WORKSPACE_BYTES is refused
+ *     with APPROXIFER_ERR_WORKSPACE_LIMIT before anything is enqueued (4 (N + 1) G bytes are needed when
+ *     few groups bring hundreds of classes or more; shapes that need no workspace are never refused).
+ *   - The device of `stream` must be the current device.  The first call on a device looks up the address
+ *     of that device's copy of the array (no allocation, no synchronisation).
+ *   - All calls on one GPU share that GPU's array.  Each call clears the part it uses with a kernel of
+ *     its own, so what an earlier call left there does not matter; two calls whose work OVERLAPS on one
+ *     GPU (different streams, or graphs replayed concurrently) race on it and give undefined results.
+ *     Calls on one stream, one after the other, are safe.
+ * Results, other arguments, requirements and error codes are those of approxifer_decode_byzantine().
+ */
+#define APPROXIFER_STATIC_WORKSPACE_BYTES 65536
+int approxifer_decode_byzantine_static(const float *d_preds, const uint8_t *d_mask, float *d_out,
+                                       int32_t *d_adv, int32_t *d_status,
+                                       int64_t G, int K, int N, int S, int A, int64_t C,
+                                       const double *h_alpha, const double *h_beta, int sign_mode, void *stream);
 
 /*
  * Byzantine decoder with the locator of Section 2, Algorithm 1, in place of Algorithm 2: the

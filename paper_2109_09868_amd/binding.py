@@ -32,6 +32,7 @@ EXPORTS = (
     "approxifer_decode_byzantine",
     "approxifer_decode_byzantine_homogeneous",
     "approxifer_workspace_bytes",
+    "approxifer_decode_byzantine_static",
 )
 
 _lib = None
@@ -77,6 +78,10 @@ def load() -> ctypes.CDLL:
     lib.approxifer_workspace_bytes.restype = ctypes.c_size_t
     lib.approxifer_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                ctypes.c_int64]
+    lib.approxifer_decode_byzantine_static.restype = ctypes.c_int
+    lib.approxifer_decode_byzantine_static.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                                       ctypes.c_int, ctypes.c_int, ctypes.c_int64, c_dp, c_dp,
+                                                       ctypes.c_int, vp]
     lib.approxifer_decode_byzantine_homogeneous.restype = ctypes.c_int
     lib.approxifer_decode_byzantine_homogeneous.argtypes = lib.approxifer_decode_byzantine.argtypes
     lib.approxifer_wait_mask.restype = ctypes.c_int
@@ -242,6 +247,28 @@ def approxifer_decode_byzantine_homogeneous(preds, mask, alpha, beta, S, A, sign
     """As approxifer_decode_byzantine, with Algorithm 1's homogeneous fit as the per-class locator."""
     return _decode_byzantine("approxifer_decode_byzantine_homogeneous", preds, mask, alpha, beta, S, A, sign_mode,
                              out, adv, status, stream, workspace)
+
+
+STATIC_WORKSPACE_BYTES = 65536
+
+
+def approxifer_decode_byzantine_static(preds, mask, alpha, beta, S, A, out, adv, status, sign_mode=SIGN_WORKER_INDEX,
+                                       stream=None):
+    """approxifer_decode_byzantine on the library's built-in workspace.  Allocates nothing: every output is the
+    caller's.  Raises ApproxiferError(-8) for shapes whose workspace exceeds STATIC_WORKSPACE_BYTES."""
+    import torch
+    a, ap = _nodes(alpha)
+    b, bp = _nodes(beta)
+    G, N, C = preds.shape
+    K = a.size
+    if N != b.size:
+        raise ValueError("preds.shape[1] must equal len(beta)")
+    _check(load().approxifer_decode_byzantine_static(_dev(preds, torch.float32), _dev(mask, torch.uint8, (G, N)),
+                                                     _dev(out, torch.float32, (G, K, C)),
+                                                     _dev(adv, torch.int32, (G, int(A))),
+                                                     _dev(status, torch.int32, (G,)), G, K, N, int(S), int(A), C, ap, bp,
+                                                     int(sign_mode), ctypes.c_void_p(_stream_handle(stream))))
+    return out, adv, status
 
 
 def approxifer_wait_mask(arrival, wait_for, mask=None, count=None, stream=None):

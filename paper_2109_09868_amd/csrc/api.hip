@@ -48,6 +48,9 @@ const char *approxifer_strerror(int code) {
         case APPROXIFER_ERR_TOO_FEW_WORKERS: return "the Byzantine decoder needs N - S >= 2 (K + A) available workers";
         case APPROXIFER_ERR_BAD_SIGN_MODE: return "sign_mode must be 0 (worker index) or 1 (survivor rank)";
         case APPROXIFER_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
+        case APPROXIFER_ERR_WORKSPACE_LIMIT:
+            return "the shape needs more scratch memory than the built-in workspace holds (APPROXIFER_STATIC_WORKSPACE_BYTES); "
+                   "use approxifer_decode_byzantine with a workspace of approxifer_workspace_bytes()";
         default: return "unknown approxifer error code";
     }
 }
@@ -140,6 +143,21 @@ int approxifer_decode_byzantine_homogeneous(const float *d_preds, const uint8_t 
                                             int sign_mode, void *d_workspace, size_t workspace_bytes, void *stream) {
     return decode_byzantine_checked(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, S, A, C, h_alpha, h_beta,
                                     sign_mode, true, d_workspace, workspace_bytes, stream);
+}
+
+int approxifer_decode_byzantine_static(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
+                                       int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C,
+                                       const double *h_alpha, const double *h_beta, int sign_mode, void *stream) {
+    // shapes the decoder refuses are refused by the checked call below with their own codes (need is 0 for them)
+    const size_t need = approxifer_workspace_bytes(G, K, N, S, A, C);
+    if (need > APPROXIFER_STATIC_WORKSPACE_BYTES) return APPROXIFER_ERR_WORKSPACE_LIMIT;
+    void *d_scratch = nullptr;
+    if (need > 0) {
+        const int rc = approxifer::static_workspace(&d_scratch);
+        if (rc != APPROXIFER_OK) return rc;
+    }
+    return decode_byzantine_checked(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, S, A, C, h_alpha, h_beta,
+                                    sign_mode, false, d_scratch, need, stream);
 }
 
 size_t approxifer_workspace_bytes(int64_t G, int K, int N, int S, int A, int64_t C) {

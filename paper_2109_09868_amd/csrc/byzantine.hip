@@ -30,7 +30,14 @@
 // rounds of a DPP arg-min in the projected one) vote in an LDS histogram, the A most voted workers
 // (equal counts: smaller index first) leave the available list, and the workgroup decodes the group
 // over the rest.
+#include <mutex>
+
 #include "decode_common.h"
+
+// Built-in workspace of approxifer_decode_byzantine_static(): one copy per GPU the library runs on, held until
+// the process ends.  In host code this name only stands for the symbol; its device address comes from
+// hipGetSymbolAddress (see static_workspace below) and kernels receive that address as an argument.
+static __device__ __align__(256) unsigned char scratch[APPROXIFER_STATIC_WORKSPACE_BYTES];
 
 namespace approxifer {
 namespace {
@@ -989,6 +996,24 @@ int run_proj(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t 
 }
 
 }  // namespace
+
+// Device address of this GPU's copy of the built-in workspace.  Looked up once per device, with that device current
+// (every GPU has its own copy at its own address), and kept for the life of the process.
+int static_workspace(void **d_ptr) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static void *per_device[kMaxDevices] = {};
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return APPROXIFER_ERR_LAUNCH;
+    std::lock_guard<std::mutex> hold(lock);
+    if (per_device[device] == nullptr) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return APPROXIFER_ERR_LAUNCH;
+        per_device[device] = p;
+    }
+    *d_ptr = per_device[device];
+    return APPROXIFER_OK;
+}
 
 size_t byzantine_workspace_bytes(int64_t G, int K, int N, int S, int A, int64_t C) {
     const int n = avail_capacity(N, S);

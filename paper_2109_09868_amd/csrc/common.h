@@ -128,6 +128,7 @@ int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *
                             const Nodes &nodes, int sign_mode, bool homogeneous, void *d_workspace,
                             size_t workspace_bytes, hipStream_t stream);
 size_t byzantine_workspace_bytes(int64_t G, int K, int N, int S, int A, int64_t C);
+int static_workspace(void **d_ptr);
 
 int launch_wait_mask(const float *d_arrival, uint8_t *d_mask, int32_t *d_count, int64_t G, int N, int wait_for,
                      hipStream_t stream);

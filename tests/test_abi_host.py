@@ -42,6 +42,7 @@ def test_header_constants_match_binding():
     assert int(consts["APPROXIFER_MAX_K"]) == binding.MAX_K
     assert int(consts["APPROXIFER_MAX_N"]) == binding.MAX_N
     assert int(consts["APPROXIFER_MAX_AVAIL_BYZ"]) == binding.MAX_AVAIL_BYZ
+    assert int(consts["APPROXIFER_STATIC_WORKSPACE_BYTES"]) == binding.STATIC_WORKSPACE_BYTES
     assert int(consts["APPROXIFER_S_FROM_MASK"]) == binding.S_FROM_MASK == -1
     assert int(consts["APPROXIFER_SIGN_WORKER_INDEX"]) == binding.SIGN_WORKER_INDEX == orc.SIGN_WORKER_INDEX
     assert int(consts["APPROXIFER_SIGN_SURVIVOR_RANK"]) == binding.SIGN_SURVIVOR_RANK == orc.SIGN_SURVIVOR_RANK
@@ -58,11 +59,11 @@ def test_library_nodes_match_oracle_nodes(lib, K, N):
 
 def test_strerror_texts(lib):
     seen = set()
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         s = binding.strerror(code)
         assert s and "unknown" not in s
         seen.add(s)
-    assert len(seen) == 8
+    assert len(seen) == 9
     assert "unknown" in binding.strerror(-99)
 
 
@@ -135,6 +136,21 @@ def test_workspace_bytes(lib):
     # never more than 4 (N + 1) bytes per group plus the rounding
     for G, K, N, S, A, C in ((1, 2, 128, 64, 1, 100000), (5, 14, 64, 0, 2, 5000), (4095, 1, 6, 0, 1, 70000)):
         assert wb(G, K, N, S, A, C) <= 4 * (N + 1) * G + 255
+
+
+def test_static_entry_point_refuses_shapes_beyond_its_workspace(lib):
+    fake = ctypes.c_void_p(256)          # never dereferenced: the calls below are refused on the host
+    st = lib.approxifer_decode_byzantine_static
+    a8, b128 = orc.chebyshev_nodes(8, 128)
+    assert binding.approxifer_workspace_bytes(512, 8, 128, 80, 2, 1000) > binding.STATIC_WORKSPACE_BYTES
+    assert st(fake, fake, fake, fake, None, 512, 8, 128, 80, 2, 1000, _dp(a8), _dp(b128), 0, None) == -8
+    assert "APPROXIFER_STATIC_WORKSPACE_BYTES" in binding.strerror(-8)
+    # the other refusals keep their own codes
+    a8, b24 = orc.chebyshev_nodes(8, 24)
+    assert st(fake, fake, fake, fake, None, 1, 8, 24, 4, 0, 3, _dp(a8), _dp(b24), 0, None) == -2
+    assert st(fake, fake, fake, fake, None, 1, 8, 24, 5, 2, 3, _dp(a8), _dp(b24), 0, None) == -5
+    assert st(fake, fake, fake, None, None, 1, 8, 24, 4, 2, 3, _dp(a8), _dp(b24), 0, None) == -1
+    assert st(None, None, None, None, None, 0, 8, 24, 4, 2, 3, _dp(a8), _dp(b24), 0, None) == 0
 
 
 def test_binding_raises_typed_error(lib):

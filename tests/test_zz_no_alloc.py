@@ -1,0 +1,85 @@
+"""approxifer_decode_byzantine_static: the Byzantine decoder on the library's built-in workspace, for callers that
+cannot allocate.  Called through the raw C ABI and compared with approxifer_decode_byzantine on a caller workspace:
+located sets bit for bit, decoded values within the 1e-5 bar (they are in fact the same bits), two calls in a row,
+the second on a smaller input, so that what the first call left in the shared array must not matter."""
+import ctypes
+
+import numpy as np
+import pytest
+
+from oracle import approxifer_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+def _case(seed, G, K, A, N, C):
+    rng = np.random.default_rng(seed)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    X = rng.uniform(0, 1, (G, K, 40))
+    clean = (orc.encode(X, alpha, beta) @ (rng.standard_normal((40, C)) / 6)).astype(np.float32)
+    M = K + A
+    mask = np.zeros((G, N), np.uint8)
+    Y = clean.copy()
+    for g in range(G):
+        cnt = 2 * M - 1 if g == 1 else int(rng.integers(2 * M, N + 1))     # group 1: one worker too few
+        avail = np.sort(rng.permutation(N)[:cnt])
+        mask[g, avail] = 1
+        ok = avail[np.abs(beta[avail]) > 1e-9]
+        bad = np.sort(rng.permutation(ok)[:A])
+        Y[g, bad] += (10 * clean.std() * rng.standard_normal((A, C))).astype(np.float32)
+    return alpha, beta, Y, mask
+
+
+def test_static_workspace_entry_point_matches_the_workspace_one():
+    import torch
+    from paper_2109_09868_amd import binding
+    assert torch.cuda.is_available()
+    lib = binding.load()
+    dev = torch.device("cuda:0")
+    dp = ctypes.POINTER(ctypes.c_double)
+    # first a larger input whose groups are shared between workgroups, then a smaller one (fewer groups, fewer
+    # workers, fewer classes: its workspace words are a strict subset of the first call's, left dirty by it),
+    # then a shape that needs no workspace at all
+    for seed, (G, K, A, N, C) in enumerate([(6, 8, 2, 24, 1000), (3, 4, 1, 12, 515), (64, 8, 2, 24, 10)]):
+        alpha, beta, Y, mask = _case(40 + seed, G, K, A, N, C)
+        need = binding.approxifer_workspace_bytes(G, K, N, binding.S_FROM_MASK, A, C)
+        assert need <= binding.STATIC_WORKSPACE_BYTES and (need > 0) == (seed < 2)
+        a64, b64 = np.ascontiguousarray(alpha), np.ascontiguousarray(beta)
+        Yd, md = torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev)
+        stream = torch.cuda.current_stream().cuda_stream
+
+        def outputs():
+            return (torch.full((G, K, C), -3.0, dtype=torch.float32, device=dev),
+                    torch.full((G, A), -7, dtype=torch.int32, device=dev),
+                    torch.full((G,), -9, dtype=torch.int32, device=dev))
+
+        o_ws, a_ws, s_ws = outputs()
+        ws = torch.zeros((max(need, 4),), dtype=torch.uint8, device=dev)
+        rc = lib.approxifer_decode_byzantine(Yd.data_ptr(), md.data_ptr(), o_ws.data_ptr(), a_ws.data_ptr(),
+                                             s_ws.data_ptr(), G, K, N, binding.S_FROM_MASK, A, C, a64.ctypes.data_as(dp),
+                                             b64.ctypes.data_as(dp), 1, ws.data_ptr() if need else None,
+                                             ctypes.c_size_t(need), stream)
+        assert rc == 0
+        o_st, a_st, s_st = outputs()
+        torch.cuda.synchronize()
+        rc = lib.approxifer_decode_byzantine_static(Yd.data_ptr(), md.data_ptr(), o_st.data_ptr(), a_st.data_ptr(),
+                                                    s_st.data_ptr(), G, K, N, binding.S_FROM_MASK, A, C,
+                                                    a64.ctypes.data_as(dp), b64.ctypes.data_as(dp), 1, stream)
+        assert rc == 0
+        torch.cuda.synchronize()
+        s = s_st.cpu().numpy()
+        assert np.array_equal(s, s_ws.cpu().numpy()) and s[1] == 1 and s.sum() == 1
+        assert np.array_equal(a_st.cpu().numpy(), a_ws.cpu().numpy())          # located sets, bit for bit
+        got, want = o_st.cpu().numpy().astype(np.float64), o_ws.cpu().numpy().astype(np.float64)
+        assert np.all(got[1] == -3.0) and np.all(a_st.cpu().numpy()[1] == -7)   # the rejected group is untouched
+        good = s == 0
+        scale = np.abs(want[good]).reshape(good.sum(), -1).max(axis=1)
+        err = np.abs(got[good] - want[good]).reshape(good.sum(), -1).max(axis=1) / scale
+        assert err.max() <= TOL
+        # and both agree with the oracle
+        ref, adv_ref, st_ref = orc.decode_byzantine(Y, mask, alpha, beta, None, A, 1)
+        assert np.array_equal(s, st_ref) and np.array_equal(a_st.cpu().numpy()[good], adv_ref[good])
+        err = np.abs(got[good] - ref[good]).reshape(good.sum(), -1).max(axis=1) / np.abs(ref[good]).reshape(good.sum(), -1).max(axis=1)
+        assert err.max() <= TOL
