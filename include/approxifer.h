@@ -94,6 +94,24 @@ int approxifer_encode(const float *d_queries, float *d_coded,
                       const double *h_alpha, const double *h_beta, void *stream);
 
 /*
+ * Forming groups out of a stream of queries (Section 2, "System Architecture": the K queries of a group are
+ * encoded together).  With the [G][K][D] layout of approxifer_encode() a stream of Q queries stored row by row,
+ * [Q][D], IS its groups: queries g K .. g K + K - 1 are group g, no copy is made.  approxifer_group_count()
+ * returns G = ceil(Q / K) (-1 for Q < 0 or K < 1).  When K does not divide Q the last group is short; the paper
+ * has no rule for it, this library completes it by repeating the stream's last query (the interpolant then passes
+ * through that query at every added node -- for a group of one query this is the replication the encoder reduces
+ * to at K = 1 -- and the added answers are simply not read back).
+ *
+ * approxifer_pad_last_group(): d_queries is a device buffer of at least G K rows of D floats whose first Q rows
+ * hold the stream; rows Q .. G K - 1 are overwritten with copies of row Q - 1.  Nothing is enqueued when K
+ * divides Q, or when Q = 0 or D = 0.  Ungrouping needs no call: row q of the decoded [G][K][C] tensor (of the
+ * [G][K] top-1 tensor) is query q's answer, rows Q and up belong to the repeated query.
+ * Returns OK, ERR_NULL_POINTER, ERR_BAD_SHAPE (Q < 0, D < 0, K < 1), ERR_LIMIT (K > APPROXIFER_MAX_K) or ERR_LAUNCH.
+ */
+int64_t approxifer_group_count(int64_t Q, int K);
+int approxifer_pad_last_group(float *d_queries, int64_t Q, int K, int64_t D, void *stream);
+
+/*
  * Decoder (Section 3, "ApproxIFER Decoding", step 2).  For every group g, with F the
  * set of workers whose mask byte is non-zero, in ascending order,
  *     d_out[g][j][:] = r_g(alpha_j)
@@ -219,6 +237,25 @@ int approxifer_decode_byzantine_homogeneous(const float *d_preds, const uint8_t 
                                             void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Decoder by rational reconstruction (Appendix A, Algorithm 3 and Theorem 2).  For every group, class c and
+ * query j: with (P, Q) the least-squares fit of Algorithm 2 (degrees K + A - 1, Q_0 = 1) to the class's
+ * values on the available workers,
+ *     d_out[g][j][c] = P(alpha_j) / Q(alpha_j).
+ * No worker is located or dropped and Berrut's interpolant is not used: when the hosted model makes the
+ * coded predictions exactly rational in the node and at most A workers lie, P / Q is that rational function
+ * (Theorem 2).  The paper sets this decoder aside because the quotient is fragile under round-off -- P and Q
+ * share the error-locator factor -- and so does this library: it is here to make the comparison possible,
+ * approxifer_decode_byzantine() is the decoder to use.  On float32 data of the paper's sizes single groups lose
+ * several digits; the fit's condition number, not the arithmetic (float64 Householder QR), bounds the accuracy.
+ *   arguments, requirements, status values and error codes as approxifer_decode_byzantine(), without
+ *   d_adv, sign_mode and workspace; groups with a bad mask leave their d_out rows untouched.  Q can vanish
+ *   at a query node only by accident of the data; the quotient is then non-finite.
+ */
+int approxifer_decode_rational(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_status,
+                               int64_t G, int K, int N, int S, int A, int64_t C,
+                               const double *h_alpha, const double *h_beta, void *stream);
+
+/*
  * Fused decoder + top-1 (Section 4.1, "Performance metric": the paper scores the class of the
  * largest decoded soft label).  Decodes exactly as approxifer_decode() does, in float64, and for
  * every group g and query j writes only
@@ -235,6 +272,18 @@ int approxifer_decode_byzantine_homogeneous(const float *d_preds, const uint8_t 
 int approxifer_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_top1, float *d_score,
                            int32_t *d_status, int64_t G, int K, int N, int S, int64_t C,
                            const double *h_alpha, const double *h_beta, int sign_mode, void *stream);
+
+/*
+ * Top-1 of an already decoded tensor (Section 4.1, "Performance metric"): for every row of d_values [rows][C]
+ * the class of the largest value (equal values: the smallest class) and, optionally, that value.  For the
+ * outputs of approxifer_decode_byzantine(), whose [G][K][C] tensor is [G K][C] row by row;
+ * approxifer_decode_top1() fuses the same decision into the plain decoder.  The decision is taken on the
+ * float32 values as stored.  NaN never wins; a row without any ordinary value gives class 0.
+ *   d_values  [rows][C] float32, device, read only
+ *   d_top1    [rows] int32, device, written;  d_score [rows] float32, device, written, or NULL
+ * Returns OK, ERR_NULL_POINTER, ERR_BAD_SHAPE (rows < 0 or C < 0), ERR_LIMIT (C >= 2^31) or ERR_LAUNCH.
+ */
+int approxifer_top1(const float *d_values, int32_t *d_top1, float *d_score, int64_t rows, int64_t C, void *stream);
 
 /*
  * Wait rule (Section 3, "ApproxIFER Decoding", step 1: the decoder waits for the results of the

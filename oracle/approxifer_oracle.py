@@ -29,7 +29,9 @@ and under that reading the fit is pinned to the exact minimiser (normal equation
 over rationals on small systems); the reading itself is ours: parity unpinned.  Algorithm 1's homogeneous system is read as "the
 unit coefficient vector of least residual" (smallest right singular vector); on
 exactly rational data every reading gives the same null vector and the pins
-hold it there, on other data: parity unpinned beyond that reading.
+hold it there, on other data: parity unpinned beyond that reading.  Algorithm 3
+(`rational_reconstruction`, `decode_rational`) is pinned by Theorem 2: on exactly
+rational float64 data with at most A errors it returns the hosted function itself.
 """
 from __future__ import annotations
 
@@ -113,6 +115,21 @@ def encode(X, alpha, beta):
         raise ValueError("X must be [G, K, D] with K = len(alpha)")
     L = encode_weights(alpha, beta)                       # [W, K]
     return np.einsum("ij,gjd->gid", L, X.astype(np.float64))
+
+
+def group_queries(stream, K):
+    """Groups of K consecutive queries out of a stream [Q, D] (Section 2, "System Architecture": the K queries of
+    a group are encoded together).  Returns [G, K, D] with G = ceil(Q / K).  The paper has no rule for a stream whose
+    length K does not divide; here the last group is completed by repeating the stream's last query (a reading of
+    our own), and the answers of the repeats are not read back: answers [G, K, ...] flattened to [G K, ...] hold
+    query q's answer in row q."""
+    stream = np.asarray(stream)
+    Q, D = stream.shape
+    G = -(-Q // K)
+    out = np.empty((G * K, D), dtype=stream.dtype)
+    out[:Q] = stream
+    out[Q:] = stream[Q - 1] if Q > 0 else 0
+    return out.reshape(G, K, D)
 
 
 # --------------------------------------------------------------------------
@@ -333,4 +350,26 @@ def rational_reconstruction(x, y, K, A, z):
         num = num * z + P[k]
         den = den * z + Q[k]
     return num / den
+
+
+def decode_rational(Y, mask, alpha, beta, S, A):
+    """Appendix A, Algorithm 3 as a decoder for whole groups: out[g, j, c] = r_c(alpha_j) with r_c = P / Q the
+    reconstruction of class c from the group's available workers (rational_reconstruction above).  No worker is
+    located or dropped.  Group acceptance as in decode_byzantine.  Returns (out [G, K, C] float64, status [G])."""
+    Y = np.asarray(Y)
+    mask = np.asarray(mask)
+    alpha = np.asarray(alpha, dtype=np.float64)
+    beta = np.asarray(beta, dtype=np.float64)
+    G, W, C = Y.shape
+    K = alpha.size
+    out = np.zeros((G, K, C), dtype=np.float64)
+    status = np.zeros(G, dtype=np.int32)
+    for g in range(G):
+        avail = np.nonzero(mask[g] != 0)[0]
+        if (avail.size != W - S) if (S is not None and S >= 0) else (avail.size < 2 * (K + A)):
+            status[g] = 1
+            continue
+        for c in range(C):
+            out[g, :, c] = rational_reconstruction(beta[avail], Y[g, avail, c], K, A, alpha)
+    return out, status
 

@@ -33,6 +33,10 @@ EXPORTS = (
     "approxifer_decode_byzantine_homogeneous",
     "approxifer_workspace_bytes",
     "approxifer_decode_byzantine_static",
+    "approxifer_decode_rational",
+    "approxifer_group_count",
+    "approxifer_pad_last_group",
+    "approxifer_top1",
 )
 
 _lib = None
@@ -82,6 +86,15 @@ def load() -> ctypes.CDLL:
     lib.approxifer_decode_byzantine_static.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                                        ctypes.c_int, ctypes.c_int, ctypes.c_int64, c_dp, c_dp,
                                                        ctypes.c_int, vp]
+    lib.approxifer_group_count.restype = ctypes.c_int64
+    lib.approxifer_group_count.argtypes = [ctypes.c_int64, ctypes.c_int]
+    lib.approxifer_pad_last_group.restype = ctypes.c_int
+    lib.approxifer_pad_last_group.argtypes = [vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int64, vp]
+    lib.approxifer_top1.restype = ctypes.c_int
+    lib.approxifer_top1.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int64, vp]
+    lib.approxifer_decode_rational.restype = ctypes.c_int
+    lib.approxifer_decode_rational.argtypes = [vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                               ctypes.c_int, ctypes.c_int64, c_dp, c_dp, vp]
     lib.approxifer_decode_byzantine_homogeneous.restype = ctypes.c_int
     lib.approxifer_decode_byzantine_homogeneous.argtypes = lib.approxifer_decode_byzantine.argtypes
     lib.approxifer_wait_mask.restype = ctypes.c_int
@@ -130,6 +143,24 @@ def approxifer_chebyshev_nodes(K: int, N: int):
                                              alpha.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
                                              beta.ctypes.data_as(ctypes.POINTER(ctypes.c_double))))
     return alpha, beta
+
+
+def approxifer_group_count(Q: int, K: int) -> int:
+    """Number of groups of K consecutive queries that a stream of Q queries forms."""
+    return int(load().approxifer_group_count(int(Q), int(K)))
+
+
+def approxifer_pad_last_group(buffer, Q, K, stream=None):
+    """buffer: [rows, D] float32 device tensor with rows >= ceil(Q / K) * K whose first Q rows hold the stream;
+    rows Q .. ceil(Q / K) * K - 1 become copies of row Q - 1.  Returns the buffer's first G * K rows as [G, K, D]."""
+    import torch
+    rows, D = buffer.shape
+    G = approxifer_group_count(Q, K)
+    if G < 0 or rows < G * K:
+        raise ValueError("the buffer must hold ceil(Q / K) * K rows")
+    _check(load().approxifer_pad_last_group(_dev(buffer, torch.float32), int(Q), int(K), int(D),
+                                            ctypes.c_void_p(_stream_handle(stream))))
+    return buffer[: G * K].view(G, K, D)
 
 
 def approxifer_encode(queries, alpha, beta, coded=None, stream=None):
@@ -247,6 +278,42 @@ def approxifer_decode_byzantine_homogeneous(preds, mask, alpha, beta, S, A, sign
     """As approxifer_decode_byzantine, with Algorithm 1's homogeneous fit as the per-class locator."""
     return _decode_byzantine("approxifer_decode_byzantine_homogeneous", preds, mask, alpha, beta, S, A, sign_mode,
                              out, adv, status, stream, workspace)
+
+
+def approxifer_decode_rational(preds, mask, alpha, beta, S, A, out=None, status=None, stream=None):
+    """Algorithm 3: out[g, j, c] = P(alpha_j) / Q(alpha_j) with (P, Q) Algorithm 2's fit per class.
+    Returns (out [G, K, C] float32, status [G] int32)."""
+    import torch
+    a, ap = _nodes(alpha)
+    b, bp = _nodes(beta)
+    G, N, C = preds.shape
+    K = a.size
+    if N != b.size:
+        raise ValueError("preds.shape[1] must equal len(beta)")
+    if out is None:
+        out = torch.zeros((G, K, C), dtype=torch.float32, device=preds.device)
+    if status is None:
+        status = torch.full((G,), -1, dtype=torch.int32, device=preds.device)
+    _check(load().approxifer_decode_rational(_dev(preds, torch.float32), _dev(mask, torch.uint8, (G, N)),
+                                             _dev(out, torch.float32, (G, K, C)), _dev(status, torch.int32, (G,)),
+                                             G, K, N, int(S), int(A), C, ap, bp, ctypes.c_void_p(_stream_handle(stream))))
+    return out, status
+
+
+def approxifer_top1(values, top1=None, score=None, stream=None, want_score=True):
+    """values [..., C] float32 device tensor -> (top1 [...] int32, score [...] float32 or None)."""
+    import torch
+    C = values.shape[-1]
+    lead = tuple(values.shape[:-1])
+    rows = int(np.prod(lead)) if lead else 1
+    if top1 is None:
+        top1 = torch.full(lead, -1, dtype=torch.int32, device=values.device)
+    if score is None and want_score:
+        score = torch.zeros(lead, dtype=torch.float32, device=values.device)
+    _check(load().approxifer_top1(_dev(values, torch.float32), _dev(top1, torch.int32, lead),
+                                  _dev(score, torch.float32, lead) if score is not None else None, rows, C,
+                                  ctypes.c_void_p(_stream_handle(stream))))
+    return top1, score
 
 
 STATIC_WORKSPACE_BYTES = 65536

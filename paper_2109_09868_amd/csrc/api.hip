@@ -74,6 +74,19 @@ int approxifer_encode(const float *d_queries, float *d_coded, int64_t G, int K, 
     return approxifer::launch_encode(d_queries, d_coded, G, K, N, D, nodes, static_cast<hipStream_t>(stream));
 }
 
+int64_t approxifer_group_count(int64_t Q, int K) {
+    if (Q < 0 || K < 1) return -1;
+    return (Q + K - 1) / K;
+}
+
+int approxifer_pad_last_group(float *d_queries, int64_t Q, int K, int64_t D, void *stream) {
+    if (Q < 0 || D < 0 || K < 1) return APPROXIFER_ERR_BAD_SHAPE;
+    if (K > APPROXIFER_MAX_K) return APPROXIFER_ERR_LIMIT;
+    if (Q == 0 || D == 0 || Q % K == 0) return APPROXIFER_OK;
+    if (d_queries == nullptr) return APPROXIFER_ERR_NULL_POINTER;
+    return approxifer::launch_pad_last_group(d_queries, Q, K, D, static_cast<hipStream_t>(stream));
+}
+
 int approxifer_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_status, int64_t G, int K,
                       int N, int S, int64_t C, const double *h_alpha, const double *h_beta, int sign_mode,
                       void *stream) {
@@ -145,6 +158,23 @@ int approxifer_decode_byzantine_homogeneous(const float *d_preds, const uint8_t 
                                     sign_mode, true, d_workspace, workspace_bytes, stream);
 }
 
+int approxifer_decode_rational(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_status, int64_t G,
+                               int K, int N, int S, int A, int64_t C, const double *h_alpha, const double *h_beta,
+                               void *stream) {
+    if (G < 0 || C < 0) return APPROXIFER_ERR_BAD_SHAPE;
+    Nodes nodes;
+    const int rc = check_common(K, N, h_alpha, h_beta, &nodes);
+    if (rc != APPROXIFER_OK) return rc;
+    if (S < APPROXIFER_S_FROM_MASK || S >= N || A < 1) return APPROXIFER_ERR_BAD_SHAPE;
+    const int most_available = S < 0 ? N : N - S;
+    if (most_available < 2 * (K + A)) return APPROXIFER_ERR_TOO_FEW_WORKERS;
+    if (S >= 0 && N - S > APPROXIFER_MAX_AVAIL_BYZ) return APPROXIFER_ERR_LIMIT;
+    if (G == 0 || C == 0) return APPROXIFER_OK;
+    if (d_mask == nullptr || d_preds == nullptr || d_out == nullptr) return APPROXIFER_ERR_NULL_POINTER;
+    return approxifer::launch_decode_rational(d_preds, d_mask, d_out, d_status, G, K, N, S, A, C, nodes,
+                                              static_cast<hipStream_t>(stream));
+}
+
 int approxifer_decode_byzantine_static(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
                                        int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C,
                                        const double *h_alpha, const double *h_beta, int sign_mode, void *stream) {
@@ -167,6 +197,14 @@ size_t approxifer_workspace_bytes(int64_t G, int K, int N, int S, int A, int64_t
     const int most_available = S < 0 ? N : N - S;
     if (most_available < 2 * (K + A) || (S >= 0 && N - S > APPROXIFER_MAX_AVAIL_BYZ)) return 0;
     return approxifer::byzantine_workspace_bytes(G, K, N, S, A, C);
+}
+
+int approxifer_top1(const float *d_values, int32_t *d_top1, float *d_score, int64_t rows, int64_t C, void *stream) {
+    if (rows < 0 || C < 0) return APPROXIFER_ERR_BAD_SHAPE;
+    if (C > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;   // class indices are int32
+    if (rows == 0 || C == 0) return APPROXIFER_OK;
+    if (d_values == nullptr || d_top1 == nullptr) return APPROXIFER_ERR_NULL_POINTER;
+    return approxifer::launch_argmax_rows(d_values, d_top1, d_score, rows, C, static_cast<hipStream_t>(stream));
 }
 
 int approxifer_wait_mask(const float *d_arrival, uint8_t *d_mask, int32_t *d_count, int64_t G, int N, int wait_for,

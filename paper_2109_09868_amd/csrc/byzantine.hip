@@ -709,33 +709,13 @@ __device__ __forceinline__ void homogeneous_q(double *mat, int LD, double *coef,
     __builtin_amdgcn_wave_barrier();                      // key is reused by the caller
 }
 
-// Algorithm 2, steps 1-5, for the classes c0 .. c0+cpw-1 of one group, by one wave.
-//   n        available workers (rows), M = K + A, W2 = 2M columns including the right-hand side
-//   xs[n]    worker nodes of the available workers (LDS, shared by the workgroup)
-//   scratch  this wave's LDS: per class  mat[n][W2] | coef[M] | key[n]
-// Lane (cl, j) = (lane / W2, lane % W2) works on class c0 + cl; lanes beyond cpw classes idle.
-// HOMOG: Algorithm 1's fit instead (Q_0 free).  The last column, y, then is one more column of the homogeneous
-// system [V | -y x^1 .. -y x^(M-1) | y] whose coefficient is -Q_0; (P, Q) is its null vector of unit length.
-template <bool HOMOG>
-__device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg, int64_t C, int64_t c0, int cpw,
-                                                    const int *avail, const double *xs, int n, int M, int A,
-                                                    double *scratch, int *votes) {
-    const int lane = lane_id();
-    const int W2 = 2 * M;
-    const int cols = W2 - 1;                 // unknowns P_0..P_{M-1}, Q_1..Q_{M-1}; column `cols` is the rhs
-    const int cl = lane / W2;
-    const int j = lane - cl * W2;
-    const int64_t c = c0 + cl;
-    const bool live = cl < cpw && c < C;     // this lane's class exists
-    const int LD = HOMOG ? W2 + 1 : W2;     // row stride of mat; odd for the column rotations of Algorithm 1's fit
-    const int per_class = n * LD + M + n;
-    double *mat = scratch + (live ? cl : 0) * per_class;
-    double *coef = mat + n * LD;
-    double *key = coef + M;
-
-    // ---- steps 1-2: the system, one lane per row (rows j, j+W2, ..) -------------------
+// Algorithm 2, steps 1-2, for one class: row r of the n x 2M matrix  [x^0 .. x^(M-1) | -y x^1 .. -y x^(M-1) | y]
+// (the last column is the right-hand side), written by lane j of the class's `width` lanes for rows j, j+width, ..
+__device__ __forceinline__ void build_class_system(const float *__restrict__ pg, int64_t C, int64_t c, const int *avail,
+                                                   const double *xs, int n, int M, double *mat, int LD, int j, int width,
+                                                   bool live) {
     if (live) {
-        for (int r = j; r < n; r += W2) {
+        for (int r = j; r < n; r += width) {
             const double x = xs[r];
             const double y = static_cast<double>(pg[static_cast<size_t>(avail[r]) * C + c]);
             double *row = mat + r * LD;
@@ -745,15 +725,15 @@ __device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg
                 if (k >= 1) row[M - 1 + k] = -y * p;      // -y x^k
                 p *= x;
             }
-            row[cols] = y;
+            row[2 * M - 1] = y;
         }
     }
     __builtin_amdgcn_wave_barrier();
+}
 
-    // ---- Householder QR in least-squares form, one lane per column ---------------------
-    // Step k reflects column k onto e_k over rows k..n-1 and applies the reflector to the
-    // columns right of it (and to the right-hand side).
-    const int qr_steps = HOMOG ? W2 : cols;               // n >= W2: eq. (3)
+// Householder QR in least-squares form, one lane per column: step k reflects column k onto e_k over rows k..n-1
+// and applies the reflector to the columns right of it (and to the right-hand side).
+__device__ __forceinline__ void factor_class_system(double *mat, int LD, int n, int j, int qr_steps, bool live) {
     for (int k = 0; k < qr_steps; ++k) {
         double sigma = 0.0, d = 0.0;
 #pragma unroll 4
@@ -780,6 +760,34 @@ __device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg
         }
         __builtin_amdgcn_wave_barrier();
     }
+}
+
+// Algorithm 2, steps 1-5, for the classes c0 .. c0+cpw-1 of one group, by one wave.
+//   n        available workers (rows), M = K + A, W2 = 2M columns including the right-hand side
+//   xs[n]    worker nodes of the available workers (LDS, shared by the workgroup)
+//   scratch  this wave's LDS: per class  mat[n][W2] | coef[M] | key[n]
+// Lane (cl, j) = (lane / W2, lane % W2) works on class c0 + cl; lanes beyond cpw classes idle.
+// HOMOG: Algorithm 1's fit instead (Q_0 free).  The last column, y, then is one more column of the homogeneous
+// system [V | -y x^1 .. -y x^(M-1) | y] whose coefficient is -Q_0; (P, Q) is its null vector of unit length.
+template <bool HOMOG>
+__device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg, int64_t C, int64_t c0, int cpw,
+                                                    const int *avail, const double *xs, int n, int M, int A,
+                                                    double *scratch, int *votes) {
+    const int lane = lane_id();
+    const int W2 = 2 * M;
+    const int cols = W2 - 1;                 // unknowns P_0..P_{M-1}, Q_1..Q_{M-1}; column `cols` is the rhs
+    const int cl = lane / W2;
+    const int j = lane - cl * W2;
+    const int64_t c = c0 + cl;
+    const bool live = cl < cpw && c < C;     // this lane's class exists
+    const int LD = HOMOG ? W2 + 1 : W2;     // row stride of mat; odd for the column rotations of Algorithm 1's fit
+    const int per_class = n * LD + M + n;
+    double *mat = scratch + (live ? cl : 0) * per_class;
+    double *coef = mat + n * LD;
+    double *key = coef + M;
+
+    build_class_system(pg, C, c, avail, xs, n, M, mat, LD, j, W2, live);
+    factor_class_system(mat, LD, n, j, HOMOG ? W2 : cols, live);
 
     if (HOMOG) {
         // ---- the null vector, then a_r = Q(x_r): Q_k = coef[k-1] for k >= 1, Q_0 = -coef[M-1] ----------------------
@@ -820,6 +828,84 @@ __device__ __forceinline__ void locate_classes_wave(const float *__restrict__ pg
     __builtin_amdgcn_wave_barrier();
     if (live) pick_and_vote(key, avail, n, A, j, W2, votes);
     __builtin_amdgcn_wave_barrier();
+}
+
+// Appendix A, Algorithm 3, for the classes c0 .. c0+cpw-1 of one group, by one wave: the same least-squares fit of
+// (P, Q) as Algorithm 2, then the K values r(alpha_j) = P(alpha_j) / Q(alpha_j) instead of an error locator.
+// Layout as locate_classes_wave (per class  mat[n][2M] | sol[2M-1] in the coef and key slots); lane j of a class
+// evaluates query j, so K <= 2M lanes always suffice.
+__device__ __forceinline__ void reconstruct_classes_wave(const float *__restrict__ pg, float *__restrict__ og, int64_t C,
+                                                         int64_t c0, int cpw, const int *avail, const double *xs,
+                                                         const double *alpha_s, int n, int K, int M, double *scratch) {
+    const int lane = lane_id();
+    const int W2 = 2 * M;
+    const int cols = W2 - 1;                 // unknowns P_0..P_{M-1}, Q_1..Q_{M-1}; column `cols` is the rhs
+    const int cl = lane / W2;
+    const int j = lane - cl * W2;
+    const int64_t c = c0 + cl;
+    const bool live = cl < cpw && c < C;
+    const int per_class = n * W2 + M + n;    // M + n >= 3M > cols doubles follow the matrix
+    double *mat = scratch + (live ? cl : 0) * per_class;
+    double *sol = mat + n * W2;
+
+    build_class_system(pg, C, c, avail, xs, n, M, mat, W2, j, W2, live);
+    factor_class_system(mat, W2, n, j, cols, live);
+
+    // back substitution for every unknown; lane j holds the transformed right-hand side entry of row j
+    double s = (live && j < cols) ? mat[j * W2 + cols] : 0.0;
+    const double diag = (live && j < cols) ? mat[j * W2 + j] : 1.0;
+    for (int t = cols - 1; t >= 0; --t) {
+        if (live && j == t) sol[t] = s / diag;
+        __builtin_amdgcn_wave_barrier();
+        const double v = sol[t];
+        if (live && j < t) s = fma(-mat[j * W2 + t], v, s);
+        __builtin_amdgcn_wave_barrier();
+    }
+    if (live && j < K) {
+        const double z = alpha_s[j];
+        double num = 0.0, den = 0.0;
+        for (int k = M - 1; k >= 0; --k) num = fma(num, z, sol[k]);              // P_0 .. P_{M-1}
+        for (int k = M - 1; k >= 1; --k) den = fma(den, z, sol[M - 1 + k]);      // Q_1 .. Q_{M-1}
+        den = fma(den, z, 1.0);                                                  // Q_0 = 1
+        og[static_cast<size_t>(j) * C + c] = static_cast<float>(num / den);
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+// One workgroup per group; waves take the classes cpw at a time.
+// dynamic LDS: double scratch[nw][cpw * (n*2M + M + n)] | double xs[n] | double alpha_s[K] | double beta_s[N] | int avail[N] | int n
+__global__ void decode_rational_kernel(const float *__restrict__ preds, const uint8_t *__restrict__ mask,
+                                       float *__restrict__ out, int32_t *__restrict__ status, int K, int N, int S, int A,
+                                       int64_t C, int cpw, int n_cap, const Nodes nodes) {
+    extern __shared__ __align__(16) double lds_d[];
+    const int M = K + A;
+    const int nw = blockDim.x / kWave;
+    const int wave_doubles = cpw * (n_cap * 2 * M + M + n_cap);
+    double *scratch = lds_d;
+    double *xs = scratch + static_cast<size_t>(nw) * wave_doubles;
+    double *alpha_s = xs + n_cap;
+    double *beta_s = alpha_s + K;
+    int *avail = reinterpret_cast<int *>(beta_s + N);
+    int *n_sh = avail + N;
+    const int64_t g = blockIdx.x;
+    const int wv = wave_id();
+
+    stage_nodes(nodes, K, N, alpha_s, beta_s);
+    if (wv == 0) {
+        const int cnt = survivors_from_mask(mask + g * N, N, avail);
+        if (lane_id() == 0) *n_sh = cnt;
+    }
+    __syncthreads();
+    const int n = *n_sh;
+    const bool good = S < 0 ? (n >= 2 * M && n <= n_cap) : n == n_cap;
+    if (threadIdx.x == 0 && status != nullptr) status[g] = good ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
+    if (!good) return;
+    for (int r = threadIdx.x; r < n; r += blockDim.x) xs[r] = beta_s[avail[r]];
+    __syncthreads();
+    const float *pg = preds + static_cast<size_t>(g) * N * C;
+    float *og = out + static_cast<size_t>(g) * K * C;
+    for (int64_t c0 = static_cast<int64_t>(wv) * cpw; c0 < C; c0 += static_cast<int64_t>(nw) * cpw)
+        reconstruct_classes_wave(pg, og, C, c0, cpw, avail, xs, alpha_s, n, K, M, scratch + static_cast<size_t>(wv) * wave_doubles);
 }
 
 // dynamic LDS: double scratch[nw][cpw * (n*LD + M + n)] (LD = 2M, 2M+1 for Algorithm 1) | double WdT[(n-A) * KP] | double xs[n]
@@ -1013,6 +1099,29 @@ int static_workspace(void **d_ptr) {
     }
     *d_ptr = per_device[device];
     return APPROXIFER_OK;
+}
+
+int launch_decode_rational(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_status, int64_t G, int K,
+                           int N, int S, int A, int64_t C, const Nodes &nodes, hipStream_t stream) {
+    const int n = avail_capacity(N, S);
+    const int M = K + A;
+    if (G > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    int cpw = kWave / (2 * M);
+    if (cpw < 1) cpw = 1;
+    if (cpw > C) cpw = static_cast<int>(C);
+    const size_t fixed = sizeof(double) * (static_cast<size_t>(n) + K + N) + sizeof(int) * (static_cast<size_t>(N) + 2);
+    const size_t per_class = sizeof(double) * (static_cast<size_t>(n) * 2 * M + M + n);
+    const size_t budget = 64 * 1024;
+    while (cpw > 1 && fixed + cpw * per_class > budget) --cpw;
+    const size_t per_wave = cpw * per_class;
+    if (fixed + per_wave > budget) return APPROXIFER_ERR_LIMIT;
+    int nw = static_cast<int>((C + cpw - 1) / cpw);
+    if (nw > 4) nw = 4;
+    if (nw > static_cast<int>((budget - fixed) / per_wave)) nw = static_cast<int>((budget - fixed) / per_wave);
+    if (nw < 1) nw = 1;
+    return launch_status(launch_kernel(decode_rational_kernel, dim3(static_cast<unsigned>(G)), dim3(nw * kWave),
+                                       fixed + nw * per_wave, stream, d_preds, d_mask, d_out, d_status, K, N, S, A, C, cpw, n,
+                                       nodes));
 }
 
 size_t byzantine_workspace_bytes(int64_t G, int K, int N, int S, int A, int64_t C) {

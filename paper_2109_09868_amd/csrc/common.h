@@ -117,6 +117,7 @@ inline int launch_status(hipError_t e) { return e == hipSuccess ? APPROXIFER_OK 
 // Host-side launchers (defined in encode.hip / decode.hip / byzantine.hip).
 int launch_encode(const float *d_queries, float *d_coded, int64_t G, int K, int N, int64_t D,
                   const Nodes &nodes, hipStream_t stream);
+int launch_pad_last_group(float *d_queries, int64_t Q, int K, int64_t D, hipStream_t stream);
 int launch_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_status,
                   int64_t G, int K, int N, int S, int64_t C, const Nodes &nodes, int sign_mode,
                   hipStream_t stream);
@@ -127,9 +128,13 @@ int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *
                             int32_t *d_status, int64_t G, int K, int N, int S, int A, int64_t C,
                             const Nodes &nodes, int sign_mode, bool homogeneous, void *d_workspace,
                             size_t workspace_bytes, hipStream_t stream);
+int launch_decode_rational(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_status, int64_t G, int K,
+                           int N, int S, int A, int64_t C, const Nodes &nodes, hipStream_t stream);
 size_t byzantine_workspace_bytes(int64_t G, int K, int N, int S, int A, int64_t C);
 int static_workspace(void **d_ptr);
 
+int launch_argmax_rows(const float *d_values, int32_t *d_top1, float *d_score, int64_t rows, int64_t C,
+                       hipStream_t stream);
 int launch_wait_mask(const float *d_arrival, uint8_t *d_mask, int32_t *d_count, int64_t G, int N, int wait_for,
                      hipStream_t stream);
 

@@ -626,6 +626,46 @@ __global__ __launch_bounds__(kWaitGroups *kWave) void wait_mask_kernel(const flo
     if (lane == 0 && count != nullptr) count[g] = total;
 }
 
+// ------------------------------------------------------------------------------------
+// top-1 of an already decoded tensor
+// ------------------------------------------------------------------------------------
+// One wave per row of [rows][C] float32: largest value, smallest class on equal values (NaN never wins; a row of
+// NaNs gives class 0).  Four rows per workgroup.
+constexpr int kArgmaxRows = 4;
+
+__global__ __launch_bounds__(kArgmaxRows *kWave) void argmax_rows_kernel(const float *__restrict__ values,
+                                                                          int32_t *__restrict__ top1,
+                                                                          float *__restrict__ score, int64_t rows,
+                                                                          int64_t C) {
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * kArgmaxRows + wave_id();
+    if (row >= rows) return;
+    const int lane = lane_id();
+    const float *v = values + row * C;
+    float bv = -__builtin_inff();
+    int bi = 0x7fffffff;
+    for (int64_t c = lane; c < C; c += kWave) {
+        const float x = v[c];
+        if (x > bv) {                                       // ascending c: the first occurrence stays
+            bv = x;
+            bi = static_cast<int>(c);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float ov = __shfl_xor(bv, off, kWave);
+        const int oi = __shfl_xor(bi, off, kWave);
+        if (ov > bv || (ov == bv && oi < bi)) {
+            bv = ov;
+            bi = oi;
+        }
+    }
+    if (lane == 0) {
+        const bool none = bi == 0x7fffffff;                 // every value NaN or -inf
+        top1[row] = none ? 0 : bi;
+        if (score != nullptr) score[row] = none ? v[0] : bv;
+    }
+}
+
 bool packed_shape(int K, int N, int S, int64_t C) {
     return K <= 32 && N <= kWave && C <= kPk;             // N <= 64: the survivors fit the largest tile
 }
@@ -756,6 +796,14 @@ int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_t
     }
     return launch_status(launch_kernel(vec4 ? decode_top1_kernel<4> : decode_top1_kernel<1>, grid, block, lds, stream,
                                        d_preds, d_mask, d_top1, d_score, d_status, K, N, S, C, Cv, sign_mode, qsplit, nodes));
+}
+
+int launch_argmax_rows(const float *d_values, int32_t *d_top1, float *d_score, int64_t rows, int64_t C,
+                       hipStream_t stream) {
+    const int64_t blocks = (rows + kArgmaxRows - 1) / kArgmaxRows;
+    if (blocks > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    return launch_status(launch_kernel(argmax_rows_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kArgmaxRows * kWave), 0,
+                                       stream, d_values, d_top1, d_score, rows, C));
 }
 
 int launch_wait_mask(const float *d_arrival, uint8_t *d_mask, int32_t *d_count, int64_t G, int N, int wait_for,

@@ -399,6 +399,25 @@ int run_encode_k(const float *d_queries, float *d_coded, int64_t G, int N, int64
 
 }  // namespace
 
+// Rows Q .. Q + fill - 1 of a [rows][D] query buffer become copies of row Q - 1 (a stream whose length is not a
+// multiple of K: the last group is completed by repeating its last query).  One float per thread.
+__global__ void pad_last_group_kernel(float *__restrict__ queries, int64_t Q, int64_t D, int64_t fill) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= fill * D) return;
+    const int64_t d = i % D;
+    queries[Q * D + i] = queries[(Q - 1) * D + d];
+}
+
+int launch_pad_last_group(float *d_queries, int64_t Q, int K, int64_t D, hipStream_t stream) {
+    const int64_t fill = (K - Q % K) % K;
+    if (fill == 0 || D == 0) return APPROXIFER_OK;
+    const int threads = 256;
+    const int64_t blocks = (fill * D + threads - 1) / threads;
+    if (blocks > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    return launch_status(launch_kernel(pad_last_group_kernel, dim3(static_cast<unsigned>(blocks)), dim3(threads), 0, stream,
+                                       d_queries, Q, D, fill));
+}
+
 #define APPROXIFER_K_CASE(k) \
     case k: return run_encode_k<k>(d_queries, d_coded, G, N, D, nodes, stream);
 #define APPROXIFER_K_CASE8(b)                                                                        \

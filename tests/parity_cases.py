@@ -220,3 +220,27 @@ def assert_rounding_ties(Y, mask, beta, K, A, adv_gpu, adv_ref, locator=orc.LOCA
                 assert counts[v] - counts[w] <= 2 * len(ties), ("vote gap beyond the tied classes", g, int(v), int(w),
                                                                 counts.tolist(), ties)
     return differing
+
+
+# --------------------------------------------------------------------------------------
+# Algorithm 3: how far two float64 solvers of one class's fit can be apart in P(alpha_j) / Q(alpha_j)
+# --------------------------------------------------------------------------------------
+def rational_tolerance(x, y, K, A, alpha):
+    """Per query j, the first-order bound on |r_1(alpha_j) - r_2(alpha_j)| for two backward-stable float64
+    least-squares solutions z = (P, Q) of H z = y:
+        |dz| <= 100 u kappa (1 + kappa |res| / (smax |z|)) |z|         (the factor 100 covers the solvers' constants),
+        |d(P/Q)(alpha_j)| <= sqrt(M) |dz| (1 + |r(alpha_j)|) / |Q(alpha_j)|      (nodes in [-1, 1]).
+    The 1e-5 bar of the other decoders is the floor; the bound exceeds it only where the fit itself is
+    ill-conditioned, which is the fragility Appendix A ends on."""
+    M = K + A
+    H, rhs = orc.locator_system(x, y, K, A)
+    z = np.linalg.lstsq(H, rhs, rcond=None)[0]
+    sv = np.linalg.svd(H, compute_uv=False)
+    kappa = sv[0] / sv[-1]
+    res = np.linalg.norm(H @ z - rhs)
+    dz = 100.0 * 2.0 ** -52 * kappa * (1.0 + kappa * res / (sv[0] * np.linalg.norm(z))) * np.linalg.norm(z)
+    a = np.asarray(alpha, dtype=np.float64)
+    Q = 1.0 + sum(z[M - 1 + k] * a ** k for k in range(1, M))
+    r = sum(z[k] * a ** k for k in range(M)) / Q
+    return np.sqrt(M) * dz * (1.0 + np.abs(r)) / np.abs(Q)
+

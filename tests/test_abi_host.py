@@ -153,6 +153,18 @@ def test_static_entry_point_refuses_shapes_beyond_its_workspace(lib):
     assert st(None, None, None, None, None, 0, 8, 24, 4, 2, 3, _dp(a8), _dp(b24), 0, None) == 0
 
 
+def test_grouping_host_side(lib):
+    gc = lib.approxifer_group_count
+    assert [gc(q, 4) for q in (0, 1, 4, 5, 8, 9)] == [0, 1, 1, 2, 2, 3]
+    assert gc(-1, 4) == -1 and gc(5, 0) == -1
+    pad = lib.approxifer_pad_last_group
+    fake = ctypes.c_void_p(256)          # never dereferenced below
+    assert pad(fake, -1, 4, 8, None) == -2 and pad(fake, 5, 0, 8, None) == -2 and pad(fake, 5, 4, -1, None) == -2
+    assert pad(fake, 5, 65, 8, None) == -3
+    assert pad(None, 5, 4, 8, None) == -1
+    assert pad(None, 8, 4, 8, None) == 0 and pad(None, 0, 4, 8, None) == 0 and pad(None, 5, 4, 0, None) == 0
+
+
 def test_binding_raises_typed_error(lib):
     with pytest.raises(binding.ApproxiferError) as e:
         binding.approxifer_chebyshev_nodes(0, 5)

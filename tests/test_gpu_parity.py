@@ -10,7 +10,8 @@ import pytest
 from oracle import approxifer_oracle as orc
 from paper_2109_09868_amd import synthetic as syn
 from parity_cases import (TOL, ILL_POSED_FUZZ_ALL, ILL_POSED_FUZZ_BYZANTINE, ILL_POSED_RAGGED, assert_rounding_ties,
-                          fuzz_all_cases, fuzz_byzantine_cases, group_err, ragged_decode_case, well_posed)
+                          fuzz_all_cases, fuzz_byzantine_cases, group_err, ragged_decode_case, rational_tolerance,
+                          well_posed)
 
 pytestmark = pytest.mark.gpu
 
@@ -969,6 +970,76 @@ def test_homogeneous_locator_bad_and_ragged_masks(gpu):
     assert np.all(out[bad] == -3.0) and np.all(adv[bad] == -7)
     assert np.array_equal(adv[~bad], adv_ref[~bad]) and np.array_equal(adv[~bad], adv_true[~bad])
     assert group_err(out[~bad], ref[~bad]).max() <= TOL
+
+
+# --------------------------------------------------------------------------------------
+# Algorithm 3 (Appendix A): the decoder by rational reconstruction, P(alpha_j) / Q(alpha_j)
+# --------------------------------------------------------------------------------------
+def _rational_case(seed, K, A, S, N, C, G, ragged=False):
+    rng = np.random.default_rng(seed)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    X = rng.uniform(0, 1, (G, K, 48))
+    clean = (orc.encode(X, alpha, beta) @ (rng.standard_normal((48, C)) / 7)).astype(np.float32)
+    mask = np.zeros((G, N), np.uint8)
+    Y = clean.copy()
+    for g in range(G):
+        cnt = int(rng.integers(2 * (K + A), N + 1)) if ragged else N - S
+        avail = np.sort(rng.permutation(N)[:cnt])
+        mask[g, avail] = 1
+        bad = rng.permutation(avail)[:A]
+        Y[g, bad] += (10 * (clean.std() + 1e-3) * rng.standard_normal((A, C))).astype(np.float32)
+    Y[mask == 0] = np.nan                                   # rows of missing workers must never be read
+    return alpha, beta, Y, mask
+
+
+@pytest.mark.parametrize("K,A,S,N,C,G", [(1, 1, 0, 8, 2, 8), (2, 1, 0, 6, 3, 16), (3, 1, 1, 9, 6, 40), (2, 2, 2, 12, 70, 9),
+                                         (4, 1, 3, 13, 17, 8), (3, 1, 0, 64, 5, 3), (2, 1, 0, 20, 300, 2)])
+def test_decode_rational_well_conditioned_shapes(gpu, K, A, S, N, C, G):
+    # small K + A: the fit is well conditioned even on float32 data, and the plain 1e-5 bar holds for every group
+    torch, binding, dev = gpu
+    alpha, beta, Y, mask = _rational_case(K * 10 + A + N, K, A, S, N, C, G)
+    out, st = binding.approxifer_decode_rational(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev), alpha, beta, S, A)
+    ref, st_ref = orc.decode_rational(Y, mask, alpha, beta, S, A)
+    assert np.array_equal(st.cpu().numpy(), st_ref) and np.all(st_ref == 0)
+    assert group_err(out.cpu().numpy(), ref).max() <= TOL
+
+
+def test_decode_rational_ragged_and_bad_masks(gpu):
+    torch, binding, dev = gpu
+    K, A, N, C, G = 3, 1, 14, 9, 40
+    alpha, beta, Y, mask = _rational_case(5, K, A, 0, N, C, G, ragged=True)
+    mask[4] = 0
+    mask[4, :2 * (K + A) - 1] = 1                            # one available worker too few
+    Y[4] = 1.0
+    out = torch.full((G, K, C), -3.0, dtype=torch.float32, device=dev)
+    out, st = binding.approxifer_decode_rational(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev), alpha, beta,
+                                                 binding.S_FROM_MASK, A, out=out)
+    ref, st_ref = orc.decode_rational(np.nan_to_num(Y), mask, alpha, beta, None, A)
+    o, s = out.cpu().numpy(), st.cpu().numpy()
+    assert np.array_equal(s, st_ref) and s[4] == 1 and s.sum() == 1
+    assert np.all(o[4] == -3.0) and np.all(np.isfinite(o))
+    good = s == 0
+    assert group_err(o[good], ref[good]).max() <= TOL
+
+
+@pytest.mark.parametrize("K,A,S,N,C,G", [(8, 2, 4, 24, 10, 64), (12, 2, 0, 28, 10, 16), (6, 2, 0, 40, 4, 8)])
+def test_decode_rational_at_the_paper_sizes_within_the_conditioning_bound(gpu, K, A, S, N, C, G):
+    # K + A = 10 .. 14 on float32 data: the fit's condition number is 1e8 and more, and this decoder is as fragile as
+    # Appendix A says.  Every element must stay within the first-order bound of its own class's fit
+    # (rational_tolerance), never less than the 1e-5 bar; and the typical group meets the plain bar.
+    torch, binding, dev = gpu
+    alpha, beta, Y, mask = _rational_case(K + A, K, A, S, N, C, G)
+    out, st = binding.approxifer_decode_rational(torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev), alpha, beta, S, A)
+    ref, st_ref = orc.decode_rational(Y, mask, alpha, beta, S, A)
+    o = out.cpu().numpy().astype(np.float64)
+    assert np.array_equal(st.cpu().numpy(), st_ref) and np.all(st_ref == 0)
+    for g in range(G):
+        avail = np.nonzero(mask[g])[0]
+        scale = np.abs(ref[g]).max()
+        for c in range(C):
+            tol = np.maximum(rational_tolerance(beta[avail], Y[g, avail, c].astype(np.float64), K, A, alpha), TOL * scale)
+            assert np.all(np.abs(o[g, :, c] - ref[g, :, c]) <= tol), (g, c)
+    assert np.median(group_err(o, ref)) <= TOL
 
 
 # --------------------------------------------------------------------------------------

@@ -337,3 +337,26 @@ def test_wait_mask_then_decode_uses_the_fastest_workers():
     ref = orc.decode_weights(alpha, beta, fastest, 1) @ Y[0, fastest]
     assert st[0] == 0 and np.allclose(out[0], ref, rtol=1e-14, atol=0)
 
+
+def test_group_queries_is_a_view_of_the_stream_with_the_last_query_repeated():
+    rng = np.random.default_rng(2)
+    stream = rng.standard_normal((12, 5))
+    assert np.array_equal(orc.group_queries(stream, 4), stream.reshape(3, 4, 5))      # K divides Q: the stream itself
+    assert np.array_equal(orc.group_queries(stream, 1), stream[:, None, :])
+    g = orc.group_queries(stream[:7], 3)                                               # 7 = 2 * 3 + 1
+    assert g.shape == (3, 3, 5)
+    assert np.array_equal(g.reshape(9, 5)[:7], stream[:7])                             # row q is query q
+    assert np.array_equal(g[2], np.broadcast_to(stream[6], (3, 5)))
+    g = orc.group_queries(stream[:8], 3)
+    assert np.array_equal(g[2, 0], stream[6]) and np.array_equal(g[2, 1], stream[7]) and np.array_equal(g[2, 2], stream[7])
+    assert orc.group_queries(stream[:0], 3).shape == (0, 3, 5)
+    # a last group of one real query is replication: every worker gets that query (constants reproduce),
+    # and any survivor set decodes it back
+    K, W = 3, 5
+    alpha, beta = orc.chebyshev_nodes(K, W)
+    coded = orc.encode(orc.group_queries(stream[:7], K), alpha, beta)
+    assert np.allclose(coded[2], np.broadcast_to(stream[6], (W, 5)), rtol=0, atol=1e-14)
+    mask = np.array([[1, 0, 1, 1, 0]] * 3, np.uint8)
+    out, st = orc.decode(coded, mask, alpha, beta, 2, 1)
+    assert np.all(st == 0) and np.allclose(out[2], np.broadcast_to(stream[6], (K, 5)), rtol=0, atol=1e-13)
+

@@ -401,3 +401,35 @@ def test_algorithm3_is_exact_in_float64_and_fragile_on_float32_data():
     assert np.median(fragile) < 1e-4 and fragile.max() > 1e-2 and fragile.max() > 1e3 * np.median(fragile)
     assert np.allclose(berrut32, berrut64, rtol=1e-3, atol=1e-6) and berrut32.max() < 1.0
 
+
+def test_decode_rational_returns_the_hosted_function_on_exactly_rational_data():
+    # Theorem 2: with a linear model and at most A lying workers P / Q is f o u itself, so reading it at the query
+    # nodes returns f(X_j); float64 data, per-group masks, a refused group
+    K, A, N, C, G = 3, 1, 12, 5, 6
+    rng = np.random.default_rng(31)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    X = rng.uniform(0, 1, (G, K, 16))
+    Mf = rng.standard_normal((16, C))
+    truth = X @ Mf
+    Y = orc.encode(X, alpha, beta) @ Mf
+    mask = np.zeros((G, N), np.uint8)
+    for g in range(G):
+        cnt = 2 * (K + A) - 1 if g == 2 else int(rng.integers(2 * (K + A), N + 1))
+        avail = np.sort(rng.permutation(N)[:cnt])
+        mask[g, avail] = 1
+        Y[g, rng.permutation(avail)[:A]] += 5.0 * rng.standard_normal((A, C))
+    out, st = orc.decode_rational(Y, mask, alpha, beta, None, A)
+    assert list(st) == [0, 0, 1, 0, 0, 0] and np.all(out[2] == 0.0)
+    good = st == 0
+    assert np.max(np.abs(out[good] - truth[good])) < 1e-8 * np.abs(truth).max()
+    # fixed straggler count: a group with another count is refused
+    out2, st2 = orc.decode_rational(Y, mask, alpha, beta, N - int(mask[0].sum()), A)
+    assert st2[0] == 0 and np.array_equal(out2[0], out[0])
+    assert np.all(st2[mask.sum(axis=1) != mask[0].sum()] == 1)
+    # K = 1: replication, every honest worker returns f(X_0) and P / Q is that constant
+    alpha1, beta1 = orc.chebyshev_nodes(1, 6)
+    Y1 = np.full((1, 6, 2), 3.25)
+    Y1[0, 4] = -7.0
+    out1, _ = orc.decode_rational(Y1, np.ones((1, 6), np.uint8), alpha1, beta1, 0, 1)
+    assert np.max(np.abs(out1 - 3.25)) < 1e-10
+

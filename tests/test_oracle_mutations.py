@@ -227,6 +227,26 @@ def _top1_last_on_ties(Y, mask, alpha, beta, S, sign_mode=0):
     return top1, np.max(out, axis=2), status
 
 
+def _reconstruction_inverted(x, y, K, A, z):
+    return 1.0 / _ORIG["rational_reconstruction"](x, y, K, A, z)
+
+
+def _reconstruction_without_q0(x, y, K, A, z):
+    # Q read without its constant term
+    M = K + A
+    Amat, rhs = orc.locator_system(x, y, K, A)
+    sol = np.linalg.lstsq(Amat, rhs, rcond=None)[0]
+    z = np.asarray(z, dtype=np.float64)
+    num = sum(sol[k] * z ** k for k in range(M))
+    den = sum(sol[M - 1 + k] * z ** k for k in range(1, M))
+    return num / den
+
+
+def _decode_rational_at_worker_nodes(Y, mask, alpha, beta, S, A):
+    # P / Q read at the first K worker nodes instead of the query nodes
+    return _ORIG["decode_rational"](Y, mask, np.asarray(beta)[: np.asarray(alpha).size] * 0.999, beta, S, A)
+
+
 MUTATIONS = {
     "worker nodes divided by the worker count (the paper's N is W-1)": ("chebyshev_nodes", _nodes_paper_n_confused),
     "first and second kind nodes swapped": ("chebyshev_nodes", _nodes_kinds_swapped),
@@ -253,6 +273,9 @@ MUTATIONS = {
     "wait rule keeps the slowest": ("wait_mask", _wait_for_the_slowest),
     "wait rule counts workers that never answer": ("wait_mask", _wait_counts_absentees),
     "top-1 takes the last class on ties": ("decode_top1", _top1_last_on_ties),
+    "Algorithm 3 returns Q / P": ("rational_reconstruction", _reconstruction_inverted),
+    "Algorithm 3 drops Q_0": ("rational_reconstruction", _reconstruction_without_q0),
+    "Algorithm 3 read at the worker nodes": ("decode_rational", _decode_rational_at_worker_nodes),
 }
 _ORIG = {name: getattr(orc, name) for name, _ in MUTATIONS.values()}
 
