@@ -259,9 +259,9 @@ def other_workloads(torch, binding, syn, orc_nodes, dev, sign_mode):
     alpha, beta = orc_nodes(w.K, w.W)
     q = torch.from_numpy(syn.queries(w, threads=16)).to(dev)
     coded = torch.empty((w.G, w.W, w.D), dtype=torch.float32, device=dev)
-    t = time_launches(torch, lambda: binding.approxifer_encode(q, alpha, beta, coded=coded), 20, flush=flush)
+    t = time_launches(torch, lambda: binding.approxifer_encode(q, alpha, beta, coded=coded), 20)       # 0.8-1 GB a launch: nothing stays cached
     res["mnist_k8_encode"] = dict(t, coded_queries_per_s=w.G * w.W / (t["ms"] * 1e-3),
-                                  hbm_gbs=encode_bytes(w) / (t["ms"] * 1e6), note=COLD)
+                                  hbm_gbs=encode_bytes(w) / (t["ms"] * 1e6))
     Mm = torch.from_numpy(syn.model_params(w)["M"]).to(dev)
     preds = torch.softmax(coded.double().reshape(-1, w.D) @ Mm, dim=1).float().reshape(w.G, w.W, w.C).contiguous()
     mask = torch.from_numpy(syn.masks(w)).to(dev)
@@ -310,9 +310,9 @@ def other_workloads(torch, binding, syn, orc_nodes, dev, sign_mode):
     alpha, beta = orc_nodes(w.K, w.W)
     q = torch.from_numpy(syn.queries(w, threads=16)).to(dev)
     coded = torch.empty((w.G, w.W, w.D), dtype=torch.float32, device=dev)
-    t = time_launches(torch, lambda: binding.approxifer_encode(q, alpha, beta, coded=coded), 20, flush=flush)
+    t = time_launches(torch, lambda: binding.approxifer_encode(q, alpha, beta, coded=coded), 20)       # 0.8-1 GB a launch: nothing stays cached
     res["byzantine_encode"] = dict(t, coded_queries_per_s=w.G * w.W / (t["ms"] * 1e-3),
-                                   hbm_gbs=encode_bytes(w) / (t["ms"] * 1e6), note=COLD)
+                                   hbm_gbs=encode_bytes(w) / (t["ms"] * 1e6))
     M = torch.from_numpy(syn.model_params(w)["M"]).to(dev)
     clean = (coded.double().reshape(-1, w.D) @ M).float().reshape(w.G, w.W, w.C).cpu().numpy()
     mask_h = syn.masks(w)
@@ -345,9 +345,9 @@ def other_workloads(torch, binding, syn, orc_nodes, dev, sign_mode):
     alpha, beta = orc_nodes(w.K, w.W)
     q = torch.from_numpy(syn.queries(w, threads=16)).to(dev)
     coded = torch.empty((w.G, w.W, w.D), dtype=torch.float32, device=dev)
-    t = time_launches(torch, lambda: binding.approxifer_encode(q, alpha, beta, coded=coded), 20, flush=flush)
+    t = time_launches(torch, lambda: binding.approxifer_encode(q, alpha, beta, coded=coded), 20)       # 0.8-1 GB a launch: nothing stays cached
     res["mnist_byz_k12_encode"] = dict(t, coded_queries_per_s=w.G * w.W / (t["ms"] * 1e-3),
-                                       hbm_gbs=encode_bytes(w) / (t["ms"] * 1e6), note=COLD)
+                                       hbm_gbs=encode_bytes(w) / (t["ms"] * 1e6))
     M = torch.from_numpy(syn.model_params(w)["M"]).to(dev)
     clean = (coded.double().reshape(-1, w.D) @ M).float().reshape(w.G, w.W, w.C).cpu().numpy()
     mask_h = syn.masks(w)

@@ -151,20 +151,24 @@ int approxifer_decode(const float *d_preds, const uint8_t *d_mask, float *d_out,
  *
  *   d_adv     [G][A] int32, device, written: located workers in ascending order
  *   d_workspace, workspace_bytes
- *             device scratch memory owned by the caller, 4-byte aligned, or NULL / 0.  The vote of
- *             Algorithm 2's return step is the one place where the classes of a group meet.  With few
- *             groups and many classes the library spreads a group's classes over several workgroups,
- *             which pool their per-class picks in the workspace (N vote counters and an arrival counter
- *             per group, cleared by the call itself; contents on entry and exit are meaningless).
- *             approxifer_workspace_bytes() gives the size that lets it do so.  With NULL, or fewer
- *             bytes, the call is just as correct and d_out, d_adv, d_status hold the same values: every
- *             group then stays with one workgroup, which is slower only for few groups with hundreds
- *             of classes or more.  Nothing but the workspace is ever used as scratch: output rows are
- *             written once, with their final values.  The workspace must not be shared with a call
- *             that may run concurrently.
+ *             device scratch memory owned by the caller, 8-byte aligned, or NULL / 0; contents on entry and exit
+ *             are meaningless, the call initialises what it uses.  Two things live there.
+ *             (1) The vote of Algorithm 2's return step is the one place where the classes of a group meet.  With
+ *             few groups and many classes the library spreads a group's classes over several workgroups, which
+ *             pool their per-class picks in N vote counters and an arrival counter per group.
+ *             (2) Without stragglers (S = 0, the setting of the paper's Byzantine experiments, or
+ *             APPROXIFER_S_FROM_MASK) every group whose mask is full fits the same node set: the part of
+ *             Algorithm 2's system that does not depend on the predictions is then factorised once per call
+ *             instead of once per group, and kept in the workspace.
+ *             approxifer_workspace_bytes() gives the size that allows both.  With NULL, fewer bytes or a
+ *             misaligned pointer the call uses what fits and is just as correct: d_out, d_adv and d_status hold
+ *             the same bits; only time is lost (every group stays with one workgroup and repeats the
+ *             factorisation).  Nothing but the workspace is ever used as scratch: output rows are written
+ *             once, with their final values.  The workspace must not be shared with a call that may run
+ *             concurrently.
  *   other arguments as approxifer_decode(); groups with a bad mask leave d_out and
  *   d_adv rows untouched.
- * On APPROXIFER_ERR_LAUNCH the kernel that clears the workspace may have been enqueued; no output
+ * On APPROXIFER_ERR_LAUNCH the kernels that prepare the workspace may have been enqueued; no output
  * is touched.
  * Requires A >= 1, N - S >= 2 (K + A) (Section 3, eq. (3), the decoding condition) and
  * N - S <= APPROXIFER_MAX_AVAIL_BYZ.  With S = APPROXIFER_S_FROM_MASK a group is decoded when its
@@ -183,9 +187,9 @@ int approxifer_decode_byzantine(const float *d_preds, const uint8_t *d_mask, flo
  * Size in bytes of the workspace with which approxifer_decode_byzantine() and
  * approxifer_decode_byzantine_homogeneous() run fastest for this shape (Algorithm 2, return step: the
  * per-class picks of a group are pooled there when its classes are spread over several workgroups).
- * 0 when the shape needs none -- enough groups to fill the GPU with one workgroup each, or few
- * classes -- and for shapes the decoders refuse.  Host arithmetic only; at most
- * 4 (N + 1) bytes per group, rounded up to a multiple of 256.
+ * 0 when the shape needs none -- a fixed number S > 0 of stragglers with enough groups to fill the GPU with one
+ * workgroup each, or few classes -- and for shapes the decoders refuse.  Host arithmetic only; at most
+ * 4 (N + 1) bytes per group plus 13 KiB, each part rounded up to a multiple of 256.
  */
 size_t approxifer_workspace_bytes(int64_t G, int K, int N, int S, int A, int64_t C);
 
@@ -198,7 +202,8 @@ size_t approxifer_workspace_bytes(int64_t G, int K, int N, int S, int A, int64_t
  * are still the caller's.
  *   - A shape for which approxifer_workspace_bytes() exceeds APPROXIFER_STATIC_WORKSPACE_BYTES is refused
  *     with APPROXIFER_ERR_WORKSPACE_LIMIT before anything is enqueued (4 (N + 1) G bytes are needed when
- *     few groups bring hundreds of classes or more; shapes that need no workspace are never refused).
+ *     few groups bring hundreds of classes or more, up to 13 KiB when no stragglers are asked for; shapes
+ *     that need no workspace are never refused).
  *   - The device of `stream` must be the current device.  The first call on a device looks up the address
  *     of that device's copy of the array (no allocation, no synchronisation).
  *   - All calls on one GPU share that GPU's array.  Each call clears the part it uses with a kernel of

@@ -58,34 +58,35 @@ __device__ __forceinline__ void contract_group(const float *__restrict__ pg, flo
 
 // The A most voted workers (equal counts: smaller index first) go to adv_g in ascending order; F = the
 // available workers without them (ascending), Fpos = their positions in `avail`.  Called by the whole
-// workgroup after every vote has been added and a barrier; ends with a barrier.  n <= 64.
+// workgroup after every vote has been added and a barrier; ends with a barrier.  n <= 64, N <= 128.
+// One wave does it in registers: lane i ranks workers i and i + 64 by counting against the vote counts
+// (broadcast reads of LDS), ballots turn ranks into the ascending lists.
 __device__ __forceinline__ void select_adversaries(int32_t *__restrict__ adv_g, const int *avail, int n, int N, int A,
-                                                   const int *votes, int *sel, int *F, int *Fpos) {
-    for (int i = threadIdx.x; i < N; i += blockDim.x) {
-        const int mine = votes[i];
-        int rank = 0;
+                                                   const int *votes, int *F, int *Fpos) {
+    if (wave_id() == 0) {
+        const int lane = lane_id();
+        const int mine0 = lane < N ? votes[lane] : -1;
+        const int mine1 = lane + kWave < N ? votes[lane + kWave] : -1;
+        int rank0 = 0, rank1 = 0;
 #pragma unroll 8
         for (int o = 0; o < N; ++o) {
             const int v = votes[o];
-            rank += (v > mine || (v == mine && o < i)) ? 1 : 0;
+            rank0 += (v > mine0 || (v == mine0 && o < lane)) ? 1 : 0;
+            rank1 += (v > mine1 || (v == mine1 && o < lane + kWave)) ? 1 : 0;
         }
-        sel[i] = rank < A ? 1 : 0;
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < N; i += blockDim.x) {
-        if (sel[i]) {
-            int pos = 0;
-            for (int o = 0; o < i; ++o) pos += sel[o];
-            adv_g[pos] = i;
-        }
-    }
-    if (wave_id() == 0) {
-        const int lane = lane_id();
-        const bool keep = (lane < n) && !sel[avail[lane]];
-        const unsigned long long m = __ballot(keep);
+        const bool s0 = lane < N && rank0 < A;
+        const bool s1 = lane + kWave < N && rank1 < A;
+        const unsigned long long m0 = __ballot(s0), m1 = __ballot(s1);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        if (s0) adv_g[__popcll(m0 & below)] = lane;
+        if (s1) adv_g[__popcll(m0) + __popcll(m1 & below)] = lane + kWave;
+        const int w = lane < n ? avail[lane] : 0;
+        const bool dropped = ((w < kWave ? m0 >> w : m1 >> (w - kWave)) & 1ull) != 0ull;
+        const bool keep = lane < n && !dropped;
+        const unsigned long long mk = __ballot(keep);
         if (keep) {
-            const int pos = __popcll(m & ((1ull << lane) - 1ull));
-            F[pos] = avail[lane];
+            const int pos = __popcll(mk & below);
+            F[pos] = w;
             Fpos[pos] = lane;
         }
     }
@@ -122,9 +123,9 @@ __device__ __forceinline__ bool pool_votes_last_arrival(int *gvotes, int *votes,
 __device__ __forceinline__ void finish_group(const float *__restrict__ pg, float *__restrict__ og,
                                              int32_t *__restrict__ adv_g, const int *avail, int n, int N, int A, int K,
                                              int KP, int64_t C, int64_t Cv, bool vec4, int sign_mode,
-                                             const double *alpha_s, const double *beta_s, const int *votes, int *sel,
+                                             const double *alpha_s, const double *beta_s, const int *votes,
                                              int *F, int *Fpos, double *WdT) {
-    select_adversaries(adv_g, avail, n, N, A, votes, sel, F, Fpos);
+    select_adversaries(adv_g, avail, n, N, A, votes, F, Fpos);
     const int nF = n - A;
     decoder_weights(alpha_s, beta_s, F, nF, K, KP, sign_mode, WdT);
     __syncthreads();
@@ -200,9 +201,12 @@ struct Reflector {
 __device__ __forceinline__ Reflector reflector(double sigma, double d, double xkk, double akj) {
     Reflector h;
     h.degenerate = !(sigma > 0.0);
-    const double nrm = sqrt_normal(sigma);
+    // a zero (or NaN) column: the caller applies no reflection; alpha and f stay finite so that a factor 0 times
+    // them is 0 and not NaN (an exactly singular system must keep its exact zero on the diagonal)
+    const double s = h.degenerate ? 1.0 : sigma;
+    const double nrm = sqrt_normal(s);
     h.alpha = (xkk >= 0.0) ? -nrm : nrm;
-    const double scale = rcp_normal(fma(-h.alpha, xkk, sigma));   // 2 / (v^T v) = 1 / (sigma + |x_k| ||x||)
+    const double scale = rcp_normal(fma(-h.alpha, xkk, s));   // 2 / (v^T v) = 1 / (sigma + |x_k| ||x||)
     h.f = scale * fma(-h.alpha, akj, d);
     return h;
 }
@@ -222,7 +226,8 @@ struct SharedQrSteps {
             // no branch: columns up to the pivot (and every column of a degenerate step) take the factor 0, so the
             // pivot values read for the dot products serve the update as well
             const double nf = (!h.degenerate && lane > K0) ? -h.f : 0.0;
-            col[K0] = fma(nf, xkk - h.alpha, col[K0]);
+            const double ckk = fma(nf, xkk - h.alpha, col[K0]);
+            col[K0] = (!h.degenerate && lane == K0) ? h.alpha : ckk;      // R[k][k] in the pivot lane
 #pragma unroll
             for (int r = K0 + 1; r < NB; ++r) col[r] = fma(nf, read_lane(col[r], K0), col[r]);
             SharedQrSteps<K0 + 1, NB>::run(col, lane, M);
@@ -235,8 +240,12 @@ struct SharedQrSteps<kProjMaxM, NB> {
 };
 
 // Pw[r][e] = x_r^e (LDS), n rows, M <= 16 columns.  Writes Ush[i][r] = U[i][r], i < RM, row stride ush_stride(NB).
-template <int NB, int RM>
-__device__ __forceinline__ void shared_complement_basis(const double *Pw, int n, int M, double *Ush) {
+// WITH_RANGE (Algorithm 1's locator needs the whole factorisation): also Q1sh[i][r] = row i < M of Q^T (16 rows of
+// the same stride, rows from M on left as they are) and Rv[i][j] = R[i][j], the M x M triangular factor of V (row
+// stride 16, zero below the diagonal).
+template <int NB, int RM, bool WITH_RANGE = false>
+__device__ __forceinline__ void shared_complement_basis(const double *Pw, int n, int M, double *Ush, double *Q1sh = nullptr,
+                                                        double *Rv = nullptr) {
     const int lane = lane_id();
     double col[NB];
     const bool vandermonde = lane < M;                // lanes 0..M-1: V; lanes M..M+n-1: the identity
@@ -254,6 +263,16 @@ __device__ __forceinline__ void shared_complement_basis(const double *Pw, int n,
             const int i = row - M;
             if (i >= 0 && i < RM) Ush[i * ush_stride(NB) + r_out] = col[row];
         }
+        if (WITH_RANGE) {
+#pragma unroll
+            for (int row = 0; row < kProjMaxM && row < NB; ++row)
+                if (row < M) Q1sh[row * ush_stride(NB) + r_out] = col[row];
+        }
+    }
+    if (WITH_RANGE && lane < M) {
+#pragma unroll
+        for (int row = 0; row < kProjMaxM && row < NB; ++row)
+            if (row < M) Rv[row * kProjMaxM + lane] = row <= lane ? col[row] : 0.0;
     }
 }
 
@@ -423,32 +442,147 @@ __device__ __forceinline__ void locate_classes_proj(const float *Ysh, int CW, in
     }
 }
 
-// dynamic LDS (doubles): Ush[ush_rows(RM)*ush_stride(NB)] | Pw[NB*16] | xs[NB] | WdT[(n_cap-A)*KP] | alpha_s[K] | beta_s[N]
-//               then float Ysh[NB*CW], then ints: avail[N] | F[N] | Fpos[N] | votes[N] | sel[N] | n
+__device__ __forceinline__ void homogeneous_q(double *mat, int LD, double *coef, double *key, int W2, int M, int j,
+                                              bool live);
+
+// Algorithm 1 (the homogeneous fit, Q_0 free) for the four classes c_rel..c_rel+3 of the staged tile, by one wave, on
+// the shared factorisation V = Q [R_V; 0] of the group.  With H_c = [V | diag(y_c) V] (the sign of the second block
+// only flips the sign of Q),
+//     Q^T H_c = [ R_V   Q1^T diag(y_c) V ]      Q1^T = rows 0..M-1 of Q^T,
+//               [  0     U  diag(y_c) V ]      U    = rows M..n-1,
+// so the 2M x 2M triangular factor of H_c is [[R_V, B1], [0, R2]] with B1 = Q1^T diag(y_c) V (M x M) and
+// R2 the triangular factor of B2 = U diag(y_c) V ((n-M) x M; n - M >= M by eq. (3)).  B1 and B2 come from the
+// float64 matrix cores exactly as the projected system of Algorithm 2 does (Q1 sits in the 16 rows that follow U in
+// LDS), R2 from the same register Householder QR, run over all M columns.  The smallest right singular vector of
+// the assembled factor is then found as in the LDS kernel (homogeneous_q), 64 / 2M classes at a time in this wave's
+// scratch: per class  mat[2M][2M+1] | coef[M] | key[n].
 template <int NB, int RM>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 && NB <= 28 ? 3 : 2))) void decode_byzantine_proj_kernel(
+__device__ __forceinline__ void locate_classes_hom_proj(const float *Ysh, int CW, int c_rel, int tile_classes,
+                                                        const int *avail, const double *xs, const double *Pw,
+                                                        const double *Ush, const double *Rv, int n, int M, int A,
+                                                        double *scratch, int *votes) {
+    typedef double v4d __attribute__((ext_vector_type(4)));
+    const int lane = lane_id();
+    const int j = lane % kClsLanes;
+    const int e = j < M ? j : 0;                          // column of this lane: y x^j; idle lanes hold zeros
+    const double sgn = j < M ? 1.0 : 0.0;
+    constexpr int kKSteps = NB / 4;
+    constexpr int kUBlocks = ush_rows(RM) / 4;
+    constexpr int kBlocks = kUBlocks + kProjMaxM / 4;     // then the 16 rows of Q1
+    double bop[kKSteps], yop[kKSteps];
+    {
+        const int k = lane / kClsLanes, cm = (lane % kClsLanes) & 3;
+#pragma unroll
+        for (int s = 0; s < kKSteps; ++s) {
+            const int r = 4 * s + k;
+            bop[s] = sgn * Pw[r * kPwStride + e];
+            yop[s] = static_cast<double>(Ysh[r * CW + c_rel + cm]);
+        }
+    }
+    double a[RM], b1[kProjMaxM];
+    {
+        const double *urow = Ush + ((lane % kClsLanes) >> 2) * ush_stride(NB) + lane / kClsLanes;
+        v4d acc[kBlocks];
+#pragma unroll
+        for (int b = 0; b < kBlocks; ++b) acc[b] = v4d{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int s = 0; s < kKSteps; ++s)
+#pragma unroll
+            for (int b = 0; b < kBlocks; ++b)
+                acc[b] = __builtin_amdgcn_mfma_f64_16x16x4f64(urow[4 * b * ush_stride(NB) + 4 * s] * yop[s], bop[s], acc[b],
+                                                              0, 0, 0);
+#pragma unroll
+        for (int b = 0; b < kUBlocks; ++b)
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (4 * b + t < RM) a[4 * b + t] = acc[b][t];
+#pragma unroll
+        for (int i = 0; i < kProjMaxM; ++i) b1[i] = acc[kUBlocks + i / 4][i % 4];
+    }
+
+    // R2: steps 0 .. min(M, RM - 1) - 1; when M == RM the last diagonal entry is the one row that is left
+    constexpr int kSteps = RM - 1 < kProjMaxM - 1 ? RM - 1 : kProjMaxM - 1;
+    ClassQrSteps<0, kSteps, RM>::run(a, j, M);
+
+    // ---- assemble the factor and find its smallest right singular vector, cpw classes at a time --------------------
+    const int W2 = 2 * M;
+    const int LD = W2 + 1;
+    const int per_class = W2 * LD + M + n;
+    const int cpw = kWave / W2;                           // >= 2: M <= 15
+    const int cl16 = lane / kClsLanes;                    // class slot of this lane in the register layout
+    const int clw = lane / W2, jw = lane - clw * W2;      // .. and in the layout of homogeneous_q (lane jw owns row jw)
+    for (int p0 = 0; p0 < kClsPerWave; p0 += cpw) {
+        if (cl16 >= p0 && cl16 < p0 + cpw && j < M) {
+            double *mat = scratch + (cl16 - p0) * per_class;
+#pragma unroll
+            for (int i = 0; i < kProjMaxM; ++i) {
+                if (i < M) {
+                    mat[i * LD + j] = Rv[i * kProjMaxM + j];                    // R_V (zero below its diagonal)
+                    mat[(M + i) * LD + j] = 0.0;
+                    mat[i * LD + M + j] = b1[i];                                // B1
+                    mat[(M + i) * LD + M + j] = (i < RM && i <= j) ? a[i < RM ? i : 0] : 0.0;   // R2
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        const bool live = clw < cpw && p0 + clw < kClsPerWave && c_rel + p0 + clw < tile_classes;
+        double *mat = scratch + (live ? clw : 0) * per_class;
+        double *coef = mat + W2 * LD;
+        double *key = coef + M;
+        homogeneous_q(mat, LD, coef, key, W2, M, jw, live);
+        if (live) {
+            for (int r = jw; r < n; r += W2) {            // a_r = Q(x_r), Q_k = coef[k]
+                const double x = xs[r];
+                double av = 0.0;
+                for (int t = M - 1; t >= 0; --t) av = fma(av, x, coef[t]);
+                key[r] = (av != av) ? __builtin_inf() : fabs(av);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (live) pick_and_vote(key, avail, n, A, jw, W2, votes);
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// Doubles of the shared factorisation as the kernel keeps it in LDS (and as full_basis_kernel writes it out):
+// Ush[ush_rows(RM)][ush_stride(NB)], and for Algorithm 1's locator also Q1sh[16][ush_stride(NB)] | Rv[16][16].
+template <int NB, int RM, bool HOMOG>
+constexpr int basis_doubles() {
+    return ush_rows(RM) * ush_stride(NB) + (HOMOG ? kProjMaxM * ush_stride(NB) + kProjMaxM * kProjMaxM : 0);
+}
+
+// HOMOG: Algorithm 1's fit as the per-class locator (locate_classes_hom_proj) instead of Algorithm 2's.
+// dynamic LDS (doubles): basis (see basis_doubles) | Pw[NB*16] | xs[NB] | WdT[(n_cap-A)*KP] | alpha_s[K] | beta_s[N]
+//               | HOMOG: scratch[nw][(64 / 2M) * (2M (2M+1) + M + n_cap)]
+//               then float Ysh[NB*CW], then ints: avail[N] | F[N] | Fpos[N] | votes[N] | n | flag
+template <int NB, int RM, bool HOMOG>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(!HOMOG && RM <= 16 && NB <= 28 ? 3 : 2))) void decode_byzantine_proj_kernel(
     const float *__restrict__ preds, const uint8_t *__restrict__ mask, float *__restrict__ out,
     int32_t *__restrict__ adv, int32_t *__restrict__ status, int K, int N, int S, int A, int64_t C, int64_t Cv,
-    int vec4, int sign_mode, int n_cap, int cw_log2, int splits, int32_t *__restrict__ workspace, const Nodes nodes) {
+    int vec4, int sign_mode, int n_cap, int cw_log2, int splits, int32_t *__restrict__ workspace,
+    const double *__restrict__ full_basis, const Nodes nodes) {
     extern __shared__ __align__(16) double lds_d[];
     const int KP = round_up4(K);
     const int M = K + A;
     const int nw = blockDim.x / kWave;
     const int CW = 1 << cw_log2;                          // classes per staged tile (16, 32 or 64)
     double *Ush = lds_d;
-    constexpr int kUshDoubles = ush_rows(RM) * ush_stride(NB);
+    constexpr int kUshDoubles = basis_doubles<NB, RM, HOMOG>();
+    double *Q1sh = Ush + ush_rows(RM) * ush_stride(NB);   // HOMOG only: the 16 rows after U, then R_V
+    double *Rv = Q1sh + kProjMaxM * ush_stride(NB);
     double *Pw = Ush + kUshDoubles;
     double *xs = Pw + NB * kPwStride;
     double *WdT = xs + NB;
     double *alpha_s = WdT + (n_cap - A) * KP;
     double *beta_s = alpha_s + K;
-    float *Ysh = reinterpret_cast<float *>(beta_s + N);
+    const int hom_wave_doubles = HOMOG ? (kWave / (2 * M)) * (2 * M * (2 * M + 1) + M + n_cap) : 0;
+    double *hom_scratch = beta_s + N;
+    float *Ysh = reinterpret_cast<float *>(hom_scratch + static_cast<size_t>(nw) * hom_wave_doubles);
     int *avail = reinterpret_cast<int *>(Ysh + NB * CW);
     int *F = avail + N;
     int *Fpos = F + N;
     int *votes = Fpos + N;
-    int *sel = votes + N;
-    int *n_sh = sel + N;
+    int *n_sh = votes + N;
 
     // splits > 1: `splits` workgroups share a group, workgroup `part` taking the class tiles part, part + splits, ..
     const int64_t g = blockIdx.x / splits;
@@ -459,7 +593,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
 
     stage_nodes(nodes, K, N, alpha_s, beta_s);
     for (int e = tid; e < (n_cap - A) * KP; e += blockDim.x) WdT[e] = 0.0;
-    for (int e = tid; e < kUshDoubles; e += blockDim.x) Ush[e] = 0.0;
     for (int e = tid; e < N; e += blockDim.x) votes[e] = 0;
     if (wv == 0) {
         const int cnt = survivors_from_mask(mask + g * N, N, avail);
@@ -470,6 +603,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
     const bool good = S < 0 ? (n >= 2 * M && n <= n_cap) : n == n_cap;
     if (tid == 0 && status != nullptr) status[g] = good ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
     if (!good) return;
+    // A group in which every worker answered has the node set of the whole call: its complement basis was
+    // factorised once, ahead of this launch (full_basis_kernel), and is only copied here.
+    const bool preloaded = full_basis != nullptr && n == N;
+    for (int e = tid; e < kUshDoubles; e += blockDim.x) Ush[e] = preloaded ? full_basis[e] : 0.0;
 
     // first class tile: the loads are issued now and land in LDS after the shared factorisation
     constexpr int kPrefetch = 8;
@@ -494,7 +631,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
         }
     }
     __syncthreads();
-    if (wv == 0) shared_complement_basis<NB, RM>(Pw, n, M, Ush);
+    if (wv == 0 && !preloaded) shared_complement_basis<NB, RM, HOMOG>(Pw, n, M, Ush, Q1sh, Rv);
 
     for (int64_t cb = cb_first; cb < C; cb += static_cast<int64_t>(splits) * CW) {   // class tiles of this part
         if (cb == cb_first) {
@@ -516,16 +653,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
         }
         __syncthreads();
         const int tile_classes = (C - cb < CW) ? static_cast<int>(C - cb) : CW;
-        for (int c_rel = wv * kClsPerWave; c_rel < tile_classes; c_rel += nw * kClsPerWave)
-            locate_classes_proj<NB, RM>(Ysh, CW, c_rel, c_rel + lane_id() / kClsLanes < tile_classes, avail, xs, Pw, Ush,
-                                        n, M, A, votes);
+        for (int c_rel = wv * kClsPerWave; c_rel < tile_classes; c_rel += nw * kClsPerWave) {
+            if (HOMOG)
+                locate_classes_hom_proj<NB, RM>(Ysh, CW, c_rel, tile_classes, avail, xs, Pw, Ush, Rv, n, M, A,
+                                                hom_scratch + static_cast<size_t>(wv) * hom_wave_doubles, votes);
+            else
+                locate_classes_proj<NB, RM>(Ysh, CW, c_rel, c_rel + lane_id() / kClsLanes < tile_classes, avail, xs, Pw,
+                                            Ush, n, M, A, votes);
+        }
     }
     __syncthreads();
 
     float *og = out + static_cast<size_t>(g) * K * C;
     if (splits > 1 && !pool_votes_last_arrival(workspace + g * (N + 1), votes, N, splits, n_sh + 1)) return;
     const bool staged = C <= CW;                          // the one tile holds every prediction of the group
-    select_adversaries(adv + g * A, avail, n, N, A, votes, sel, F, Fpos);
+    select_adversaries(adv + g * A, avail, n, N, A, votes, F, Fpos);
     const int nF = n - A;
     decoder_weights(alpha_s, beta_s, F, nF, K, KP, sign_mode, WdT);
     __syncthreads();
@@ -545,6 +687,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
     } else {
         contract_group<1>(pg, og, F, nF, K, KP, C, Cv, WdT);
     }
+}
+
+// The complement basis of the node set of ALL N workers, once per call, for the groups whose mask is full (the
+// paper's Byzantine experiments have no stragglers: every group then shares this one factorisation).  One wave;
+// writes Ush as the kernel above lays it out, ush_rows(RM) * ush_stride(NB) doubles, to `basis`.
+template <int NB, int RM, bool HOMOG>
+__global__ __launch_bounds__(kWave) void full_basis_kernel(double *__restrict__ basis, int N, int M, const Nodes nodes) {
+    constexpr int kUshDoubles = basis_doubles<NB, RM, HOMOG>();
+    __shared__ double Ush[kUshDoubles];
+    __shared__ double Pw[NB * kPwStride];
+    const int tid = threadIdx.x;
+    for (int e = tid; e < kUshDoubles; e += kWave) Ush[e] = 0.0;
+    for (int r = tid; r < NB; r += kWave) {
+        const double x = r < N ? nodes.beta[r] : 0.0;
+        double p = r < N ? 1.0 : 0.0;
+        for (int e = 0; e < kPwStride; ++e) {
+            Pw[r * kPwStride + e] = p;
+            p *= x;
+        }
+    }
+    __syncthreads();
+    shared_complement_basis<NB, RM, HOMOG>(Pw, N, M, Ush, Ush + ush_rows(RM) * ush_stride(NB),
+                                           Ush + (ush_rows(RM) + kProjMaxM) * ush_stride(NB));
+    __syncthreads();
+    for (int e = tid; e < kUshDoubles; e += kWave) basis[e] = Ush[e];
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -910,7 +1077,7 @@ __global__ void decode_rational_kernel(const float *__restrict__ preds, const ui
 
 // dynamic LDS: double scratch[nw][cpw * (n*LD + M + n)] (LD = 2M, 2M+1 for Algorithm 1) | double WdT[(n-A) * KP] | double xs[n]
 //              | double alpha_s[K] | double beta_s[N]
-//              | int avail[N] | int F[N] | int Fpos[N] | int votes[N] | int sel[N] | int n
+//              | int avail[N] | int F[N] | int Fpos[N] | int votes[N] | int n | int flag
 template <bool HOMOG>
 __global__ void decode_byzantine_general_kernel(const float *__restrict__ preds, const uint8_t *__restrict__ mask,
                                                 float *__restrict__ out, int32_t *__restrict__ adv,
@@ -933,8 +1100,7 @@ __global__ void decode_byzantine_general_kernel(const float *__restrict__ preds,
     int *F = avail + N;
     int *Fpos = F + N;
     int *votes = Fpos + N;
-    int *sel = votes + N;
-    int *n_sh = sel + N;
+    int *n_sh = votes + N;
 
     // splits > 1: `splits` workgroups share a group, see pool_votes_last_arrival
     const int64_t g = blockIdx.x / splits;
@@ -964,7 +1130,7 @@ __global__ void decode_byzantine_general_kernel(const float *__restrict__ preds,
     if (splits > 1 && !pool_votes_last_arrival(workspace + g * (N + 1), votes, N, splits, n_sh + 1)) return;
 
     finish_group(pg, out + static_cast<size_t>(g) * K * C, adv + g * A, avail, n, N, A, K, KP, C, Cv, vec4 != 0, sign_mode,
-                 alpha_s, beta_s, votes, sel, F, Fpos, WdT);
+                 alpha_s, beta_s, votes, F, Fpos, WdT);
 }
 
 // Before a launch in which several workgroups share a group: zero the workspace words through which they meet.
@@ -1021,7 +1187,7 @@ GeneralShape general_shape(int64_t G, int K, int N, int n, int A, int64_t C, boo
     int cpw = kWave / (2 * M);
     if (cpw < 1) cpw = 1;
     if (cpw > C) cpw = static_cast<int>(C);
-    const size_t fixed = sizeof(double) * (static_cast<size_t>(n - A) * KP + n + K + N) + sizeof(int) * (5 * static_cast<size_t>(N) + 2);
+    const size_t fixed = sizeof(double) * (static_cast<size_t>(n - A) * KP + n + K + N) + sizeof(int) * (4 * static_cast<size_t>(N) + 2);
     const size_t per_class = sizeof(double) * (static_cast<size_t>(n) * (homogeneous ? 2 * M + 1 : 2 * M) + M + n);
     const size_t budget = 64 * 1024;
     while (cpw > 1 && fixed + cpw * per_class > budget) --cpw;
@@ -1058,27 +1224,97 @@ int clear_workspace(int32_t *ws, int64_t G, int N, hipStream_t stream) {
                                        dim3(threads), 0, stream, ws, words));
 }
 
-template <int NB, int RM>
+// Register tiles <rows of [V | I], rows of the projected system> of the projected kernel, smallest first.
+struct ProjTile {
+    int nb, rm;
+};
+constexpr ProjTile kProjTiles[] = {
+    {20, 10},                 // n = 2M, the minimum of eq. (3), up to K + A = 10
+    {20, 12}, {24, 12},       // n = 2M up to K + A = 12
+    {24, 16}, {28, 14},       // n = 2M up to K + A = 14
+    {32, 16}, {32, 32}, {48, 16}, {48, 32},
+};
+constexpr int kProjTileCount = sizeof(kProjTiles) / sizeof(kProjTiles[0]);
+int proj_tile(int n, int M) {         // the smallest tile that holds (n, n - M); inside proj_domain one always does
+    for (int t = 0; t < kProjTileCount; ++t)
+        if (n <= kProjTiles[t].nb && n - M <= kProjTiles[t].rm) return t;
+    return -1;
+}
+size_t basis_bytes(int tile, bool homogeneous) {
+    const int stride = ush_stride(kProjTiles[tile].nb);
+    const size_t b = sizeof(double) * (ush_rows(kProjTiles[tile].rm) * stride +
+                                       (homogeneous ? kProjMaxM * stride + kProjMaxM * kProjMaxM : 0));
+    return (b + 255) & ~static_cast<size_t>(255);
+}
+// Algorithm 1 on the shared factorisation: the register QR runs min(M, RM - 1) <= 15 steps, and two classes of 2M
+// lanes have to fit a wave for the singular-vector stage.
+// It pays where the full n x 2M factorisation in LDS is the larger part of the work -- K + A from 13 on, or six and
+// more workers beyond the minimum of eq. (3) (measured, 10 classes: K + A = 14, 28 workers 2.6 -> 2.2 ms, 1.3 ms
+// with the shared basis of a call without stragglers; K + A = 10, 28 workers 0.59 -> 0.36 ms) -- and loses elsewhere
+// to the LDS kernel's higher occupancy in the singular-vector stage (K + A = 10, 20 workers: 0.23 -> 0.31 ms).
+bool hom_proj_domain(int M, int n) {
+    return proj_domain(M, n) && M <= kProjMaxM - 1 && (M >= 13 || n >= 2 * M + 6);
+}
+size_t votes_bytes(int64_t G, int N) {
+    return (sizeof(int32_t) * static_cast<size_t>(G) * (N + 1) + 255) & ~static_cast<size_t>(255);
+}
+// Groups with a full mask exist only when no fixed number of stragglers is asked for; the shared basis serves the
+// projected kernel (Algorithm 2).
+bool full_basis_applies(int N, int S, int M) { return S <= 0 && proj_domain(M, N); }
+
+// The caller's workspace, carved: first the basis of the full node set (8-byte aligned), then the vote words.
+struct Carved {
+    double *basis;
+    int32_t *votes;
+};
+Carved carve_workspace(void *d_workspace, size_t bytes, size_t need_basis, size_t need_votes) {
+    Carved c = {nullptr, nullptr};
+    unsigned char *p = static_cast<unsigned char *>(d_workspace);
+    if (p == nullptr) return c;
+    if (need_basis != 0 && reinterpret_cast<uintptr_t>(p) % sizeof(double) == 0 && bytes >= need_basis) {
+        c.basis = reinterpret_cast<double *>(p);
+        p += need_basis;
+        bytes -= need_basis;
+    }
+    if (need_votes != 0 && reinterpret_cast<uintptr_t>(p) % sizeof(int32_t) == 0 && bytes >= need_votes)
+        c.votes = reinterpret_cast<int32_t *>(p);
+    return c;
+}
+
+// kNoFit: the shape does not fit this kernel's LDS (Algorithm 1 with many workers): the caller falls back.
+constexpr int kNoFit = 1;
+
+template <int NB, int RM, bool HOMOG>
 int run_proj(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv, int32_t *d_status, int64_t G,
              int K, int N, int S, int A, int64_t C, int n_cap, bool vec4, const Nodes &nodes, int sign_mode,
-             int32_t *ws, hipStream_t stream) {
+             void *d_workspace, size_t workspace_bytes, int tile, hipStream_t stream) {
     const int KP = (K + 3) & ~3;
+    const int M = K + A;
     const int64_t Cv = vec4 ? C / 4 : C;
-    const ProjShape p = proj_shape(G, C, ws != nullptr);
+    const size_t need_basis = full_basis_applies(N, S, M) ? basis_bytes(tile, HOMOG) : 0;
+    const Carved ws = carve_workspace(d_workspace, workspace_bytes, need_basis, votes_bytes(G, N));
+    ProjShape p = proj_shape(G, C, ws.votes != nullptr);
     const int CW = 1 << p.cw_log2;
-    const size_t lds = sizeof(double) * (static_cast<size_t>(ush_rows(RM)) * ush_stride(NB) + NB * kPwStride + NB +
-                                         static_cast<size_t>(n_cap - A) * KP + K + N) +
-                       sizeof(float) * (static_cast<size_t>(NB) * CW) + sizeof(int) * (5 * static_cast<size_t>(N) + 2);
-    if (lds > 64 * 1024) return APPROXIFER_ERR_LIMIT;      // cannot happen inside the projected kernel's domain
+    const size_t hom_wave = HOMOG ? sizeof(double) * (kWave / (2 * M)) * (static_cast<size_t>(2 * M) * (2 * M + 1) + M + n_cap) : 0;
+    const size_t fixed = sizeof(double) * (static_cast<size_t>(basis_doubles<NB, RM, HOMOG>()) + NB * kPwStride + NB +
+                                           static_cast<size_t>(n_cap - A) * KP + K + N) +
+                         sizeof(float) * (static_cast<size_t>(NB) * CW) + sizeof(int) * (4 * static_cast<size_t>(N) + 2);
+    while (p.nw > 1 && fixed + p.nw * hom_wave > 64 * 1024) --p.nw;
+    const size_t lds = fixed + p.nw * hom_wave;
+    if (lds > 64 * 1024) return HOMOG ? kNoFit : APPROXIFER_ERR_LIMIT;   // Algorithm 2: cannot happen inside the domain
     if (G * p.splits > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    if (ws.basis != nullptr) {
+        const hipError_t e = launch_kernel(full_basis_kernel<NB, RM, HOMOG>, dim3(1), dim3(kWave), 0, stream, ws.basis, N, M, nodes);
+        if (e != hipSuccess) return APPROXIFER_ERR_LAUNCH;
+    }
     if (p.splits > 1) {
-        const int rc = clear_workspace(ws, G, N, stream);
+        const int rc = clear_workspace(ws.votes, G, N, stream);
         if (rc != APPROXIFER_OK) return rc;
     }
     const dim3 grid(static_cast<unsigned>(G * p.splits)), block(p.nw * kWave);
-    return launch_status(launch_kernel(decode_byzantine_proj_kernel<NB, RM>, grid, block, lds, stream, d_preds, d_mask, d_out,
+    return launch_status(launch_kernel(decode_byzantine_proj_kernel<NB, RM, HOMOG>, grid, block, lds, stream, d_preds, d_mask, d_out,
                                        d_adv, d_status, K, N, S, A, C, Cv, vec4 ? 1 : 0, sign_mode, n_cap, p.cw_log2,
-                                       p.splits, ws, nodes));
+                                       p.splits, ws.votes, static_cast<const double *>(ws.basis), nodes));
 }
 
 }  // namespace
@@ -1128,12 +1364,15 @@ size_t byzantine_workspace_bytes(int64_t G, int K, int N, int S, int A, int64_t 
     const int n = avail_capacity(N, S);
     const int M = K + A;
     bool splits = false;
-    if (proj_domain(M, n)) splits = proj_shape(G, C, true).splits > 1;
-    else splits = general_shape(G, K, N, n, A, C, false, true).splits > 1;
+    size_t basis = 0;
+    if (proj_domain(M, n)) {
+        splits = proj_shape(G, C, true).splits > 1;
+        if (full_basis_applies(N, S, M)) basis = basis_bytes(proj_tile(n, M), hom_proj_domain(M, n));
+    } else {
+        splits = general_shape(G, K, N, n, A, C, false, true).splits > 1;
+    }
     splits = splits || general_shape(G, K, N, n, A, C, true, true).splits > 1;       // Algorithm 1's locator
-    if (!splits) return 0;
-    const size_t bytes = sizeof(int32_t) * static_cast<size_t>(G) * (N + 1);
-    return (bytes + 255) & ~static_cast<size_t>(255);
+    return basis + (splits ? votes_bytes(G, N) : 0);
 }
 
 int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv,
@@ -1145,41 +1384,47 @@ int launch_decode_byzantine(const float *d_preds, const uint8_t *d_mask, float *
     const bool vec4 = (C % 4 == 0) && aligned16(d_preds) && aligned16(d_out);
     const int64_t Cv = vec4 ? C / 4 : C;
     if (G > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
-    // the workgroups of a group meet in the workspace: without one that holds N + 1 words per group, and is aligned
-    // for them, every group stays with one workgroup
-    int32_t *ws = nullptr;
-    if (d_workspace != nullptr && reinterpret_cast<uintptr_t>(d_workspace) % sizeof(int32_t) == 0 &&
-        workspace_bytes / sizeof(int32_t) / static_cast<size_t>(N + 1) >= static_cast<size_t>(G))
-        ws = static_cast<int32_t *>(d_workspace);
 
-    if (!homogeneous && proj_domain(M, n)) {
-        // register tiles <rows of [V | I], rows of the projected system>: the smallest that holds (n, n - M)
-#define APPROXIFER_PROJ(NB, RM)                                                                                        \
-    if (n <= NB && n - M <= RM)                                                                                        \
-        return run_proj<NB, RM>(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, S, A, C, n, vec4, nodes, sign_mode, ws, stream);
-        APPROXIFER_PROJ(20, 10)       // n = 2M, the minimum of eq. (3), up to K + A = 10
-        APPROXIFER_PROJ(20, 12)
-        APPROXIFER_PROJ(24, 12)       // n = 2M up to K + A = 12
-        APPROXIFER_PROJ(24, 16)
-        APPROXIFER_PROJ(28, 14)       // n = 2M up to K + A = 14
-        APPROXIFER_PROJ(32, 16)
-        APPROXIFER_PROJ(32, 32)
-        APPROXIFER_PROJ(48, 16)
-        APPROXIFER_PROJ(48, 32)
+    if (homogeneous ? hom_proj_domain(M, n) : proj_domain(M, n)) {
+        int rc = kNoFit;
+#define APPROXIFER_PROJ(T, NB, RM)                                                                                     \
+    case T:                                                                                                            \
+        static_assert(kProjTiles[T].nb == NB && kProjTiles[T].rm == RM, "tile table");                                 \
+        rc = homogeneous ? run_proj<NB, RM, true>(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, S, A, C, n, vec4,     \
+                                                  nodes, sign_mode, d_workspace, workspace_bytes, T, stream)            \
+                         : run_proj<NB, RM, false>(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, S, A, C, n, vec4,    \
+                                                   nodes, sign_mode, d_workspace, workspace_bytes, T, stream);          \
+        break;
+        switch (proj_tile(n, M)) {
+            APPROXIFER_PROJ(0, 20, 10)
+            APPROXIFER_PROJ(1, 20, 12)
+            APPROXIFER_PROJ(2, 24, 12)
+            APPROXIFER_PROJ(3, 24, 16)
+            APPROXIFER_PROJ(4, 28, 14)
+            APPROXIFER_PROJ(5, 32, 16)
+            APPROXIFER_PROJ(6, 32, 32)
+            APPROXIFER_PROJ(7, 48, 16)
+            APPROXIFER_PROJ(8, 48, 32)
+            default: return APPROXIFER_ERR_LIMIT;          // cannot happen inside the projected kernel's domain
+        }
 #undef APPROXIFER_PROJ
+        if (rc != kNoFit) return rc;
     }
 
-    const GeneralShape sh = general_shape(G, K, N, n, A, C, homogeneous, ws != nullptr);
+    // the workgroups of a group meet in the workspace: without one that holds N + 1 words per group, and is aligned
+    // for them, every group stays with one workgroup
+    const Carved ws = carve_workspace(d_workspace, workspace_bytes, 0, votes_bytes(G, N));
+    const GeneralShape sh = general_shape(G, K, N, n, A, C, homogeneous, ws.votes != nullptr);
     if (sh.lds == 0) return APPROXIFER_ERR_LIMIT;
     if (G * sh.splits > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
     if (sh.splits > 1) {
-        const int rc = clear_workspace(ws, G, N, stream);
+        const int rc = clear_workspace(ws.votes, G, N, stream);
         if (rc != APPROXIFER_OK) return rc;
     }
     const dim3 grid(static_cast<unsigned>(G * sh.splits)), block(sh.nw * kWave);
     return launch_status(launch_kernel(homogeneous ? decode_byzantine_general_kernel<true> : decode_byzantine_general_kernel<false>,
                                        grid, block, sh.lds, stream, d_preds, d_mask, d_out, d_adv, d_status, K, N, S, A, C, Cv,
-                                       vec4 ? 1 : 0, sign_mode, sh.cpw, n, sh.splits, ws, nodes));
+                                       vec4 ? 1 : 0, sign_mode, sh.cpw, n, sh.splits, ws.votes, nodes));
 }
 
 }  // namespace approxifer

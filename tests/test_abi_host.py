@@ -120,22 +120,27 @@ def test_host_validation_codes(lib):
 
 def test_workspace_bytes(lib):
     wb = binding.approxifer_workspace_bytes
-    # many groups, ten classes: one workgroup per group fills the GPU, nothing to pool
+    # many groups, ten classes, a fixed number of stragglers: one workgroup per group fills the GPU, no mask is full
     assert wb(2048, 8, 24, 4, 2, 10) == 0
-    # few groups, a thousand classes: N + 1 words per group, rounded up to 256 bytes
-    need = wb(8, 12, 28, 0, 2, 1000)
-    assert need == (8 * 29 * 4 + 255) // 256 * 256
-    assert wb(3, 8, 24, -1, 2, 1000) == (3 * 25 * 4 + 255) // 256 * 256
+    # no stragglers asked for: room for the factorisation of the full node set, whatever the number of groups
+    # (K + A = 14, 28 workers: the complement basis, 16 x 28 doubles, and for Algorithm 1's locator the other 16 rows
+    # of the orthogonal factor and the 16 x 16 triangular one)
+    basis_28_14 = (16 * 28 + 16 * 28 + 16 * 16) * 8
+    assert wb(8192, 12, 28, 0, 2, 10) == basis_28_14
+    # few groups, a thousand classes: N + 1 vote words per group on top, each part rounded up to 256 bytes
+    assert wb(8, 12, 28, 0, 2, 1000) == basis_28_14 + (8 * 29 * 4 + 255) // 256 * 256
+    assert wb(3, 8, 24, -1, 2, 1000) == 16 * 24 * 8 + (3 * 25 * 4 + 255) // 256 * 256
+    assert wb(3, 8, 24, 4, 2, 1000) == (3 * 25 * 4 + 255) // 256 * 256
     # beyond the projected kernel's domain (60 available workers) the LDS kernel splits from four passes on
-    assert wb(3, 8, 60, 0, 2, 300) > 0
+    assert wb(3, 8, 60, 0, 2, 300) == (3 * 61 * 4 + 255) // 256 * 256
     # shapes the decoders refuse need nothing
     for args in ((0, 8, 24, 4, 2, 1000), (8, 8, 24, 4, 2, 0), (8, 0, 24, 4, 2, 1000), (8, 8, 24, 4, 0, 1000),
                  (8, 8, 24, 5, 2, 1000), (8, 65, 24, 4, 2, 1000), (8, 8, 129, 4, 2, 1000), (8, 2, 100, 0, 1, 1000),
                  (8, 8, 24, -2, 2, 1000), (8, 8, 24, 24, 2, 1000)):
         assert wb(*args) == 0, args
-    # never more than 4 (N + 1) bytes per group plus the rounding
+    # never more than 4 (N + 1) bytes per group plus the basis (at most 32 x 52 doubles) plus the rounding
     for G, K, N, S, A, C in ((1, 2, 128, 64, 1, 100000), (5, 14, 64, 0, 2, 5000), (4095, 1, 6, 0, 1, 70000)):
-        assert wb(G, K, N, S, A, C) <= 4 * (N + 1) * G + 255
+        assert wb(G, K, N, S, A, C) <= 4 * (N + 1) * G + 255 + 32 * 52 * 8
 
 
 def test_static_entry_point_refuses_shapes_beyond_its_workspace(lib):
