@@ -169,6 +169,28 @@ __device__ __forceinline__ double row_bcast(double v) {   // lane LANE of every 
     return __hiloint2double(hi, lo);
 }
 
+// The same for a lane index that is only known after unrolling.
+__device__ __forceinline__ double row_bcast_dyn(double v, int lane_in_row) {
+    switch (lane_in_row) {
+        case 0: return row_bcast<0>(v);
+        case 1: return row_bcast<1>(v);
+        case 2: return row_bcast<2>(v);
+        case 3: return row_bcast<3>(v);
+        case 4: return row_bcast<4>(v);
+        case 5: return row_bcast<5>(v);
+        case 6: return row_bcast<6>(v);
+        case 7: return row_bcast<7>(v);
+        case 8: return row_bcast<8>(v);
+        case 9: return row_bcast<9>(v);
+        case 10: return row_bcast<10>(v);
+        case 11: return row_bcast<11>(v);
+        case 12: return row_bcast<12>(v);
+        case 13: return row_bcast<13>(v);
+        case 14: return row_bcast<14>(v);
+        default: return row_bcast<15>(v);
+    }
+}
+
 // Reciprocal and square root of a normal, positive-or-negative (rcp) / positive (sqrt) double to full
 // double precision: the hardware estimate refined by two Newton (Goldschmidt) steps and, for the root, one
 // residual correction.  No scaling for denormals or infinities and no final correctly-rounded fix-up, which
@@ -443,7 +465,145 @@ __device__ __forceinline__ void locate_classes_proj(const float *Ysh, int CW, in
 }
 
 __device__ __forceinline__ void homogeneous_q(double *mat, int LD, double *coef, double *key, int W2, int M, int j,
-                                              bool live);
+                                              bool live, bool jacobi_only);
+
+constexpr int kInverseRounds = 24;      // inverse-iteration rounds before a class goes to the Jacobi iteration
+constexpr int kJacobiSweeps = 30;
+constexpr int kRegisterRounds = 64;     // .. and of the register form, whose rounds are cheap next to that fallback
+
+// Smallest right singular vector of the 2M x 2M factor R = [[R_V, B1], [0, R2]] of one class, by inverse iteration
+// z <- (R^T R)^-1 z, entirely in the registers of the class's 16-lane row (lane j = index j of both halves of
+// z = (p, q), M <= 15).  The four triangular solves of a round,
+//     w1 = R_V^-T p,   w2 = R2^-T (q - B1^T w1),   q' = R2^-1 w2,   p' = R_V^-1 (w1 - B1 q'),
+// are column sweeps: the entry that has just become final is broadcast along the row (DPP) and every lane subtracts
+// its multiple.  The two forward sweeps need the lane's COLUMN of R_V, B1, R2, the two backward ones its ROW; the
+// rows of B1 and R2 come through one transposition in the wave's LDS scratch (T: 4 classes x 16 x 17 doubles), those
+// of R_V from the group's LDS copy.  Start vector, settling rule, extrapolation of a slowly decaying error mode and
+// the floor under vanishing pivots are those of homogeneous_q (the LDS form, which stays the fallback for a class
+// that has not settled after kRegisterRounds: it also holds the Jacobi iteration).
+//   r2c[i] = R2[i][j] (i <= j), b1c[i] = B1[i][j]: this lane's columns; Rv: LDS, row stride 16.
+//   MT >= M bounds the unrolling and the register arrays (the register tile of the kernel bounds M: M <= NB / 2).
+// `live`: the row holds a class.  Returns q_j in `qv` and whether the class settled (the same value in all lanes of
+// the row).
+template <int MT>
+__device__ __forceinline__ bool singular_vector_rows(const double (&r2c)[MT], const double (&b1c)[MT],
+                                                     const double *Rv, double *T, int M, int j, int cl, bool live,
+                                                     double &qv) {
+    constexpr int LDT = kProjMaxM + 1;
+    const bool act = j < M;
+    double *Tc = T + cl * kProjMaxM * LDT;
+    // rows of R2 and B1 by transposition through LDS
+    double r2r[MT], b1r[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) Tc[i * LDT + j] = (act && i < M && i <= j) ? r2c[i] : 0.0;
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int k = 0; k < MT; ++k) r2r[k] = Tc[j * LDT + k];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int i = 0; i < MT; ++i) Tc[i * LDT + j] = (act && i < M) ? b1c[i] : 0.0;
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int k = 0; k < MT; ++k) b1r[k] = act ? Tc[j * LDT + k] : 0.0;   // rows MT.. of the tile were never written
+    __builtin_amdgcn_wave_barrier();
+    // R_V's column and row are read from the group's LDS copy inside the sweeps (they are the same for the wave's
+    // four classes); Rv is zero below its diagonal and outside M x M.
+    constexpr int LDV = kProjMaxM;
+    const double *rv_col = Rv + j;                         // rv_col[i * LDV] = R_V[i][j]
+    const double *rv_row = Rv + j * LDV;                   // rv_row[k] = R_V[j][k]
+    // reciprocal pivots; a pivot below 1e-24 of its column of R is raised to that (an exactly singular system keeps
+    // its null vector to 1e-24, and the solves stay finite)
+    double csv = 0.0, cs2 = 0.0;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        const double rv = rv_col[i * LDV];
+        csv = fma(rv, rv, csv);
+        cs2 = fma(b1c[i], b1c[i], fma((i < M && i <= j) ? r2c[i] : 0.0, (i < M && i <= j) ? r2c[i] : 0.0, cs2));
+    }
+    double dv = rv_row[j], d2 = 0.0;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) d2 = (i == j && i < M) ? r2c[i] : d2;
+    const double fv = 1e-24 * sqrt(csv), f2 = 1e-24 * sqrt(cs2);
+    if (fabs(dv) < fv) dv = dv < 0.0 ? -fv : fv;
+    if (fabs(d2) < f2) d2 = d2 < 0.0 ? -f2 : f2;
+    const double rdv = act ? 1.0 / dv : 0.0, rd2 = act ? 1.0 / d2 : 0.0;   // a zero column: inf, the class does not settle
+    // strictly upper parts: the multiples a sweep subtracts
+#pragma unroll
+    for (int i = 0; i < MT; ++i) r2r[i] = (act && i > j) ? r2r[i] : 0.0;
+    double r2u[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) r2u[i] = (act && i < M && i < j) ? r2c[i] : 0.0;
+
+    double p = act ? 1.0 + 0.25 * (j % 3) : 0.0;
+    double q = act ? 1.0 + 0.25 * ((M + j) % 3) : 0.0;
+    double dd_prev = __builtin_inf();
+    int since_jump = 0;
+    bool settled = false;
+    for (int round = 0; round < kRegisterRounds; ++round) {
+        // forward: w1 = R_V^-T p, t = q - B1^T w1, then w2 = R2^-T t
+        double s1 = p, t = q;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            if (i < M) {
+                const double wi = row_bcast_dyn(s1 * rdv, i);
+                s1 = fma(i < j ? -rv_col[i * LDV] : 0.0, wi, s1);
+                t = fma(-b1c[i], wi, t);
+            }
+        }
+        const double w1 = s1 * rdv;
+        double s2 = t;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            if (i < M) {
+                const double wi = row_bcast_dyn(s2 * rd2, i);
+                s2 = fma(-r2u[i], wi, s2);
+            }
+        }
+        // backward: q' = R2^-1 w2, u = w1 - B1 q', then p' = R_V^-1 u
+        double s3 = s2 * rd2, u = w1;
+#pragma unroll
+        for (int k = MT - 1; k >= 0; --k) {
+            if (k < M) {
+                const double qk = row_bcast_dyn(s3 * rd2, k);
+                s3 = fma(-r2r[k], qk, s3);
+                u = fma(-b1r[k], qk, u);
+            }
+        }
+        const double qn_raw = s3 * rd2;
+        double s4 = u;
+#pragma unroll
+        for (int k = MT - 1; k >= 0; --k) {
+            if (k < M) {
+                const double pk = row_bcast_dyn(s4 * rdv, k);
+                s4 = fma(k > j ? -rv_row[k] : 0.0, pk, s4);
+            }
+        }
+        const double pn_raw = s4 * rdv;
+        const double nn = row16_sum(act ? fma(pn_raw, pn_raw, qn_raw * qn_raw) : 0.0);
+        const double inv = rcp_normal(sqrt_normal(nn));       // nn = 0, inf or NaN: NaN, the class does not settle
+        const double pn = act ? pn_raw * inv : 0.0, qn = act ? qn_raw * inv : 0.0;
+        const double dp = pn - p, dq = qn - q;                // z' . z > 0 always: no sign to align
+        const double dd = row16_sum(fma(dp, dp, dq * dq));
+        const double dd_before = dd_prev;
+        settled = settled || dd <= 1e-22 || (dd_prev <= 1e-16 && dd >= 0.25 * dd_prev);
+        p = pn;
+        q = qn;
+        dd_prev = dd;
+        ++since_jump;
+        if (!settled && since_jump >= 3 && dd < 1e-4 && dd_before < __builtin_inf()) {
+            const double r = sqrt(dd / dd_before);
+            if (r > 0.05 && r < 0.97) {
+                p = fma(r / (1.0 - r), dp, pn);
+                q = fma(r / (1.0 - r), dq, qn);
+                since_jump = 0;
+                dd_prev = __builtin_inf();
+            }
+        }
+        if (__all((settled || !live) ? 1 : 0)) break;     // rows without a class (all zeros) never settle: not waited for
+    }
+    qv = q;
+    return settled;
+}
 
 // Algorithm 1 (the homogeneous fit, Q_0 free) for the four classes c_rel..c_rel+3 of the staged tile, by one wave, on
 // the shared factorisation V = Q [R_V; 0] of the group.  With H_c = [V | diag(y_c) V] (the sign of the second block
@@ -466,9 +626,10 @@ __device__ __forceinline__ void locate_classes_hom_proj(const float *Ysh, int CW
     const int j = lane % kClsLanes;
     const int e = j < M ? j : 0;                          // column of this lane: y x^j; idle lanes hold zeros
     const double sgn = j < M ? 1.0 : 0.0;
+    constexpr int MT = NB / 2 < kProjMaxM ? NB / 2 : kProjMaxM;   // eq. (3): M <= n / 2 <= NB / 2
     constexpr int kKSteps = NB / 4;
     constexpr int kUBlocks = ush_rows(RM) / 4;
-    constexpr int kBlocks = kUBlocks + kProjMaxM / 4;     // then the 16 rows of Q1
+    constexpr int kBlocks = kUBlocks + (MT + 3) / 4;      // then the rows of Q1 (16 of them in LDS, the first MT used)
     double bop[kKSteps], yop[kKSteps];
     {
         const int k = lane / kClsLanes, cm = (lane % kClsLanes) & 3;
@@ -479,7 +640,7 @@ __device__ __forceinline__ void locate_classes_hom_proj(const float *Ysh, int CW
             yop[s] = static_cast<double>(Ysh[r * CW + c_rel + cm]);
         }
     }
-    double a[RM], b1[kProjMaxM];
+    double a[RM], b1[MT];
     {
         const double *urow = Ush + ((lane % kClsLanes) >> 2) * ush_stride(NB) + lane / kClsLanes;
         v4d acc[kBlocks];
@@ -497,39 +658,92 @@ __device__ __forceinline__ void locate_classes_hom_proj(const float *Ysh, int CW
             for (int t = 0; t < 4; ++t)
                 if (4 * b + t < RM) a[4 * b + t] = acc[b][t];
 #pragma unroll
-        for (int i = 0; i < kProjMaxM; ++i) b1[i] = acc[kUBlocks + i / 4][i % 4];
+        for (int i = 0; i < MT; ++i) b1[i] = acc[kUBlocks + i / 4][i % 4];
     }
 
     // R2: steps 0 .. min(M, RM - 1) - 1; when M == RM the last diagonal entry is the one row that is left
     constexpr int kSteps = RM - 1 < kProjMaxM - 1 ? RM - 1 : kProjMaxM - 1;
     ClassQrSteps<0, kSteps, RM>::run(a, j, M);
 
-    // ---- assemble the factor and find its smallest right singular vector, cpw classes at a time --------------------
+    // ---- the singular vector: in registers; classes that do not settle there go through the LDS form below ---------
+    const int cl16 = lane / kClsLanes;                    // class slot of this lane in the register layout
+    double r2c[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) r2c[i] = i < RM ? a[i < RM ? i : 0] : 0.0;
+    double qv;
+    const bool class_live = c_rel + cl16 < tile_classes;
+    const bool settled = singular_vector_rows<MT>(r2c, b1, Rv, scratch, M, j, cl16, class_live, qv);
+    // a_r = Q(x_r) = sum_k q_k x_r^k, rows j, j+16, .. of this lane; the A smallest |a_r| vote
+    {
+        double qk[MT];
+#pragma unroll
+        for (int k = 0; k < MT; ++k) qk[k] = row_bcast_dyn(qv, k);              // zero from idle lanes
+        constexpr int PR = (NB + kClsLanes - 1) / kClsLanes;
+        double kv[PR];
+        int ki[PR];
+#pragma unroll
+        for (int pr = 0; pr < PR; ++pr) {
+            const int r = j + pr * kClsLanes;
+            const double x = xs[r < n ? r : 0];
+            double av = 0.0;
+#pragma unroll
+            for (int k = MT - 1; k >= 0; --k) av = fma(av, x, qk[k]);
+            kv[pr] = (r < n && av == av) ? fabs(av) : __builtin_inf();
+            ki[pr] = r;
+        }
+        for (int pick = 0; pick < A; ++pick) {
+            double bv = kv[0];
+            int bi = ki[0];
+#pragma unroll
+            for (int pr = 1; pr < PR; ++pr) {
+                const bool take = kv[pr] < bv || (kv[pr] == bv && ki[pr] < bi);
+                bv = take ? kv[pr] : bv;
+                bi = take ? ki[pr] : bi;
+            }
+            row_min_step<kDppQuadXor1>(bv, bi);
+            row_min_step<kDppQuadXor2>(bv, bi);
+            row_min_step<kDppRowHalfMirror>(bv, bi);
+            row_min_step<kDppRowMirror>(bv, bi);
+            if (class_live && settled && j == 0) atomicAdd(&votes[avail[bi]], 1);
+#pragma unroll
+            for (int pr = 0; pr < PR; ++pr) {
+                if (ki[pr] == bi) {
+                    kv[pr] = __builtin_inf();
+                    ki[pr] = 0x7fffffff;
+                }
+            }
+        }
+    }
+    const unsigned long long open_lanes = __ballot(class_live && !settled);
+    if (open_lanes == 0ull) return;
+
+    // ---- fallback: assemble the factor in LDS and find the vector there (inverse iteration again, then Jacobi) -----
     const int W2 = 2 * M;
     const int LD = W2 + 1;
     const int per_class = W2 * LD + M + n;
     const int cpw = kWave / W2;                           // >= 2: M <= 15
-    const int cl16 = lane / kClsLanes;                    // class slot of this lane in the register layout
-    const int clw = lane / W2, jw = lane - clw * W2;      // .. and in the layout of homogeneous_q (lane jw owns row jw)
+    const int clw = lane / W2, jw = lane - clw * W2;      // the layout of homogeneous_q (lane jw owns row jw)
+    __builtin_amdgcn_wave_barrier();                      // the transposition scratch is free again
     for (int p0 = 0; p0 < kClsPerWave; p0 += cpw) {
         if (cl16 >= p0 && cl16 < p0 + cpw && j < M) {
             double *mat = scratch + (cl16 - p0) * per_class;
 #pragma unroll
-            for (int i = 0; i < kProjMaxM; ++i) {
+            for (int i = 0; i < MT; ++i) {
                 if (i < M) {
                     mat[i * LD + j] = Rv[i * kProjMaxM + j];                    // R_V (zero below its diagonal)
                     mat[(M + i) * LD + j] = 0.0;
                     mat[i * LD + M + j] = b1[i];                                // B1
-                    mat[(M + i) * LD + M + j] = (i < RM && i <= j) ? a[i < RM ? i : 0] : 0.0;   // R2
+                    mat[(M + i) * LD + M + j] = (i <= j) ? r2c[i] : 0.0;        // R2
                 }
             }
         }
         __builtin_amdgcn_wave_barrier();
-        const bool live = clw < cpw && p0 + clw < kClsPerWave && c_rel + p0 + clw < tile_classes;
+        const bool in_pass = clw < cpw && p0 + clw < kClsPerWave;
+        const bool live = in_pass && ((open_lanes >> ((p0 + (in_pass ? clw : 0)) * kClsLanes)) & 1ull) != 0ull;
         double *mat = scratch + (live ? clw : 0) * per_class;
         double *coef = mat + W2 * LD;
         double *key = coef + M;
-        homogeneous_q(mat, LD, coef, key, W2, M, jw, live);
+        homogeneous_q(mat, LD, coef, key, W2, M, jw, live, true);
         if (live) {
             for (int r = jw; r < n; r += W2) {            // a_r = Q(x_r), Q_k = coef[k]
                 const double x = xs[r];
@@ -542,6 +756,14 @@ __device__ __forceinline__ void locate_classes_hom_proj(const float *Ysh, int CW
         if (live) pick_and_vote(key, avail, n, A, jw, W2, votes);
         __builtin_amdgcn_wave_barrier();
     }
+}
+
+// Per-wave LDS scratch of Algorithm 1's locator: the transposition tiles of singular_vector_rows (4 classes x 16 x 17)
+// or, for classes that fall back to homogeneous_q, 64 / 2M factors with their coefficient and key arrays.
+__host__ __device__ constexpr int hom_scratch_doubles(int M, int n_cap) {
+    const int fallback = (kWave / (2 * M)) * (2 * M * (2 * M + 1) + M + n_cap);
+    const int transpose = kClsPerWave * kProjMaxM * (kProjMaxM + 1);
+    return fallback > transpose ? fallback : transpose;
 }
 
 // Doubles of the shared factorisation as the kernel keeps it in LDS (and as full_basis_kernel writes it out):
@@ -575,7 +797,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(!HOMOG && R
     double *WdT = xs + NB;
     double *alpha_s = WdT + (n_cap - A) * KP;
     double *beta_s = alpha_s + K;
-    const int hom_wave_doubles = HOMOG ? (kWave / (2 * M)) * (2 * M * (2 * M + 1) + M + n_cap) : 0;
+    const int hom_wave_doubles = HOMOG ? hom_scratch_doubles(M, n_cap) : 0;
     double *hom_scratch = beta_s + N;
     float *Ysh = reinterpret_cast<float *>(hom_scratch + static_cast<size_t>(nw) * hom_wave_doubles);
     int *avail = reinterpret_cast<int *>(Ysh + NB * CW);
@@ -732,10 +954,9 @@ __global__ __launch_bounds__(kWave) void full_basis_kernel(double *__restrict__ 
 //     shortest is the one wanted.  Both lanes of a pair read both columns and write their own: the new value of
 //     element t depends on both reads of element t, and the lanes of a wave run in lock step, so no lane sees a
 //     half-rotated pair.
-constexpr int kInverseRounds = 24;
-constexpr int kJacobiSweeps = 30;
+// jacobi_only (wave-uniform): the caller's own inverse iteration has already failed to settle; go to step 2.
 __device__ __forceinline__ void homogeneous_q(double *mat, int LD, double *coef, double *key, int W2, int M, int j,
-                                              bool live) {
+                                              bool live, bool jacobi_only = false) {
     double *own = mat + j * LD;
     // ---- 1. inverse iteration; R mirrored into the lower triangle so that both solves read rows ----------------
     double colsq = 0.0;                                   // |column j of R|^2 = |column j of the system|^2
@@ -755,7 +976,7 @@ __device__ __forceinline__ void homogeneous_q(double *mat, int LD, double *coef,
     double dd_prev = __builtin_inf();
     int since_jump = 0;
     bool settled = false;
-    for (int round = 0; round < kInverseRounds; ++round) {
+    for (int round = jacobi_only ? kInverseRounds : 0; round < kInverseRounds; ++round) {
         double s = z;                                     // R^T w = z, forward
         for (int t = 0; t < W2; ++t) {
             const double rtj = mat[t * LD + j];           // issued ahead of the write -> read chain through key
@@ -1149,7 +1370,7 @@ struct ProjShape {
     int cw_log2, nw, splits;
 };
 // `may_split`: the caller brought a workspace for the workgroups of a group to meet in.
-ProjShape proj_shape(int64_t G, int64_t C, bool may_split) {
+ProjShape proj_shape(int64_t G, int64_t C, bool may_split, int64_t fill_waves = kFillWaves) {
     ProjShape p;
     p.cw_log2 = C <= 16 ? 4 : (C <= 32 ? 5 : 6);           // classes per staged tile: 16, 32 or 64
     const int CW = 1 << p.cw_log2;
@@ -1158,7 +1379,7 @@ ProjShape proj_shape(int64_t G, int64_t C, bool may_split) {
     // idle through the shared factorisation (measured at G = 2048, C = 10: 1 wave 44.7 us, 2 waves 42.7, 3 waves 53.0)
     int nw = static_cast<int>(((C < CW ? C : CW) + kClsPerWave - 1) / kClsPerWave);
     if (nw > 4) nw = 4;
-    const int64_t fill = (kFillWaves + G - 1) / G;
+    const int64_t fill = (fill_waves + G - 1) / G;
     if (nw > fill) nw = static_cast<int>(fill);
     p.nw = nw;
     // Few groups with many classes: one workgroup per group would leave most of the chip idle while each group walks
@@ -1168,7 +1389,7 @@ ProjShape proj_shape(int64_t G, int64_t C, bool may_split) {
     const int64_t tiles = (C + CW - 1) / CW;
     p.splits = 1;
     if (may_split && tiles >= 4) {
-        const int64_t want = kFillWaves / (G * nw);
+        const int64_t want = fill_waves / (G * nw);
         p.splits = static_cast<int>(want < tiles ? want : tiles);
         if (p.splits < 1) p.splits = 1;
     }
@@ -1246,15 +1467,11 @@ size_t basis_bytes(int tile, bool homogeneous) {
                                        (homogeneous ? kProjMaxM * stride + kProjMaxM * kProjMaxM : 0));
     return (b + 255) & ~static_cast<size_t>(255);
 }
-// Algorithm 1 on the shared factorisation: the register QR runs min(M, RM - 1) <= 15 steps, and two classes of 2M
-// lanes have to fit a wave for the singular-vector stage.
-// It pays where the full n x 2M factorisation in LDS is the larger part of the work -- K + A from 13 on, or six and
-// more workers beyond the minimum of eq. (3) (measured, 10 classes: K + A = 14, 28 workers 2.6 -> 2.2 ms, 1.3 ms
-// with the shared basis of a call without stragglers; K + A = 10, 28 workers 0.59 -> 0.36 ms) -- and loses elsewhere
-// to the LDS kernel's higher occupancy in the singular-vector stage (K + A = 10, 20 workers: 0.23 -> 0.31 ms).
-bool hom_proj_domain(int M, int n) {
-    return proj_domain(M, n) && M <= kProjMaxM - 1 && (M >= 13 || n >= 2 * M + 6);
-}
+// Algorithm 1 on the shared factorisation: the register QR runs min(M, RM - 1) <= 15 steps.  Below K + A = 6 the LDS
+// kernel, which packs 64 / 2M classes into a wave, is the faster one (measured, 10 classes, 4096 groups: K + A = 3:
+// 33 us against 77; K + A = 6: 105 against 101; K + A = 10: 233 against 124; K + A = 12: 830 against 214;
+// K + A = 14, 8192 groups: 2651 against 548).
+bool hom_proj_domain(int M, int n) { return proj_domain(M, n) && M >= 6 && M <= kProjMaxM - 1; }
 size_t votes_bytes(int64_t G, int N) {
     return (sizeof(int32_t) * static_cast<size_t>(G) * (N + 1) + 255) & ~static_cast<size_t>(255);
 }
@@ -1293,9 +1510,10 @@ int run_proj(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t 
     const int64_t Cv = vec4 ? C / 4 : C;
     const size_t need_basis = full_basis_applies(N, S, M) ? basis_bytes(tile, HOMOG) : 0;
     const Carved ws = carve_workspace(d_workspace, workspace_bytes, need_basis, votes_bytes(G, N));
-    ProjShape p = proj_shape(G, C, ws.votes != nullptr);
+    // Algorithm 1's locator runs two waves to a SIMD (registers): half as many waves fill the chip
+    ProjShape p = proj_shape(G, C, ws.votes != nullptr, HOMOG ? kFillWaves / 2 : kFillWaves);
     const int CW = 1 << p.cw_log2;
-    const size_t hom_wave = HOMOG ? sizeof(double) * (kWave / (2 * M)) * (static_cast<size_t>(2 * M) * (2 * M + 1) + M + n_cap) : 0;
+    const size_t hom_wave = HOMOG ? sizeof(double) * hom_scratch_doubles(M, n_cap) : 0;
     const size_t fixed = sizeof(double) * (static_cast<size_t>(basis_doubles<NB, RM, HOMOG>()) + NB * kPwStride + NB +
                                            static_cast<size_t>(n_cap - A) * KP + K + N) +
                          sizeof(float) * (static_cast<size_t>(NB) * CW) + sizeof(int) * (4 * static_cast<size_t>(N) + 2);

@@ -129,7 +129,7 @@ def test_workspace_bytes(lib):
     assert wb(8192, 12, 28, 0, 2, 10) == basis_28_14
     # few groups, a thousand classes: N + 1 vote words per group on top, each part rounded up to 256 bytes
     assert wb(8, 12, 28, 0, 2, 1000) == basis_28_14 + (8 * 29 * 4 + 255) // 256 * 256
-    assert wb(3, 8, 24, -1, 2, 1000) == 16 * 24 * 8 + (3 * 25 * 4 + 255) // 256 * 256
+    assert wb(3, 8, 24, -1, 2, 1000) == (16 * 24 + 16 * 24 + 16 * 16) * 8 + (3 * 25 * 4 + 255) // 256 * 256
     assert wb(3, 8, 24, 4, 2, 1000) == (3 * 25 * 4 + 255) // 256 * 256
     # beyond the projected kernel's domain (60 available workers) the LDS kernel splits from four passes on
     assert wb(3, 8, 60, 0, 2, 300) == (3 * 61 * 4 + 255) // 256 * 256
