@@ -77,8 +77,10 @@ typedef v4f v4f_dword_aligned __attribute__((aligned(4)));
 
 template <bool UNAL>
 __device__ __forceinline__ v4f load_pred_vector(const float *p, int floats) {
-    if (!UNAL) return *reinterpret_cast<const v4f *>(p);
-    if (floats >= 4) return *reinterpret_cast<const v4f_dword_aligned *>(p);
+    // every prediction is read once and every output written once: non-temporal accesses keep them out of the way of
+    // the caches (measured on the streaming kernel: 49 MB cold 21.4 -> 17.5 us, 0.4 GB 105 -> 73 us, 1.1 GB +7..9 %)
+    if (!UNAL) return __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
+    if (floats >= 4) return __builtin_nontemporal_load(reinterpret_cast<const v4f_dword_aligned *>(p));
     v4f v = v4f(0.0f);
     v[0] = p[0];
     if (floats > 1) v[1] = p[1];
@@ -165,7 +167,7 @@ __global__ __launch_bounds__(kWave) void decode_stream_kernel(const float *__res
                 v[1] = static_cast<float>(acc[j][1]);
                 v[2] = static_cast<float>(acc[j][2]);
                 v[3] = static_cast<float>(acc[j][3]);
-                *reinterpret_cast<v4f_dword_aligned *>(dst) = v;
+                __builtin_nontemporal_store(static_cast<v4f_dword_aligned>(v), reinterpret_cast<v4f_dword_aligned *>(dst));
             } else {
                 dst[0] = static_cast<float>(acc[j][0]);
                 if (floats > 1) dst[1] = static_cast<float>(acc[j][1]);

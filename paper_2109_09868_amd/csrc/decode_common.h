@@ -113,10 +113,10 @@ template <> __device__ __forceinline__ void store_row<4>(float *dst, const doubl
     v[1] = static_cast<float>(acc[1]);
     v[2] = static_cast<float>(acc[2]);
     v[3] = static_cast<float>(acc[3]);
-    *reinterpret_cast<v4f *>(dst) = v;
+    __builtin_nontemporal_store(v, reinterpret_cast<v4f *>(dst));     // written once, not read again by this call
 }
 template <> __device__ __forceinline__ void store_row<1>(float *dst, const double *acc) {
-    *dst = static_cast<float>(acc[0]);
+    __builtin_nontemporal_store(static_cast<float>(acc[0]), dst);
 }
 
 constexpr int kRowChunk = 8;   // prediction rows a lane keeps in flight at once
@@ -130,7 +130,7 @@ __device__ __forceinline__ void load_row_chunk(const float *__restrict__ pg, con
 #pragma unroll
     for (int u = 0; u < kRowChunk; ++u) {
         const int r = (r0 + u < nF) ? r0 + u : nF - 1;
-        y[u] = *reinterpret_cast<const V *>(pg + static_cast<size_t>(F[r]) * C + cv * VEC);
+        y[u] = __builtin_nontemporal_load(reinterpret_cast<const V *>(pg + static_cast<size_t>(F[r]) * C + cv * VEC));
     }
 }
 
