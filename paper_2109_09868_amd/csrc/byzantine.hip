@@ -157,6 +157,8 @@ constexpr int kPwStride = 16;      // powers table row: x^0 .. x^15
 constexpr int kProjMaxM = 16;      // M - 1 <= 15 unknown columns in lanes 0..14, right-hand side in lane 15
 // U in LDS: rows padded to a multiple of four (the matrix-core tiles below take four rows of U at a time), row
 // stride chosen so that the sixteen (row, column) pairs one operand load touches fall in distinct banks.
+// Register-array bound of Algorithm 1's locator for a tile of NB rows: eq. (3) gives M <= n / 2 <= NB / 2.
+constexpr int hom_mt(int NB) { return NB / 2 < kProjMaxM ? NB / 2 : kProjMaxM; }
 constexpr int ush_rows(int RM) { return (RM + 3) & ~3; }
 constexpr int ush_stride(int NB) { return NB % 16 == 0 ? NB + 4 : NB; }
 
@@ -477,7 +479,7 @@ constexpr int kRegisterRounds = 64;     // .. and of the register form, whose ro
 //     w1 = R_V^-T p,   w2 = R2^-T (q - B1^T w1),   q' = R2^-1 w2,   p' = R_V^-1 (w1 - B1 q'),
 // are column sweeps: the entry that has just become final is broadcast along the row (DPP) and every lane subtracts
 // its multiple.  The two forward sweeps need the lane's COLUMN of R_V, B1, R2, the two backward ones its ROW; the
-// rows of B1 and R2 come through one transposition in the wave's LDS scratch (T: 4 classes x 16 x 17 doubles), those
+// rows of B1 and R2 come through one transposition in the wave's LDS scratch (T: 4 classes x MT x (MT + 1) doubles), those
 // of R_V from the group's LDS copy.  Start vector, settling rule, extrapolation of a slowly decaying error mode and
 // the floor under vanishing pivots are those of homogeneous_q (the LDS form, which stays the fallback for a class
 // that has not settled after kRegisterRounds: it also holds the Jacobi iteration).
@@ -489,22 +491,24 @@ template <int MT>
 __device__ __forceinline__ bool singular_vector_rows(const double (&r2c)[MT], const double (&b1c)[MT],
                                                      const double *Rv, double *T, int M, int j, int cl, bool live,
                                                      double &qv) {
-    constexpr int LDT = kProjMaxM + 1;
+    constexpr int LDT = MT + 1;
     const bool act = j < M;
-    double *Tc = T + cl * kProjMaxM * LDT;
+    double *Tc = T + cl * MT * LDT;                        // M <= MT: lanes j >= MT hold no column and read no row
     // rows of R2 and B1 by transposition through LDS
     double r2r[MT], b1r[MT];
 #pragma unroll
-    for (int i = 0; i < MT; ++i) Tc[i * LDT + j] = (act && i < M && i <= j) ? r2c[i] : 0.0;
+    for (int i = 0; i < MT; ++i)
+        if (j < MT) Tc[i * LDT + j] = (act && i < M && i <= j) ? r2c[i] : 0.0;
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int k = 0; k < MT; ++k) r2r[k] = Tc[j * LDT + k];
+    for (int k = 0; k < MT; ++k) r2r[k] = Tc[(j < MT ? j : 0) * LDT + k];
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int i = 0; i < MT; ++i) Tc[i * LDT + j] = (act && i < M) ? b1c[i] : 0.0;
+    for (int i = 0; i < MT; ++i)
+        if (j < MT) Tc[i * LDT + j] = (act && i < M) ? b1c[i] : 0.0;
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int k = 0; k < MT; ++k) b1r[k] = act ? Tc[j * LDT + k] : 0.0;   // rows MT.. of the tile were never written
+    for (int k = 0; k < MT; ++k) b1r[k] = act ? Tc[j * LDT + k] : 0.0;
     __builtin_amdgcn_wave_barrier();
     // R_V's column and row are read from the group's LDS copy inside the sweeps (they are the same for the wave's
     // four classes); Rv is zero below its diagonal and outside M x M.
@@ -614,19 +618,20 @@ __device__ __forceinline__ bool singular_vector_rows(const double (&r2c)[MT], co
 // R2 the triangular factor of B2 = U diag(y_c) V ((n-M) x M; n - M >= M by eq. (3)).  B1 and B2 come from the
 // float64 matrix cores exactly as the projected system of Algorithm 2 does (Q1 sits in the 16 rows that follow U in
 // LDS), R2 from the same register Householder QR, run over all M columns.  The smallest right singular vector of
-// the assembled factor is then found as in the LDS kernel (homogeneous_q), 64 / 2M classes at a time in this wave's
-// scratch: per class  mat[2M][2M+1] | coef[M] | key[n].
+// the assembled factor is found in registers (singular_vector_rows); a class that does not settle there is assembled
+// in this wave's scratch, mat[2M][2M+1] | coef[M] | key[n], and goes through the LDS form (homogeneous_q), as many
+// classes at a time as the scratch holds (one, as the host sizes it).
 template <int NB, int RM>
 __device__ __forceinline__ void locate_classes_hom_proj(const float *Ysh, int CW, int c_rel, int tile_classes,
                                                         const int *avail, const double *xs, const double *Pw,
                                                         const double *Ush, const double *Rv, int n, int M, int A,
-                                                        double *scratch, int *votes) {
+                                                        double *scratch, int scratch_doubles, int *votes) {
     typedef double v4d __attribute__((ext_vector_type(4)));
     const int lane = lane_id();
     const int j = lane % kClsLanes;
     const int e = j < M ? j : 0;                          // column of this lane: y x^j; idle lanes hold zeros
     const double sgn = j < M ? 1.0 : 0.0;
-    constexpr int MT = NB / 2 < kProjMaxM ? NB / 2 : kProjMaxM;   // eq. (3): M <= n / 2 <= NB / 2
+    constexpr int MT = hom_mt(NB);
     constexpr int kKSteps = NB / 4;
     constexpr int kUBlocks = ush_rows(RM) / 4;
     constexpr int kBlocks = kUBlocks + (MT + 3) / 4;      // then the rows of Q1 (16 of them in LDS, the first MT used)
@@ -721,7 +726,8 @@ __device__ __forceinline__ void locate_classes_hom_proj(const float *Ysh, int CW
     const int W2 = 2 * M;
     const int LD = W2 + 1;
     const int per_class = W2 * LD + M + n;
-    const int cpw = kWave / W2;                           // >= 2: M <= 15
+    const int fit = scratch_doubles / per_class;          // >= 1 (hom_scratch_doubles)
+    const int cpw = kWave / W2 < fit ? kWave / W2 : fit;  // classes per pass: what the lanes and the scratch hold
     const int clw = lane / W2, jw = lane - clw * W2;      // the layout of homogeneous_q (lane jw owns row jw)
     __builtin_amdgcn_wave_barrier();                      // the transposition scratch is free again
     for (int p0 = 0; p0 < kClsPerWave; p0 += cpw) {
@@ -758,11 +764,13 @@ __device__ __forceinline__ void locate_classes_hom_proj(const float *Ysh, int CW
     }
 }
 
-// Per-wave LDS scratch of Algorithm 1's locator: the transposition tiles of singular_vector_rows (4 classes x 16 x 17)
-// or, for classes that fall back to homogeneous_q, 64 / 2M factors with their coefficient and key arrays.
-__host__ __device__ constexpr int hom_scratch_doubles(int M, int n_cap) {
-    const int fallback = (kWave / (2 * M)) * (2 * M * (2 * M + 1) + M + n_cap);
-    const int transpose = kClsPerWave * kProjMaxM * (kProjMaxM + 1);
+// Per-wave LDS scratch of Algorithm 1's locator: the transposition tiles of singular_vector_rows (4 classes x MT x
+// (MT + 1)) or, for a class that falls back to homogeneous_q, ONE assembled factor with its coefficient and key
+// arrays.  Kept this small on purpose: LDS, not registers, decides how many groups a CU holds (at K = 8, A = 2 with
+// three factors per wave seven workgroups fitted a CU where eight were due, and the launch took two rounds).
+__host__ __device__ constexpr int hom_scratch_doubles(int M, int n_cap, int MT) {
+    const int fallback = 2 * M * (2 * M + 1) + M + n_cap;
+    const int transpose = kClsPerWave * MT * (MT + 1);
     return fallback > transpose ? fallback : transpose;
 }
 
@@ -775,7 +783,7 @@ constexpr int basis_doubles() {
 
 // HOMOG: Algorithm 1's fit as the per-class locator (locate_classes_hom_proj) instead of Algorithm 2's.
 // dynamic LDS (doubles): basis (see basis_doubles) | Pw[NB*16] | xs[NB] | WdT[(n_cap-A)*KP] | alpha_s[K] | beta_s[N]
-//               | HOMOG: scratch[nw][(64 / 2M) * (2M (2M+1) + M + n_cap)]
+//               | HOMOG: scratch[nw][hom_scratch_doubles(M, n_cap, NB / 2)]
 //               then float Ysh[NB*CW], then ints: avail[N] | F[N] | Fpos[N] | votes[N] | n | flag
 template <int NB, int RM, bool HOMOG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(!HOMOG && RM <= 16 && NB <= 28 ? 3 : 2))) void decode_byzantine_proj_kernel(
@@ -797,7 +805,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(!HOMOG && R
     double *WdT = xs + NB;
     double *alpha_s = WdT + (n_cap - A) * KP;
     double *beta_s = alpha_s + K;
-    const int hom_wave_doubles = HOMOG ? hom_scratch_doubles(M, n_cap) : 0;
+    const int hom_wave_doubles = HOMOG ? hom_scratch_doubles(M, n_cap, hom_mt(NB)) : 0;
     double *hom_scratch = beta_s + N;
     float *Ysh = reinterpret_cast<float *>(hom_scratch + static_cast<size_t>(nw) * hom_wave_doubles);
     int *avail = reinterpret_cast<int *>(Ysh + NB * CW);
@@ -878,7 +886,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(!HOMOG && R
         for (int c_rel = wv * kClsPerWave; c_rel < tile_classes; c_rel += nw * kClsPerWave) {
             if (HOMOG)
                 locate_classes_hom_proj<NB, RM>(Ysh, CW, c_rel, tile_classes, avail, xs, Pw, Ush, Rv, n, M, A,
-                                                hom_scratch + static_cast<size_t>(wv) * hom_wave_doubles, votes);
+                                                hom_scratch + static_cast<size_t>(wv) * hom_wave_doubles, hom_wave_doubles,
+                                                votes);
             else
                 locate_classes_proj<NB, RM>(Ysh, CW, c_rel, c_rel + lane_id() / kClsLanes < tile_classes, avail, xs, Pw,
                                             Ush, n, M, A, votes);
@@ -1513,7 +1522,7 @@ int run_proj(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t 
     // Algorithm 1's locator runs two waves to a SIMD (registers): half as many waves fill the chip
     ProjShape p = proj_shape(G, C, ws.votes != nullptr, HOMOG ? kFillWaves / 2 : kFillWaves);
     const int CW = 1 << p.cw_log2;
-    const size_t hom_wave = HOMOG ? sizeof(double) * hom_scratch_doubles(M, n_cap) : 0;
+    const size_t hom_wave = HOMOG ? sizeof(double) * hom_scratch_doubles(M, n_cap, hom_mt(NB)) : 0;
     const size_t fixed = sizeof(double) * (static_cast<size_t>(basis_doubles<NB, RM, HOMOG>()) + NB * kPwStride + NB +
                                            static_cast<size_t>(n_cap - A) * KP + K + N) +
                          sizeof(float) * (static_cast<size_t>(NB) * CW) + sizeof(int) * (4 * static_cast<size_t>(N) + 2);

@@ -2,6 +2,7 @@
 
     python3 -m paper_2109_09868_amd.run_workload --workload text_k32 --op encode --reps 5
     rocprofv3 --kernel-trace --stats -- python3 -m paper_2109_09868_amd.run_workload --workload byzantine --op decode_byzantine
+    python3 -m paper_2109_09868_amd.run_workload --shape 2048,16,24,6,0,4096,4096 --op decode      # G,K,N,S,A,D,C
 
 Inputs are drawn on the device with torch (values do not matter to a profile; shapes, masks and
 launch configuration are those of the named workload).
@@ -21,7 +22,10 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="imagenet", choices=sorted(syn.WORKLOADS))
     ap.add_argument("--op", default="encode", choices=["encode", "decode", "decode_top1", "decode_byzantine",
-                                                         "decode_byzantine_homogeneous"])
+                                                         "decode_byzantine_homogeneous", "decode_rational"])
+    ap.add_argument("--shape", default=None,
+                    help="G,K,N,S,A,D,C: these sizes instead of the named workload's (its seeds and mask recipe stay)")
+    ap.add_argument("--no-workspace", action="store_true", help="Byzantine ops: pass no workspace")
     ap.add_argument("--linear-model", action="store_true",
                     help="Byzantine ops: predictions = a linear map of the coded queries plus noise on A workers "
                          "(exactly rational data, the case the locators are built for) instead of plain noise")
@@ -30,6 +34,9 @@ def main():
     args = ap.parse_args()
 
     w = syn.WORKLOADS[args.workload]
+    if args.shape:
+        G, K, N, S, A, D, C = (int(x) for x in args.shape.split(","))
+        w = syn.scaled(w, name="%s[%s]" % (w.name, args.shape), G=G, K=K, W=N, S=S, A=A, query_shape=(D,), C=C)
     dev = torch.device("cuda:0")
     alpha, beta = binding.approxifer_chebyshev_nodes(w.K, w.W)
     gen = torch.Generator(device=dev).manual_seed(syn.BASE_SEED + w.index)
@@ -60,13 +67,19 @@ def main():
                 noise = 10 * preds.std() * torch.randn((w.G, w.A, w.C), dtype=torch.float32, device=dev, generator=gen)
                 preds = preds.scatter_add(1, bad[:, :, None].expand(-1, -1, w.C), noise).contiguous()
             adv = torch.empty((w.G, w.A), dtype=torch.int32, device=dev)
-            entry = (binding.approxifer_decode_byzantine if args.op == "decode_byzantine"
-                     else binding.approxifer_decode_byzantine_homogeneous)
-            fn = lambda: entry(preds, mask, alpha, beta, w.S, w.A, args.sign_mode, out=out, adv=adv, status=st)
+            if args.op == "decode_rational":
+                fn = lambda: binding.approxifer_decode_rational(preds, mask, alpha, beta, w.S, w.A, out=out, status=st)
+            else:
+                need = 0 if args.no_workspace else binding.approxifer_workspace_bytes(w.G, w.K, w.W, w.S, w.A, w.C)
+                ws = torch.empty((need,), dtype=torch.uint8, device=dev) if need else binding.NO_WORKSPACE
+                entry = (binding.approxifer_decode_byzantine if args.op == "decode_byzantine"
+                         else binding.approxifer_decode_byzantine_homogeneous)
+                fn = lambda: entry(preds, mask, alpha, beta, w.S, w.A, args.sign_mode, out=out, adv=adv, status=st,
+                                   workspace=ws)
     for _ in range(args.reps):
         fn()
     torch.cuda.synchronize()
-    print("%s %s x%d done" % (args.workload, args.op, args.reps))
+    print("%s %s x%d done" % (w.name, args.op, args.reps))
 
 
 if __name__ == "__main__":
