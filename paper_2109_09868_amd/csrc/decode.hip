@@ -631,21 +631,24 @@ __global__ __launch_bounds__(kWaitGroups *kWave) void wait_mask_kernel(const flo
 // ------------------------------------------------------------------------------------
 // top-1 of an already decoded tensor
 // ------------------------------------------------------------------------------------
-// One wave per row of [rows][C] float32: largest value, smallest class on equal values (NaN never wins; a row of
-// NaNs gives class 0).  Four rows per workgroup.
-constexpr int kArgmaxRows = 4;
+// LPR lanes per row of [rows][C] float32 (a wave for long rows, sixteen lanes for rows of up to 32 classes, so that a
+// wave takes four rows of a ten-class output instead of idling 54 lanes on one): largest value, smallest class on
+// equal values (NaN never wins; a row of NaNs gives class 0).  Four waves per workgroup.
+constexpr int kArgmaxWaves = 4;
 
-__global__ __launch_bounds__(kArgmaxRows *kWave) void argmax_rows_kernel(const float *__restrict__ values,
-                                                                          int32_t *__restrict__ top1,
-                                                                          float *__restrict__ score, int64_t rows,
-                                                                          int64_t C) {
-    const int64_t row = static_cast<int64_t>(blockIdx.x) * kArgmaxRows + wave_id();
-    if (row >= rows) return;
+template <int LPR>
+__global__ __launch_bounds__(kArgmaxWaves *kWave) void argmax_rows_kernel(const float *__restrict__ values,
+                                                                           int32_t *__restrict__ top1,
+                                                                           float *__restrict__ score, int64_t rows,
+                                                                           int64_t C) {
+    constexpr int kRowsPerWave = kWave / LPR;
     const int lane = lane_id();
-    const float *v = values + row * C;
+    const int64_t row = (static_cast<int64_t>(blockIdx.x) * kArgmaxWaves + wave_id()) * kRowsPerWave + lane / LPR;
+    const bool live = row < rows;
+    const float *v = values + (live ? row : 0) * C;
     float bv = -__builtin_inff();
     int bi = 0x7fffffff;
-    for (int64_t c = lane; c < C; c += kWave) {
+    for (int64_t c = lane % LPR; c < C; c += LPR) {
         const float x = v[c];
         if (x > bv) {                                       // ascending c: the first occurrence stays
             bv = x;
@@ -653,7 +656,7 @@ __global__ __launch_bounds__(kArgmaxRows *kWave) void argmax_rows_kernel(const f
         }
     }
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
+    for (int off = LPR / 2; off >= 1; off >>= 1) {
         const float ov = __shfl_xor(bv, off, kWave);
         const int oi = __shfl_xor(bi, off, kWave);
         if (ov > bv || (ov == bv && oi < bi)) {
@@ -661,7 +664,7 @@ __global__ __launch_bounds__(kArgmaxRows *kWave) void argmax_rows_kernel(const f
             bi = oi;
         }
     }
-    if (lane == 0) {
+    if (live && lane % LPR == 0) {
         const bool none = bi == 0x7fffffff;                 // every value NaN or -inf
         top1[row] = none ? 0 : bi;
         if (score != nullptr) score[row] = none ? v[0] : bv;
@@ -802,10 +805,13 @@ int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_t
 
 int launch_argmax_rows(const float *d_values, int32_t *d_top1, float *d_score, int64_t rows, int64_t C,
                        hipStream_t stream) {
-    const int64_t blocks = (rows + kArgmaxRows - 1) / kArgmaxRows;
+    const bool narrow = C <= 32;
+    const int64_t per_block = kArgmaxWaves * (narrow ? kWave / 16 : 1);
+    const int64_t blocks = (rows + per_block - 1) / per_block;
     if (blocks > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
-    return launch_status(launch_kernel(argmax_rows_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kArgmaxRows * kWave), 0,
-                                       stream, d_values, d_top1, d_score, rows, C));
+    const dim3 grid(static_cast<unsigned>(blocks)), block(kArgmaxWaves * kWave);
+    if (narrow) return launch_status(launch_kernel(argmax_rows_kernel<16>, grid, block, 0, stream, d_values, d_top1, d_score, rows, C));
+    return launch_status(launch_kernel(argmax_rows_kernel<kWave>, grid, block, 0, stream, d_values, d_top1, d_score, rows, C));
 }
 
 int launch_wait_mask(const float *d_arrival, uint8_t *d_mask, int32_t *d_count, int64_t G, int N, int wait_for,
