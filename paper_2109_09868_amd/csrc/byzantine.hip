@@ -57,13 +57,14 @@ __device__ __forceinline__ void contract_group(const float *__restrict__ pg, flo
 }
 
 // The A most voted workers (equal counts: smaller index first) go to adv_g in ascending order; F = the
-// available workers without them (ascending), Fpos = their positions in `avail`.  Called by the whole
-// workgroup after every vote has been added and a barrier; ends with a barrier.  n <= 64, N <= 128.
+// available workers without them (ascending), Fpos = their positions in `avail`.  n <= 64, N <= 128.
 // One wave does it in registers: lane i ranks workers i and i + 64 by counting against the vote counts
 // (broadcast reads of LDS), ballots turn ranks into the ascending lists.
-__device__ __forceinline__ void select_adversaries(int32_t *__restrict__ adv_g, const int *avail, int n, int N, int A,
-                                                   const int *votes, int *F, int *Fpos) {
-    if (wave_id() == 0) {
+// select_adversaries_wave: called by one whole wave after every vote has been added and a barrier; the lists are
+// visible after the next barrier.
+__device__ __forceinline__ void select_adversaries_wave(int32_t *__restrict__ adv_g, const int *avail, int n, int N,
+                                                        int A, const int *votes, int *F, int *Fpos) {
+    {
         const int lane = lane_id();
         const int mine0 = lane < N ? votes[lane] : -1;
         const int mine1 = lane + kWave < N ? votes[lane + kWave] : -1;
@@ -90,6 +91,12 @@ __device__ __forceinline__ void select_adversaries(int32_t *__restrict__ adv_g, 
             Fpos[pos] = lane;
         }
     }
+}
+
+// Called by the whole workgroup after every vote has been added and a barrier; ends with a barrier.
+__device__ __forceinline__ void select_adversaries(int32_t *__restrict__ adv_g, const int *avail, int n, int N, int A,
+                                                   const int *votes, int *F, int *Fpos) {
+    if (wave_id() == 0) select_adversaries_wave(adv_g, avail, n, N, A, votes, F, Fpos);
     __syncthreads();
 }
 
@@ -361,12 +368,13 @@ __device__ __forceinline__ void row_min_step(double &v, int &i) {
     i = take ? oi : i;
 }
 
-// Algorithm 2, steps 1-5, for the four classes c_rel..c_rel+3 of the staged class tile, by one wave.
-//   Ysh[NB][CW] float: predictions of the available workers, row r = r-th available worker, zero past n and
-//   past the last class;  Ush[ush_rows(RM)][ush_stride(NB)] (zero past row n-M and column n), Pw[NB][16] (rows past n
-//   zero), xs[n]: the group's LDS.
+// Algorithm 2, steps 1-5, for four classes at a time, by one wave.
+//   ycol (per lane): the staged predictions of class slot (lane % 16) & 3 of this round, ycol[r * CW] = prediction of
+//   the r-th available worker for that class, float, zero past n (an empty slot points at zeros);
+//   live, votes (per lane): class slot lane / 16 holds a class, and the vote counters of its group;
+//   Ush[ush_rows(RM)][ush_stride(NB)] (zero past row n-M and column n), Pw[NB][16] (rows past n zero), xs[n]: LDS.
 template <int NB, int RM>
-__device__ __forceinline__ void locate_classes_proj(const float *Ysh, int CW, int c_rel, bool live, const int *avail,
+__device__ __forceinline__ void locate_classes_proj(const float *ycol, int CW, bool live, const int *avail,
                                                     const double *xs, const double *Pw, const double *Ush, int n,
                                                     int M, int A, int *votes) {
     typedef double v4d __attribute__((ext_vector_type(4)));
@@ -391,12 +399,12 @@ __device__ __forceinline__ void locate_classes_proj(const float *Ysh, int CW, in
     static_assert(NB % 4 == 0, "k-steps take four available workers at a time");
     double bop[kKSteps], yop[kKSteps];
     {
-        const int k = lane / kClsLanes, cm = (lane % kClsLanes) & 3;
+        const int k = lane / kClsLanes;
 #pragma unroll
         for (int s = 0; s < kKSteps; ++s) {
             const int r = 4 * s + k;
             bop[s] = sgn * Pw[r * kPwStride + e];
-            yop[s] = static_cast<double>(Ysh[r * CW + c_rel + cm]);
+            yop[s] = static_cast<double>(ycol[r * CW]);
         }
     }
     double a[RM];
@@ -889,8 +897,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(!HOMOG && R
                                                 hom_scratch + static_cast<size_t>(wv) * hom_wave_doubles, hom_wave_doubles,
                                                 votes);
             else
-                locate_classes_proj<NB, RM>(Ysh, CW, c_rel, c_rel + lane_id() / kClsLanes < tile_classes, avail, xs, Pw,
-                                            Ush, n, M, A, votes);
+                locate_classes_proj<NB, RM>(Ysh + c_rel + ((lane_id() % kClsLanes) & 3), CW,
+                                            c_rel + lane_id() / kClsLanes < tile_classes, avail, xs, Pw, Ush, n, M, A, votes);
         }
     }
     __syncthreads();
@@ -917,6 +925,123 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(!HOMOG && R
         contract_group<4>(pg, og, F, nF, K, KP, C, Cv, WdT);
     } else {
         contract_group<1>(pg, og, F, nF, K, KP, C, Cv, WdT);
+    }
+}
+
+// Algorithm 2 for the paper's Byzantine operating points (Section 4.2, "Byzantine-Robustness": no stragglers, ten
+// classes): every group answers in full, so all groups share the factorisation that full_basis_kernel wrote, and
+// nothing ties a wave's four class slots to one group any more.  A workgroup takes GPW consecutive groups and walks
+// their GPW * C classes four at a time: with C = 10 four groups fill ten rounds where each alone needs three (twelve
+// slots for ten classes); nodes, powers and the basis are staged once for all of them.  Per class the arithmetic is
+// that of decode_byzantine_proj_kernel (same functions, same operands in the same order): the outputs are the same bits.
+// Host guarantees: S = 0 (a group whose mask is not full is marked bad and skipped), C <= 16, N <= 48.
+// dynamic LDS (doubles): Ush | Pw[NB*16] | xs[NB] | WdT[GPW][(N-A)*KP] | alpha_s[K] | beta_s[N]
+//               then float Ysh[GPW + 1][NB*16] (the last tile stays zero: empty class slots read it),
+//               then ints: ident[N] | F[GPW][N] | Fpos[GPW][N] | votes[GPW][N] | good[GPW]
+template <int NB, int RM, int GPW>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 && NB <= 28 ? 3 : 2))) void decode_byzantine_shared_basis_kernel(
+    const float *__restrict__ preds, const uint8_t *__restrict__ mask, float *__restrict__ out,
+    int32_t *__restrict__ adv, int32_t *__restrict__ status, int64_t G, int K, int N, int A, int C, int sign_mode,
+    const double *__restrict__ full_basis, const Nodes nodes) {
+    extern __shared__ __align__(16) double lds_d[];
+    constexpr int CW = kClsLanes;                         // staged tile: sixteen class columns per row
+    constexpr int kTile = NB * CW;
+    constexpr int kUshDoubles = basis_doubles<NB, RM, false>();
+    const int KP = round_up4(K);
+    const int M = K + A;
+    const int nF = N - A;
+    const int nw = blockDim.x / kWave;
+    double *Ush = lds_d;
+    double *Pw = Ush + kUshDoubles;
+    double *xs = Pw + NB * kPwStride;
+    double *WdT = xs + NB;
+    double *alpha_s = WdT + GPW * nF * KP;
+    double *beta_s = alpha_s + K;
+    float *Ysh = reinterpret_cast<float *>(beta_s + N);
+    int *ident = reinterpret_cast<int *>(Ysh + (GPW + 1) * kTile);
+    int *F = ident + N;
+    int *Fpos = F + GPW * N;
+    int *votes = Fpos + GPW * N;
+    int *good_sh = votes + GPW * N;
+    const int64_t g0 = static_cast<int64_t>(blockIdx.x) * GPW;
+    const int here = G - g0 < GPW ? static_cast<int>(G - g0) : GPW;   // groups of this workgroup
+    const int tid = threadIdx.x;
+    const int wv = wave_id();
+    const int lane = lane_id();
+
+    stage_nodes(nodes, K, N, alpha_s, beta_s);
+    for (int e = tid; e < GPW * nF * KP; e += blockDim.x) WdT[e] = 0.0;
+    for (int e = tid; e < GPW * N; e += blockDim.x) votes[e] = 0;
+    for (int e = tid; e < N; e += blockDim.x) ident[e] = e;
+    for (int e = tid; e < (GPW + 1) * kTile; e += blockDim.x) Ysh[e] = 0.0f;
+    for (int e = tid; e < kUshDoubles; e += blockDim.x) Ush[e] = full_basis[e];
+    for (int q = wv; q < GPW; q += nw) {                  // N <= 48: one ballot counts a mask row
+        bool ok = q < here;
+        if (ok) {
+            const bool b = lane < N && mask[(g0 + q) * N + lane] != 0;
+            ok = __popcll(__ballot(b)) == N;
+            if (lane == 0 && status != nullptr) status[g0 + q] = ok ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
+        }
+        if (lane == 0) good_sh[q] = ok ? 1 : 0;
+    }
+    __syncthreads();
+    for (int r = tid; r < NB; r += blockDim.x) {
+        const double x = r < N ? beta_s[r] : 0.0;
+        if (r < N) xs[r] = x;
+        double pw = r < N ? 1.0 : 0.0;
+        for (int e = 0; e < kPwStride; ++e) {
+            Pw[r * kPwStride + e] = pw;
+            pw *= x;
+        }
+    }
+    // the predictions of the workgroup's groups are one contiguous run of here * N * C floats
+    {
+        const float *pg = preds + static_cast<size_t>(g0) * N * C;
+        const int per_group = N * C;
+        for (int idx = tid; idx < here * per_group; idx += blockDim.x) {
+            const int q = idx / per_group, rem = idx - q * per_group;
+            const int r = rem / C, c = rem - r * C;
+            if (good_sh[q] != 0) Ysh[q * kTile + r * CW + c] = pg[idx];
+        }
+    }
+    __syncthreads();
+
+    const int total = GPW * C;
+    for (int c0 = wv * kClsPerWave; c0 < total; c0 += nw * kClsPerWave) {
+        const int s_op = c0 + ((lane % kClsLanes) & 3);   // the slot whose predictions this lane feeds to the matrix cores
+        const int q_op = s_op / C, c_op = s_op - q_op * C;
+        const bool op_ok = s_op < total && good_sh[s_op < total ? q_op : 0] != 0;
+        const int s_res = c0 + lane / kClsLanes;          // the slot whose system this lane's row then holds
+        const int q_res = s_res < total ? s_res / C : 0;
+        const bool live = s_res < total && good_sh[q_res] != 0;
+        locate_classes_proj<NB, RM>(Ysh + (op_ok ? q_op * kTile + c_op : GPW * kTile), CW, live, ident, xs, Pw, Ush, N, M,
+                                    A, votes + q_res * N);
+    }
+    __syncthreads();
+
+    for (int q = wv; q < here; q += nw)                   // a wave per group
+        if (good_sh[q] != 0)
+            select_adversaries_wave(adv + (g0 + q) * A, ident, N, N, A, votes + q * N, F + q * N, Fpos + q * N);
+    __syncthreads();
+    for (int q = 0; q < here; ++q)
+        if (good_sh[q] != 0) decoder_weights(alpha_s, beta_s, F + q * N, nF, K, KP, sign_mode, WdT + q * nF * KP);
+    __syncthreads();
+    // out[g][j][c] = sum_r WdT[r][j] * Y[F_r][c] straight from the staged tiles
+    {
+        float *og = out + static_cast<size_t>(g0) * K * C;
+        const int per_group = K * C;
+        for (int o = tid; o < here * per_group; o += blockDim.x) {
+            const int q = o / per_group, rem = o - q * per_group;
+            if (good_sh[q] == 0) continue;
+            const int jq = rem / C, c = rem - jq * C;
+            const double *w = WdT + q * nF * KP + jq;
+            const float *y = Ysh + q * kTile + c;
+            const int *fp = Fpos + q * N;
+            double acc = 0.0;
+#pragma unroll 6
+            for (int r = 0; r < nF; ++r) acc = fma(w[r * KP], static_cast<double>(y[fp[r] << 4]), acc);
+            og[o] = static_cast<float>(acc);
+        }
     }
 }
 
@@ -1510,6 +1635,35 @@ Carved carve_workspace(void *d_workspace, size_t bytes, size_t need_basis, size_
 // kNoFit: the shape does not fit this kernel's LDS (Algorithm 1 with many workers): the caller falls back.
 constexpr int kNoFit = 1;
 
+// Whether decode_byzantine_shared_basis_kernel takes the call: the classes of a group leave class slots empty (C is
+// not a multiple of four), a group is staged in one sixteen-class tile, and there are enough groups to fill the chip
+// four to a workgroup (with fewer, a workgroup per group spreads them over more CUs).  Measured at K = 12, A = 2,
+// 28 workers, 10 classes, 8192 groups (kernel time): one group per workgroup 132 us; 2 groups, 2 waves 137; 4 groups,
+// 4 waves 126; 8 groups, 4 waves 125; one wave per workgroup of 2 / 4 groups 159 / 208.
+constexpr int kSharedBasisGroups = 4;
+bool shared_basis_applies(int64_t G, int64_t C) {
+    if (C > kClsLanes || C % kClsPerWave == 0) return false;
+    return G * ((C + kClsPerWave - 1) / kClsPerWave) >= kFillWaves;
+}
+
+template <int NB, int RM, int GPW>
+int run_shared_basis(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv, int32_t *d_status,
+                     int64_t G, int K, int N, int A, int64_t C, const Nodes &nodes, int sign_mode, const double *basis,
+                     hipStream_t stream) {
+    const int KP = (K + 3) & ~3;
+    const int64_t blocks = (G + GPW - 1) / GPW;
+    int nw = static_cast<int>((GPW * C + kClsPerWave - 1) / kClsPerWave);   // a wave per round of four classes, up to four
+    if (nw > 4) nw = 4;
+    const size_t lds = sizeof(double) * (static_cast<size_t>(basis_doubles<NB, RM, false>()) + NB * kPwStride + NB +
+                                         static_cast<size_t>(GPW) * (N - A) * KP + K + N) +
+                       sizeof(float) * (static_cast<size_t>(GPW + 1) * NB * kClsLanes) +
+                       sizeof(int) * (static_cast<size_t>(N) * (1 + 3 * GPW) + GPW);
+    if (lds > 64 * 1024 || blocks > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    return launch_status(launch_kernel(decode_byzantine_shared_basis_kernel<NB, RM, GPW>, dim3(static_cast<unsigned>(blocks)),
+                                       dim3(nw * kWave), lds, stream, d_preds, d_mask, d_out, d_adv, d_status, G, K, N, A,
+                                       static_cast<int>(C), sign_mode, basis, nodes));
+}
+
 template <int NB, int RM, bool HOMOG>
 int run_proj(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_adv, int32_t *d_status, int64_t G,
              int K, int N, int S, int A, int64_t C, int n_cap, bool vec4, const Nodes &nodes, int sign_mode,
@@ -1533,6 +1687,13 @@ int run_proj(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t 
     if (ws.basis != nullptr) {
         const hipError_t e = launch_kernel(full_basis_kernel<NB, RM, HOMOG>, dim3(1), dim3(kWave), 0, stream, ws.basis, N, M, nodes);
         if (e != hipSuccess) return APPROXIFER_ERR_LAUNCH;
+        if constexpr (!HOMOG) {
+            // no stragglers by contract (S = 0): every good group shares this factorisation, and groups whose classes
+            // do not fill whole rounds of four are packed several to a workgroup
+            if (S == 0 && shared_basis_applies(G, C))
+                return run_shared_basis<NB, RM, kSharedBasisGroups>(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, A, C,
+                                                                    nodes, sign_mode, ws.basis, stream);
+        }
     }
     if (p.splits > 1) {
         const int rc = clear_workspace(ws.votes, G, N, stream);

@@ -703,6 +703,52 @@ def test_byzantine_sign_modes_and_bad_masks(gpu, mode):
     assert group_err(out[good], ref[good]).max() <= TOL
 
 
+@pytest.mark.parametrize("K,A,N,C,G", [(12, 2, 28, 10, 257), (8, 2, 24, 10, 5), (4, 1, 12, 1, 7), (2, 1, 9, 3, 10),
+                                       (6, 2, 20, 5, 1), (12, 3, 30, 6, 33), (3, 1, 30, 15, 6), (14, 2, 32, 9, 4), (14, 2, 48, 7, 9),
+                                       # enough groups for four of them to share a workgroup; group counts 4 does not divide
+                                       (12, 2, 28, 10, 1367), (4, 1, 12, 1, 4099), (2, 1, 9, 3, 4101), (5, 2, 16, 6, 2050),
+                                       (3, 1, 30, 15, 1025)])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_byzantine_no_stragglers_groups_share_one_factorisation(gpu, K, A, N, C, G, mode):
+    # Section 4.2, "Byzantine-Robustness": S = 0.  With a workspace the node set is factorised once per call and, when
+    # a group's classes do not fill whole rounds of four, several groups share a workgroup.  Odd group counts, one
+    # class, a group that is not full (bad by the S = 0 contract) in the middle; against the oracle, and bit for
+    # bit against the same call without a workspace (one workgroup and one factorisation per group).
+    torch, binding, dev = gpu
+    rng = np.random.default_rng(1000 * K + 10 * C + G)
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    X = rng.uniform(0, 1, (G, K, 64))
+    Mf = rng.standard_normal((64, C)) / 8
+    Y = (orc.encode(X, alpha, beta) @ Mf).astype(np.float32)
+    mask = np.ones((G, N), np.uint8)
+    adv_true = np.zeros((G, A), np.int32)
+    ok = np.nonzero(np.abs(beta) > 1e-9)[0]
+    for g in range(G):
+        adv_true[g] = np.sort(rng.permutation(ok)[:A])
+        Y[g, adv_true[g]] += (10 * Y.std() * rng.standard_normal((A, C))).astype(np.float32)
+    bad = G // 2 if G >= 3 else -1
+    if bad >= 0:
+        mask[bad, 1] = 0
+    Yd, md = torch.from_numpy(Y).to(dev), torch.from_numpy(mask).to(dev)
+    res = {}
+    for name, ws in (("shared", None), ("alone", binding.NO_WORKSPACE)):
+        out = torch.full((G, K, C), -3.0, dtype=torch.float32, device=dev)
+        adv = torch.full((G, A), -7, dtype=torch.int32, device=dev)
+        out, adv, st = binding.approxifer_decode_byzantine(Yd, md, alpha, beta, 0, A, mode, out=out, adv=adv, workspace=ws)
+        res[name] = (out.cpu().numpy(), adv.cpu().numpy(), st.cpu().numpy())
+    assert binding.approxifer_workspace_bytes(G, K, N, 0, A, C) > 0
+    for a, b in zip(res["shared"], res["alone"]):
+        assert np.array_equal(a, b)
+    out, adv, st = res["shared"]
+    ref, adv_ref, st_ref = orc.decode_byzantine(Y, mask, alpha, beta, 0, A, mode)
+    assert np.array_equal(st, st_ref) and st.sum() == (1 if bad >= 0 else 0)
+    if bad >= 0:
+        assert st[bad] == 1 and np.all(out[bad] == -3.0) and np.all(adv[bad] == -7)
+    good = st == 0
+    assert np.array_equal(adv[good], adv_ref[good]) and np.array_equal(adv[good], adv_true[good])
+    assert group_err(out[good], ref[good]).max() <= TOL
+
+
 def test_byzantine_nonlinear_model_votes(gpu):
     # softmax outputs are not rational in beta: Algorithm 2's fit is a genuine least-squares problem
     # and single classes may disagree.  The GPU must reproduce the oracle's vote wherever the oracle's
