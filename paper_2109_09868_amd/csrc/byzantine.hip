@@ -379,7 +379,6 @@ __device__ __forceinline__ void locate_classes_proj(const float *ycol, int CW, b
                                                     int M, int A, int *votes) {
     typedef double v4d __attribute__((ext_vector_type(4)));
     const int lane = lane_id();
-    const int cl = lane / kClsLanes;
     const int j = lane % kClsLanes;
     const int cols = M - 1;                               // unknowns Q_1 .. Q_{M-1}
 
@@ -979,7 +978,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RM <= 16 &&
         bool ok = q < here;
         if (ok) {
             const bool b = lane < N && mask[(g0 + q) * N + lane] != 0;
-            ok = __popcll(__ballot(b)) == N;
+            ok = static_cast<int>(__popcll(__ballot(b))) == N;
             if (lane == 0 && status != nullptr) status[g0 + q] = ok ? APPROXIFER_GROUP_OK : APPROXIFER_GROUP_BAD_MASK;
         }
         if (lane == 0) good_sh[q] = ok ? 1 : 0;

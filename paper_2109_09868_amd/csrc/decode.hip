@@ -671,7 +671,7 @@ __global__ __launch_bounds__(kArgmaxWaves *kWave) void argmax_rows_kernel(const 
     }
 }
 
-bool packed_shape(int K, int N, int S, int64_t C) {
+bool packed_shape(int K, int N, int64_t C) {
     return K <= 32 && N <= kWave && C <= kPk;             // N <= 64: the survivors fit the largest tile
 }
 
@@ -703,7 +703,7 @@ int run_packed(bool top1_variant, const float *d_preds, const uint8_t *d_mask, f
 
 int launch_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t *d_status, int64_t G, int K,
                   int N, int S, int64_t C, const Nodes &nodes, int sign_mode, hipStream_t stream) {
-    if (packed_shape(K, N, S, C))
+    if (packed_shape(K, N, C))
         return run_packed(false, d_preds, d_mask, d_out, nullptr, nullptr, d_status, G, K, N, S, C, nodes, sign_mode, stream);
     const int KP = (K + 3) & ~3;
     const bool vec4 = (C % 4 == 0) && aligned16(d_preds) && aligned16(d_out);
@@ -747,7 +747,7 @@ int launch_decode(const float *d_preds, const uint8_t *d_mask, float *d_out, int
 int launch_decode_top1(const float *d_preds, const uint8_t *d_mask, int32_t *d_top1, float *d_score,
                        int32_t *d_status, int64_t G, int K, int N, int S, int64_t C, const Nodes &nodes,
                        int sign_mode, hipStream_t stream) {
-    if (packed_shape(K, N, S, C))
+    if (packed_shape(K, N, C))
         return run_packed(true, d_preds, d_mask, nullptr, d_top1, d_score, d_status, G, K, N, S, C, nodes, sign_mode, stream);
     const int KP = (K + 3) & ~3;
     const bool vec4 = (C % 4 == 0) && aligned16(d_preds);
