@@ -188,3 +188,48 @@ def test_wait_mask_validation_codes(lib):
     assert wm(fake, None, None, 1, 4, 2, None) == -1
     assert wm(None, None, None, 0, 4, 2, None) == 0
 
+
+
+C_CLIENT = r"""
+#include <stdio.h>
+#include <math.h>
+#include "approxifer.h"
+int main(void) {
+    double alpha[4], beta[6];
+    int rc = approxifer_chebyshev_nodes(4, 6, alpha, beta);
+    if (rc != APPROXIFER_OK) return 1;
+    if (fabs(beta[0] - 1.0) > 1e-15 || fabs(beta[5] + 1.0) > 1e-15) return 2;   /* cos(0), cos(pi) */
+    if (approxifer_group_count(10, 4) != 3) return 3;
+    if (approxifer_encode(NULL, NULL, 1, 4, 6, 8, alpha, beta, NULL) != APPROXIFER_ERR_NULL_POINTER) return 4;
+    printf("%d %s %zu\n", approxifer_version(), approxifer_strerror(APPROXIFER_ERR_TOO_FEW_WORKERS),
+           approxifer_workspace_bytes(5, 8, 24, 4, 2, 1000));
+    return 0;
+}
+"""
+
+
+def test_header_is_plain_c_and_a_c_program_links_against_the_library(lib, tmp_path):
+    # the boundary is a C ABI: the header must compile as strict C99 and as C++, and a C program that includes it
+    # must link against the shared library and get the host-side answers the binding gets
+    import shutil
+    import subprocess
+    from paper_2109_09868_amd import binding
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "client.c"
+    src.write_text(C_CLIENT)
+    gcc = shutil.which("gcc")
+    gxx = shutil.which("g++")
+    assert gcc and gxx
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(src)],
+                   check=True)
+    subprocess.run([gxx, "-std=c++11", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc,
+                    str(src)], check=True)
+    libdir = os.path.dirname(binding.LIB_PATH)
+    exe = tmp_path / "client"
+    subprocess.run([gcc, "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-lapproxifer", "-lm",
+                    "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(None, 1)
+    assert int(out[0]) == lib.approxifer_version()
+    text, ws = out[1].rsplit(None, 1)
+    assert text == binding.strerror(-5)
+    assert int(ws) == binding.approxifer_workspace_bytes(5, 8, 24, 4, 2, 1000)
