@@ -1290,6 +1290,51 @@ def test_wait_mask_feeds_the_decoder(gpu):
 # --------------------------------------------------------------------------------------
 # HIP graph capture: the calls allocate nothing, keep no state and enqueue kernels only
 # --------------------------------------------------------------------------------------
+def test_calls_on_two_streams_keep_no_state_between_them(gpu):
+    # The library keeps no state between calls: two chains (encode -> Byzantine decode with a workspace of its own,
+    # few groups x many classes so that the workgroups of a group pool their votes there) enqueued alternately on two
+    # streams of the default priority give, bit for bit, what each chain gives alone on the current stream.
+    torch, binding, dev = gpu
+    K, A, N, C, G, D = 8, 2, 24, 1000, 6, 512
+    alpha, beta = orc.chebyshev_nodes(K, N)
+    rng = np.random.default_rng(4242)
+    chains = []
+    for t in range(2):
+        X = torch.from_numpy(rng.uniform(0, 1, (G, K, D)).astype(np.float32)).to(dev)
+        Mf = torch.from_numpy((rng.standard_normal((D, C)) / 20).astype(np.float32)).to(dev)
+        noise = torch.from_numpy((5 * rng.standard_normal((G, A, C))).astype(np.float32)).to(dev)
+        bad = torch.from_numpy(np.stack([np.sort(rng.permutation(np.arange(1, N))[:A]) for _ in range(G)])).to(dev)
+        mask = torch.ones((G, N), dtype=torch.uint8, device=dev)
+        chains.append((X, Mf, noise, bad, mask))
+    need = binding.approxifer_workspace_bytes(G, K, N, 0, A, C)
+    assert need >= 4 * (N + 1) * G
+
+    def run(chain, stream, ws):
+        X, Mf, noise, bad, mask = chain
+        with torch.cuda.stream(stream):
+            coded = binding.approxifer_encode(X, alpha, beta, stream=stream)
+            preds = (coded.reshape(G * N, D) @ Mf).reshape(G, N, C)
+            preds.scatter_add_(1, bad[:, :, None].expand(-1, -1, C), noise)
+            out, adv, st = binding.approxifer_decode_byzantine(preds, mask, alpha, beta, 0, A, 1, workspace=ws, stream=stream)
+        return coded, out, adv, st, bad
+
+    cur = torch.cuda.current_stream()
+    alone = [run(c, cur, torch.zeros((need,), dtype=torch.uint8, device=dev)) for c in chains]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    spaces = [torch.zeros((need,), dtype=torch.uint8, device=dev) for _ in range(2)]
+    both = [None, None]
+    for rep in range(3):
+        for t in range(2):
+            both[t] = run(chains[t], streams[t], spaces[t])
+    torch.cuda.synchronize()
+    for t in range(2):
+        coded, out, adv, st, bad = both[t]
+        assert torch.all(st == 0) and torch.equal(adv.long(), bad)
+        for got, want in zip(both[t][:4], alone[t][:4]):
+            assert torch.equal(got, want)
+
+
 def test_calls_can_be_captured_in_a_hip_graph_and_replayed(gpu):
     torch, binding, dev = gpu
     K, N, S, D, C, G = 8, 12, 4, 3072, 100, 32
