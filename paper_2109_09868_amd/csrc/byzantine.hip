@@ -1657,7 +1657,8 @@ int run_shared_basis(const float *d_preds, const uint8_t *d_mask, float *d_out, 
                                          static_cast<size_t>(GPW) * (N - A) * KP + K + N) +
                        sizeof(float) * (static_cast<size_t>(GPW + 1) * NB * kClsLanes) +
                        sizeof(int) * (static_cast<size_t>(N) * (1 + 3 * GPW) + GPW);
-    if (lds > 64 * 1024 || blocks > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
+    if (lds > 64 * 1024) return kNoFit;                   // the caller goes on with a workgroup per group
+    if (blocks > 0x7fffffffLL) return APPROXIFER_ERR_LIMIT;
     return launch_status(launch_kernel(decode_byzantine_shared_basis_kernel<NB, RM, GPW>, dim3(static_cast<unsigned>(blocks)),
                                        dim3(nw * kWave), lds, stream, d_preds, d_mask, d_out, d_adv, d_status, G, K, N, A,
                                        static_cast<int>(C), sign_mode, basis, nodes));
@@ -1689,9 +1690,11 @@ int run_proj(const float *d_preds, const uint8_t *d_mask, float *d_out, int32_t 
         if constexpr (!HOMOG) {
             // no stragglers by contract (S = 0): every good group shares this factorisation, and groups whose classes
             // do not fill whole rounds of four are packed several to a workgroup
-            if (S == 0 && shared_basis_applies(G, C))
-                return run_shared_basis<NB, RM, kSharedBasisGroups>(d_preds, d_mask, d_out, d_adv, d_status, G, K, N, A, C,
-                                                                    nodes, sign_mode, ws.basis, stream);
+            if (S == 0 && shared_basis_applies(G, C)) {
+                const int rc = run_shared_basis<NB, RM, kSharedBasisGroups>(d_preds, d_mask, d_out, d_adv, d_status, G, K, N,
+                                                                            A, C, nodes, sign_mode, ws.basis, stream);
+                if (rc != kNoFit) return rc;
+            }
         }
     }
     if (p.splits > 1) {
